@@ -1,0 +1,146 @@
+/*
+ * knn.h -- C ABI of the MI355X (gfx950) exact k-nearest-neighbour library.
+ *
+ * The library solves the problem stated in Sect. 3 of Kato & Hosino, "Solving
+ * k-Nearest Neighbor Problem on Multiple Graphics Processors": for every query
+ * vector, the k reference vectors at the smallest distance, listed in
+ * non-decreasing order of distance, every reference left out being at least as
+ * far as the k-th one listed.  It does so by brute force, as the paper does
+ * (Sect. 4-6): a tiled all-pairs distance computation fused with a per-row
+ * selection of the k smallest, so that no distance matrix is ever stored.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     allocates and frees nothing and keeps no pointer after it returns.
+ *   - Matrices are row-major, contiguous, fp32; row stride == d.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without waiting; results are
+ *     valid once the caller has synchronised the stream.  (Exception: a call
+ *     given a profile record waits for its own work, see knn_options_t.)
+ *   - Errors are return codes; nothing aborts or throws.  On any error other
+ *     than KNN_EDEVICE nothing has been enqueued.
+ *   - Indices are 0-based reference row numbers (the paper counts from 1).
+ *   - Ties in distance go to the lower reference index (the paper allows any
+ *     resolution).  A query is never its own neighbour when it is declared to
+ *     be a member of the reference set (Sect. 4: only pairs x > y are computed);
+ *     exclusion is by row number, so another row with equal coordinates is an
+ *     ordinary neighbour at distance 0.
+ *   - NaN or infinite input values: behaviour undefined.
+ */
+#ifndef KNN_H_
+#define KNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KNN_SQEUCLIDEAN = 0, /* sum_c (u_c - v_c)^2 */
+    KNN_COSINE = 1       /* 1 - u.v / (|u| |v|); 1 if either vector is all zero */
+} knn_metric_t;
+
+typedef enum {
+    KNN_OK = 0,
+    KNN_EINVAL = 1,       /* null pointer, size out of range, k too large for the set */
+    KNN_EUNSUPPORTED = 2, /* k above KNN_MAX_K, or nr >= 2^31 */
+    KNN_ENOMEM = 3,       /* workspace smaller than knn_workspace_bytes() says */
+    KNN_EDEVICE = 4       /* a HIP call failed (no gfx950 device, launch error) */
+} knn_status_t;
+
+#define KNN_MAX_K 128
+
+/* Time spent by one call, filled in when knn_options_t.profile points here. */
+typedef struct {
+    float ms_prepare;   /* row norms / scaled copies            (Sect. 5 prologue) */
+    float ms_main;      /* fused distance + selection kernel(s) (Sect. 5 and 6)    */
+    float ms_finalize;  /* merge of partial lists, re-score, final order            */
+    float ms_total;
+    int32_t main_launches; /* kernel launches counted in ms_main */
+    int32_t symmetric;     /* 1 if the triangle-of-tiles schedule was used */
+    int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
+                              padding of ragged tiles included */
+} knn_profile_t;
+
+/* Optional knobs; pass NULL for defaults.  Zero-initialise, then set fields. */
+typedef struct {
+    int32_t symmetric;  /* knn_build only.  0 = auto, 1 = force the triangle schedule
+                           (each unordered tile pair computed once, Sect. 3-4),
+                           2 = force the full square */
+    int32_t rescore;    /* 0 = auto (on), 1 = on, 2 = off.
+                           On: the k reported distances of each query are recomputed
+                           from the original rows with double accumulation (a direct
+                           sum of squared differences, or 1 - cos from the three sums)
+                           so they do not carry the cancellation error of
+                           |u|^2+|v|^2-2u.v or of 1-cos in fp32.  Selection itself is
+                           always done on the fp32 matrix-core values */
+    int32_t r_splits;   /* 0 = auto.  Number of slices the reference range is cut
+                           into per query tile (partial lists are merged at the end) */
+    int32_t reserved;
+    knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
+                           kernels with events, waits for them and fills this in */
+} knn_options_t;
+
+/*
+ * All-pairs self kNN (Sect. 3): neighbours of every row of X among the other
+ * rows of X.
+ *   X    [n, d]  device, read only
+ *   idx  [n, k]  device, int32, out
+ *   dist [n, k]  device, fp32, out, ascending per row
+ * Requires 2 <= n < 2^31, 1 <= d, 1 <= k <= min(n-1, KNN_MAX_K).
+ */
+knn_status_t knn_build(const float *X, int64_t n, int32_t d, int32_t k, knn_metric_t metric,
+                       int32_t *idx, float *dist,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+knn_status_t knn_build_ex(const float *X, int64_t n, int32_t d, int32_t k, knn_metric_t metric,
+                          int32_t *idx, float *dist,
+                          void *workspace, size_t workspace_bytes, void *stream,
+                          const knn_options_t *opt);
+
+/*
+ * Query / reference form, the two-set shape of the paper's distance procedure
+ * (Sect. 5, CalcDistances(d, n1, {v1}, n2, {v2})) and the unit of blocking:
+ * neighbours of every row of Q among the rows of R.
+ *   Q [nq, d], R [nr, d]  device, read only (may alias)
+ *   self_offset >= 0: query i IS reference row self_offset + i and that pair is
+ *                     skipped (requires self_offset + nq <= nr); -1: no such relation.
+ *   idx [nq, k], dist [nq, k]  device, out
+ * Requires 1 <= nq, 1 <= nr < 2^31, 1 <= k <= min(nr - (self_offset >= 0), KNN_MAX_K).
+ */
+knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                        int32_t k, knn_metric_t metric, int64_t self_offset,
+                        int32_t *idx, float *dist,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                           int32_t k, knn_metric_t metric, int64_t self_offset,
+                           int32_t *idx, float *dist,
+                           void *workspace, size_t workspace_bytes, void *stream,
+                           const knn_options_t *opt);
+
+/*
+ * Bytes of device workspace a call with these sizes and default options needs;
+ * 0 if the sizes are invalid.  `symmetric` != 0 asks
+ * for knn_build (nq is ignored, nr = n), 0 for knn_search.  The workspace must be
+ * 256-byte aligned; its contents need not be initialised and are garbage after.
+ */
+size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                           int32_t symmetric);
+
+/* Same, for a given option block (a forced r_splits changes the partial-list area). */
+size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                              int32_t symmetric, const knn_options_t *opt);
+
+/* Static, human-readable name of a status code. */
+const char *knn_status_string(knn_status_t status);
+
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char *knn_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNN_H_ */

@@ -1,0 +1,179 @@
+"""Thin Python binding over the C ABI of libknn.so (see include/knn.h).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels of the library.  torch is used for device memory and streams.  There is
+no CPU fallback: if the library is missing or the device call fails, the call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libknn.so")
+
+KNN_SQEUCLIDEAN = 0
+KNN_COSINE = 1
+KNN_OK, KNN_EINVAL, KNN_EUNSUPPORTED, KNN_ENOMEM, KNN_EDEVICE = range(5)
+KNN_MAX_K = 128
+METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE}
+
+EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
+           "knn_workspace_bytes_ex", "knn_status_string", "knn_last_device_error"]
+
+
+class KnnProfile(ctypes.Structure):
+    _fields_ = [("ms_prepare", ctypes.c_float), ("ms_main", ctypes.c_float),
+                ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
+                ("main_launches", ctypes.c_int32), ("symmetric", ctypes.c_int32),
+                ("pairs_computed", ctypes.c_int64)]
+
+
+class KnnOptions(ctypes.Structure):
+    _fields_ = [("symmetric", ctypes.c_int32), ("rescore", ctypes.c_int32),
+                ("r_splits", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("profile", ctypes.POINTER(KnnProfile))]
+
+
+class KnnError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(text)
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen libknn.so and declare its entry points; raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_0906_0231_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    optp = ctypes.POINTER(KnnOptions)
+    lib.knn_build.restype = i32
+    lib.knn_build.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.knn_build_ex.restype = i32
+    lib.knn_build_ex.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, sz, vp, optp]
+    lib.knn_search.restype = i32
+    lib.knn_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, i64, vp, vp, vp, sz, vp]
+    lib.knn_search_ex.restype = i32
+    lib.knn_search_ex.argtypes = [vp, i64, vp, i64, i32, i32, i32, i64, vp, vp, vp, sz, vp, optp]
+    lib.knn_workspace_bytes.restype = sz
+    lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
+    lib.knn_workspace_bytes_ex.restype = sz
+    lib.knn_workspace_bytes_ex.argtypes = [i64, i64, i32, i32, i32, i32, optp]
+    lib.knn_status_string.restype = ctypes.c_char_p
+    lib.knn_status_string.argtypes = [i32]
+    lib.knn_last_device_error.restype = ctypes.c_char_p
+    lib.knn_last_device_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != KNN_OK:
+        lib = load_library()
+        text = lib.knn_status_string(status).decode()
+        if status == KNN_EDEVICE:
+            text += " (" + lib.knn_last_device_error().decode() + ")"
+        raise KnnError(status, text)
+
+
+def _metric(metric) -> int:
+    return METRICS[metric] if isinstance(metric, str) else int(metric)
+
+
+def _options(symmetric: int, rescore: int, r_splits: int, profile: bool):
+    opt = KnnOptions()
+    opt.symmetric, opt.rescore, opt.r_splits = symmetric, rescore, r_splits
+    prof = KnnProfile() if profile else None
+    if prof is not None:
+        opt.profile = ctypes.pointer(prof)
+    return opt, prof
+
+
+def _dev_matrix(x: torch.Tensor, name: str) -> torch.Tensor:
+    if not isinstance(x, torch.Tensor) or x.dim() != 2:
+        raise TypeError(f"{name} must be a 2-D torch tensor")
+    if not x.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (no CPU path exists)")
+    if x.dtype != torch.float32 or not x.is_contiguous():
+        raise ValueError(f"{name} must be contiguous fp32")
+    return x
+
+
+def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
+                        symmetric: bool = False, r_splits: int = 0) -> int:
+    lib = load_library()
+    opt, _ = _options(0, 0, r_splits, False)
+    return int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), int(symmetric),
+                                          ctypes.byref(opt)))
+
+
+@dataclass
+class KnnResult:
+    idx: torch.Tensor                 # [nq, k] int32
+    dist: torch.Tensor                # [nq, k] fp32, ascending
+    profile: Optional[KnnProfile] = None
+
+
+def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int = 0,
+              rescore: int = 0, r_splits: int = 0, profile: bool = False,
+              workspace: Optional[torch.Tensor] = None,
+              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
+    """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h."""
+    lib = load_library()
+    X = _dev_matrix(X, "X")
+    n, d = X.shape
+    with torch.cuda.device(X.device):
+        idx, dist = out if out is not None else (
+            torch.empty((n, k), dtype=torch.int32, device=X.device),
+            torch.empty((n, k), dtype=torch.float32, device=X.device))
+        opt, prof = _options(symmetric, rescore, r_splits, profile)
+        if workspace is None:
+            nbytes = int(lib.knn_workspace_bytes_ex(n, n, d, k, _metric(metric), 1, ctypes.byref(opt)))
+            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+        _check(lib.knn_build_ex(X.data_ptr(), n, d, k, _metric(metric), idx.data_ptr(),
+                                dist.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                stream, ctypes.byref(opt)))
+    return KnnResult(idx, dist, prof)
+
+
+def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
+               self_offset: int = -1, *, rescore: int = 0, r_splits: int = 0,
+               profile: bool = False, workspace: Optional[torch.Tensor] = None,
+               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
+    """Neighbours of every row of Q among the rows of R; see knn_search in knn.h."""
+    lib = load_library()
+    Q = _dev_matrix(Q, "Q")
+    R = _dev_matrix(R, "R")
+    if Q.shape[1] != R.shape[1] or Q.device != R.device:
+        raise ValueError("Q and R must share dimension and device")
+    nq, d = Q.shape
+    nr = R.shape[0]
+    with torch.cuda.device(Q.device):
+        idx, dist = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int32, device=Q.device),
+            torch.empty((nq, k), dtype=torch.float32, device=Q.device))
+        opt, prof = _options(0, rescore, r_splits, profile)
+        if workspace is None:
+            nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), 0, ctypes.byref(opt)))
+            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=Q.device)
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+        _check(lib.knn_search_ex(Q.data_ptr(), nq, R.data_ptr(), nr, d, k, _metric(metric),
+                                 self_offset, idx.data_ptr(), dist.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), stream,
+                                 ctypes.byref(opt)))
+    return KnnResult(idx, dist, prof)

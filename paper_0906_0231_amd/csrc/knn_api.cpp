@@ -1,0 +1,302 @@
+// Host side of the C ABI declared in include/knn.h: argument checks, workspace
+// layout, launch sequence.  No computation happens here.
+#include "knn.h"
+
+#include <hip/hip_runtime_api.h>
+#include <string.h>
+
+#include "knn_device.h"
+
+namespace {
+
+using namespace knn;
+
+thread_local char g_last_error[256] = "";
+
+void set_error(const char *where, hipError_t e)
+{
+    const char *s = hipGetErrorString(e);
+    size_t n = 0;
+    for (; where[n] && n < 100; ++n) g_last_error[n] = where[n];
+    g_last_error[n++] = ':';
+    g_last_error[n++] = ' ';
+    for (size_t i = 0; s && s[i] && n < sizeof(g_last_error) - 1; ++i) g_last_error[n++] = s[i];
+    g_last_error[n] = 0;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+    int32_t dpad, kcap, S, n_qtiles, n_rtiles, rt_per_split;
+    int64_t nq_pad, n_cpad;
+    bool self;      // knn_build: one matrix serves as queries and references
+    bool rcopy;     // references need a scaled / padded copy
+    size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
+};
+
+int32_t list_capacity(int32_t k)
+{
+    int32_t c = 16;
+    while (c < k) c <<= 1;
+    return c;
+}
+
+// Sizes are assumed validated.  r_splits == 0 picks a split count that gives
+// the 256 compute units at least two workgroups each when query tiles are few.
+bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
+               int32_t r_splits, Plan &p)
+{
+    p.self = self;
+    p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
+    p.kcap = list_capacity(k);
+    p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
+    p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
+    p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
+    p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
+    int32_t smax = KNN_FIN_MAX / p.kcap;
+    if (smax > p.n_rtiles) smax = p.n_rtiles;
+    int32_t S = r_splits;
+    if (S <= 0) S = p.n_qtiles >= 512 ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
+    if (S > smax) S = smax;
+    if (S < 1) S = 1;
+    p.rt_per_split = (p.n_rtiles + S - 1) / S;
+    p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
+    p.rcopy = metric == KNN_COSINE || p.dpad != d;
+
+    size_t o = 0;
+    p.off_qp = o;
+    o = align_up(o + (size_t)nq * p.dpad * sizeof(float), 256);
+    p.off_rp = o;
+    if (p.rcopy) o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
+    p.off_c = o;
+    o = align_up(o + (size_t)p.n_cpad * sizeof(float), 256);
+    p.off_sq = o;
+    o = align_up(o + (size_t)nq * sizeof(float), 256);
+    p.off_lists = o;
+    o = align_up(o + (size_t)p.S * p.nq_pad * p.kcap * sizeof(u64), 256);
+    p.total = o;
+    return true;
+}
+
+knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                         int64_t self_offset)
+{
+    if (nq < 1 || nr < 1 || d < 1 || k < 1) return KNN_EINVAL;
+    if (metric != KNN_SQEUCLIDEAN && metric != KNN_COSINE) return KNN_EINVAL;
+    if (self_offset < -1) return KNN_EINVAL;
+    if (self_offset >= 0 && self_offset + nq > nr) return KNN_EINVAL;
+    if ((int64_t)k > nr - (self_offset >= 0 ? 1 : 0)) return KNN_EINVAL;
+    if (nr >= ((int64_t)1 << 31) || nq >= ((int64_t)1 << 31)) return KNN_EUNSUPPORTED;
+    if (d > (1 << 20)) return KNN_EUNSUPPORTED;
+    if (k > KNN_MAX_K) return KNN_EUNSUPPORTED;
+    return KNN_OK;
+}
+
+struct Events {
+    hipEvent_t e[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool on = false;
+    hipError_t create()
+    {
+        for (auto &x : e) {
+            hipError_t r = hipEventCreate(&x);
+            if (r != hipSuccess) return r;
+        }
+        on = true;
+        return hipSuccess;
+    }
+    void record(int i, hipStream_t s)
+    {
+        if (on) (void)hipEventRecord(e[i], s);
+    }
+    ~Events()
+    {
+        for (auto &x : e)
+            if (x) (void)hipEventDestroy(x);
+    }
+};
+
+knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d, int32_t k,
+                 knn_metric_t metric, int64_t self_offset, bool self, int32_t *idx, float *dist,
+                 void *workspace, size_t workspace_bytes, void *stream_v, const knn_options_t *opt)
+{
+    g_last_error[0] = 0;
+    if (!Q || !R || !idx || !dist) return KNN_EINVAL;
+    knn_status_t st = check_sizes(nq, nr, d, k, metric, self_offset);
+    if (st != KNN_OK) return st;
+    if (((uintptr_t)Q & 15) || ((uintptr_t)R & 15) || ((uintptr_t)idx & 3) || ((uintptr_t)dist & 3))
+        return KNN_EINVAL;
+    knn_options_t o;
+    memset(&o, 0, sizeof(o));
+    if (opt) o = *opt;
+    if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0)
+        return KNN_EINVAL;
+
+    Plan p;
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, p);
+    if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
+    if (workspace_bytes < p.total) return KNN_ENOMEM;
+
+    hipStream_t stream = (hipStream_t)stream_v;
+    char *ws = (char *)workspace;
+    float *qp = (float *)(ws + p.off_qp);
+    float *rp = p.rcopy ? (float *)(ws + p.off_rp) : nullptr;
+    float *cr = (float *)(ws + p.off_c);
+    float *sq = (float *)(ws + p.off_sq);
+    u64 *lists = (u64 *)(ws + p.off_lists);
+
+    Events ev;
+    if (o.profile) {
+        hipError_t e = ev.create();
+        if (e != hipSuccess) {
+            set_error("hipEventCreate", e);
+            return KNN_EDEVICE;
+        }
+    }
+    hipError_t e;
+    ev.record(0, stream);
+
+    // ---- prologue: norms and scaled copies ----
+    if (self) {
+        PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq};
+        e = launch_prep(a, stream);
+        if (e != hipSuccess) { set_error("prep_rows", e); return KNN_EDEVICE; }
+    } else {
+        PrepArgs aq = {Q, nq, d, p.dpad, (int32_t)metric, qp, nullptr, nullptr, nq, sq};
+        e = launch_prep(aq, stream);
+        if (e != hipSuccess) { set_error("prep_rows(Q)", e); return KNN_EDEVICE; }
+        PrepArgs ar = {R, nr, d, p.dpad, (int32_t)metric, nullptr, rp, cr, p.n_cpad, nullptr};
+        e = launch_prep(ar, stream);
+        if (e != hipSuccess) { set_error("prep_rows(R)", e); return KNN_EDEVICE; }
+    }
+    ev.record(1, stream);
+
+    // ---- fused distance + selection ----
+    TileArgs t;
+    t.Qp = qp;
+    t.Rp = p.rcopy ? rp : R;
+    t.cR = cr;
+    t.lists = lists;
+    t.ldq = p.dpad;
+    t.ldr = p.rcopy ? p.dpad : d;
+    t.nq = nq;
+    t.nr = nr;
+    t.nq_pad = p.nq_pad;
+    t.self_offset = self_offset;
+    t.dpad = p.dpad;
+    t.k = k;
+    t.kcap = p.kcap;
+    t.n_qtiles = p.n_qtiles;
+    t.n_rtiles = p.n_rtiles;
+    t.S = p.S;
+    t.rt_per_split = p.rt_per_split;
+    e = launch_tiles(t, stream);
+    if (e != hipSuccess) { set_error("knn_tiles", e); return KNN_EDEVICE; }
+    ev.record(2, stream);
+
+    // ---- merge partial lists, re-score, final order ----
+    FinArgs f;
+    f.lists = lists;
+    f.Q = Q;
+    f.R = R;
+    f.sq = sq;
+    f.idx = idx;
+    f.dist = dist;
+    f.nq = nq;
+    f.nq_pad = p.nq_pad;
+    f.d = d;
+    f.k = k;
+    f.kcap = p.kcap;
+    f.S = p.S;
+    if (metric == KNN_COSINE)
+        f.mode = o.rescore == 2 ? FIN_ADD_ONE : FIN_RESCORE_COS;
+    else
+        f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_SQ;
+    f.vec4 = (d % 4 == 0) ? 1 : 0;
+    e = launch_finalize(f, stream);
+    if (e != hipSuccess) { set_error("finalize_rows", e); return KNN_EDEVICE; }
+    ev.record(3, stream);
+
+    if (o.profile) {
+        e = hipEventSynchronize(ev.e[3]);
+        if (e != hipSuccess) { set_error("hipEventSynchronize", e); return KNN_EDEVICE; }
+        knn_profile_t *pr = o.profile;
+        memset(pr, 0, sizeof(*pr));
+        (void)hipEventElapsedTime(&pr->ms_prepare, ev.e[0], ev.e[1]);
+        (void)hipEventElapsedTime(&pr->ms_main, ev.e[1], ev.e[2]);
+        (void)hipEventElapsedTime(&pr->ms_finalize, ev.e[2], ev.e[3]);
+        (void)hipEventElapsedTime(&pr->ms_total, ev.e[0], ev.e[3]);
+        pr->main_launches = 1;
+        pr->symmetric = 0;
+        pr->pairs_computed = p.nq_pad * p.n_cpad;
+    }
+    return KNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+knn_status_t knn_build_ex(const float *X, int64_t n, int32_t d, int32_t k, knn_metric_t metric,
+                          int32_t *idx, float *dist, void *workspace, size_t workspace_bytes,
+                          void *stream, const knn_options_t *opt)
+{
+    if (n < 2) return KNN_EINVAL;
+    return run(X, n, X, n, d, k, metric, 0, true, idx, dist, workspace, workspace_bytes, stream, opt);
+}
+
+knn_status_t knn_build(const float *X, int64_t n, int32_t d, int32_t k, knn_metric_t metric,
+                       int32_t *idx, float *dist, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    return knn_build_ex(X, n, d, k, metric, idx, dist, workspace, workspace_bytes, stream, nullptr);
+}
+
+knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                           int32_t k, knn_metric_t metric, int64_t self_offset, int32_t *idx,
+                           float *dist, void *workspace, size_t workspace_bytes, void *stream,
+                           const knn_options_t *opt)
+{
+    return run(Q, nq, R, nr, d, k, metric, self_offset, false, idx, dist, workspace,
+               workspace_bytes, stream, opt);
+}
+
+knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                        int32_t k, knn_metric_t metric, int64_t self_offset, int32_t *idx,
+                        float *dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return knn_search_ex(Q, nq, R, nr, d, k, metric, self_offset, idx, dist, workspace,
+                         workspace_bytes, stream, nullptr);
+}
+
+size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                              int32_t symmetric, const knn_options_t *opt)
+{
+    if (symmetric) nq = nr;
+    if (symmetric && nr < 2) return 0;
+    if (check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1) != KNN_OK) return 0;
+    Plan p;
+    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, p);
+    return p.total;
+}
+
+size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                           int32_t symmetric)
+{
+    return knn_workspace_bytes_ex(nq, nr, d, k, metric, symmetric, nullptr);
+}
+
+const char *knn_status_string(knn_status_t s)
+{
+    switch (s) {
+    case KNN_OK: return "ok";
+    case KNN_EINVAL: return "invalid argument";
+    case KNN_EUNSUPPORTED: return "unsupported size";
+    case KNN_ENOMEM: return "workspace too small";
+    case KNN_EDEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+const char *knn_last_device_error(void) { return g_last_error; }
+
+}  // extern "C"

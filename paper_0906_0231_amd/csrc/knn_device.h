@@ -1,0 +1,62 @@
+// Argument blocks shared by the host-side C ABI (knn_api.cpp) and the kernels
+// (knn_kernels.hip).  Plain structs passed by value at launch.
+#ifndef KNN_DEVICE_H_
+#define KNN_DEVICE_H_
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#ifndef KNN_DC
+#define KNN_DC 16          // coordinates staged through LDS per step
+#endif
+#define KNN_MAX_KCAP 128   // largest list capacity (>= KNN_MAX_K of the ABI)
+#define KNN_FIN_MAX 2048   // most keys per query finalize_rows can merge (S * kcap)
+#define KNN_TILE 128       // queries per workgroup tile == references per tile
+
+namespace knn {
+
+typedef unsigned long long u64;
+constexpr u64 KEY_INF = ~0ull;
+
+struct PrepArgs {
+    const float *X;    // [n, d]
+    int64_t n;
+    int32_t d, dpad, metric;
+    float *q_out;      // [n, dpad] query-side copy (scaled by -2 or -1/|x|), or null
+    float *r_out;      // [n, dpad] reference-side copy (x or x/|x|), or null
+    float *c_out;      // [n_cpad]  c_j, +inf beyond n, or null
+    int64_t n_cpad;
+    float *s_out;      // [n] squared norms, or null
+};
+
+struct TileArgs {
+    const float *Qp;   // [nq, ldq]
+    const float *Rp;   // [nr, ldr]
+    const float *cR;   // [n_rtiles * 128]
+    u64 *lists;        // [S, nq_pad, kcap]
+    int64_t ldq, ldr;
+    int64_t nq, nr, nq_pad;
+    int64_t self_offset;
+    int32_t dpad, k, kcap;
+    int32_t n_qtiles, n_rtiles, S, rt_per_split;
+};
+
+enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3 };
+
+struct FinArgs {
+    const u64 *lists;
+    const float *Q;    // original query rows  [nq, d]   (re-score)
+    const float *R;    // original references  [nr, d]
+    const float *sq;   // [nq] squared norms of the queries
+    int32_t *idx;      // [nq, k]
+    float *dist;       // [nq, k]
+    int64_t nq, nq_pad;
+    int32_t d, k, kcap, S, mode, vec4;
+};
+
+hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
+hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
+hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
+
+}  // namespace knn
+#endif

@@ -1,0 +1,246 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, on a real MI355X.
+
+Acceptance rule (oracle/compare.py): distances within 1e-5 relative of the oracle's
+double-precision value, identical neighbour sets except inside the 1e-5 band around the
+k-th distance, ties to the lower index.  Where the arithmetic is exact (integer
+lattice, one-hot rows, duplicated rows) the index lists must match bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import compare
+from paper_0906_0231_amd import api, knn_build, knn_search, workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    api.load_library()
+
+
+def _check_rows(R, rows, self_offset, k, metric, g_idx, g_dist, strict=False, atol=0.0):
+    """Oracle on the given query rows (indices into R offset by self_offset) vs GPU rows."""
+    R = np.ascontiguousarray(R)
+    rows = np.asarray(rows, dtype=np.int64)
+    Q = R[rows + max(self_offset, 0)] if self_offset >= 0 else None
+    assert Q is not None
+    self_idx = rows + self_offset
+    o_idx, o_dist, o_next = oracle.search(Q, R, k, metric, self_idx=self_idx)
+    rep = compare.check(Q, R, metric, o_idx, o_dist, o_next, g_idx[rows], g_dist[rows],
+                        self_idx=self_idx, rtol=RTOL, atol=atol, strict_ties=strict)
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)
+    return rep
+
+
+def _sample_rows(n, count, seed):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, n // 2 - 1, n // 2, n - 129, n - 128, n - 2, n - 1]
+    fixed = [r for r in fixed if 0 <= r < n]
+    extra = rng.choice(n, size=max(0, min(count, n) - len(fixed)), replace=False).tolist()
+    return np.array(sorted(set(fixed + extra)), dtype=np.int64)
+
+
+# ---------------------------------------------------------------------------
+# small cases: several tiles, ragged tails in n and d, both metrics, every list capacity
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,k,metric", [
+    (1500, 64, 10, "sqeuclidean"),
+    (777, 37, 5, "sqeuclidean"),
+    (1000, 48, 20, "cosine"),
+    (600, 130, 100, "sqeuclidean"),
+    (515, 16, 64, "cosine"),
+    (300, 1, 7, "sqeuclidean"),
+    (129, 8, 128, "sqeuclidean"),
+    (2, 5, 1, "sqeuclidean"),
+    (70, 3, 69, "cosine"),
+])
+def test_build_small(n, d, k, metric):
+    _say(f"  build n={n} d={d} k={k} {metric}")
+    X = workloads.gaussian(n, d, seed=1000 + n + d)
+    res = knn_build(X.cuda(), k, metric)
+    torch.cuda.synchronize()
+    _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+@pytest.mark.parametrize("splits", [1, 3, 16])
+@pytest.mark.parametrize("rescore", [1, 2])
+def test_split_reference_range_and_rescore(splits, rescore):
+    """Partial lists from several reference slices merge to the same answer; the answer
+    without the re-score still meets the tolerance."""
+    n, d, k = 2100, 32, 12
+    _say(f"  splits={splits} rescore={rescore}")
+    X = workloads.mixture(n, d, 8, seed=77)
+    res = knn_build(X.cuda(), k, "sqeuclidean", r_splits=splits, rescore=rescore)
+    torch.cuda.synchronize()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", res.idx.cpu().numpy(),
+                res.dist.cpu().numpy())
+
+
+@pytest.mark.parametrize("nq,nr,off,metric", [
+    (300, 1000, -1, "sqeuclidean"),
+    (257, 900, 643, "sqeuclidean"),
+    (128, 128, 0, "cosine"),
+    (1, 513, 512, "cosine"),
+    (640, 200, -1, "sqeuclidean"),
+])
+def test_search_small(nq, nr, off, metric):
+    d, k = 24, 9
+    _say(f"  search nq={nq} nr={nr} self_offset={off} {metric}")
+    R = workloads.gaussian(nr, d, seed=5 + nr)
+    if off >= 0:
+        Q = R[off:off + nq].contiguous()
+        self_idx = np.arange(nq) + off
+    else:
+        Q = workloads.gaussian(nq, d, seed=6 + nq)
+        self_idx = None
+    res = knn_search(Q.cuda(), R.cuda(), k, metric, self_offset=off)
+    torch.cuda.synchronize()
+    o_idx, o_dist, o_next = oracle.search(Q.numpy(), R.numpy(), k, metric, self_idx=self_idx)
+    rep = compare.check(Q.numpy(), R.numpy(), metric, o_idx, o_dist, o_next,
+                        res.idx.cpu().numpy(), res.dist.cpu().numpy(), self_idx=self_idx, rtol=RTOL)
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)
+
+
+def test_search_equals_build():
+    """knn_build(X) == knn_search(X, X, self_offset=0), bit for bit."""
+    X = workloads.gaussian(900, 40, seed=3).cuda()
+    a = knn_build(X, 11)
+    b = knn_search(X, X, 11, self_offset=0)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+
+
+# ---------------------------------------------------------------------------
+# exact cases: ties must go to the lower index, bit-exact distances
+# ---------------------------------------------------------------------------
+def test_lattice_exact():
+    n, k = 2000, 6
+    X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
+    res = knn_build(X.cuda(), k)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", gi, gd, strict=True)
+    assert gi[1000].tolist() == [999, 1001, 998, 1002, 997, 1003]
+    assert gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
+
+
+@pytest.mark.parametrize("metric", ["sqeuclidean", "cosine"])
+def test_all_equidistant(metric):
+    n, k = 200, 17
+    X = torch.eye(n, dtype=torch.float32)
+    res = knn_build(X.cuda(), k, metric)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    for i in (0, 1, 16, 17, 18, 127, 128, 199):
+        assert gi[i].tolist() == [j for j in range(n) if j != i][:k]
+    assert np.all(gd == (2.0 if metric == "sqeuclidean" else 1.0))
+    _check_rows(X.numpy(), np.arange(n), 0, k, metric, gi, gd, strict=True)
+
+
+def test_duplicate_rows():
+    base = workloads.gaussian(300, 20, seed=9)
+    X = base.repeat_interleave(2, dim=0).contiguous()
+    res = knn_build(X.cuda(), 4)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    assert np.array_equal(gi[:, 0], np.arange(600) ^ 1)
+    assert np.all(gd[:, 0] == 0.0)              # the re-score makes the twin's distance exactly 0
+    # each row's 2nd/3rd neighbours are another duplicated pair: an exact tie, lower index first
+    assert np.all(gi[:, 1] + 1 == gi[:, 2]) and np.all(gi[:, 1] % 2 == 0)
+    _check_rows(X.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
+
+
+def test_deterministic():
+    X = workloads.mixture(3000, 64, 16, seed=4).cuda()
+    a = knn_build(X, 10)
+    b = knn_build(X, 10)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+
+
+def test_nondefault_stream_and_caller_buffers():
+    X = workloads.gaussian(1000, 32, seed=8)
+    Xd = X.cuda()
+    idx = torch.empty((1000, 5), dtype=torch.int32, device="cuda")
+    dist = torch.empty((1000, 5), dtype=torch.float32, device="cuda")
+    ws = torch.empty(api.knn_workspace_bytes(1000, 1000, 32, 5, symmetric=True), dtype=torch.uint8,
+                     device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        knn_build(Xd, 5, workspace=ws, out=(idx, dist))
+    s.synchronize()
+    _check_rows(X.numpy(), np.arange(1000), 0, 5, "sqeuclidean", idx.cpu().numpy(), dist.cpu().numpy())
+
+
+def test_device_error_paths():
+    X = workloads.gaussian(100, 8, seed=1).cuda()
+    with pytest.raises(api.KnnError) as e:
+        knn_build(X, 100)
+    assert e.value.status == api.KNN_EINVAL
+    with pytest.raises(api.KnnError) as e:
+        knn_build(X, 5, workspace=torch.empty(512, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.KNN_ENOMEM
+
+
+# ---------------------------------------------------------------------------
+# the benchmark configurations at full size (oracle on sampled rows where the full
+# oracle would take hours)
+# ---------------------------------------------------------------------------
+def test_config1_full():
+    w = workloads.config(1)
+    _say(f"  {w.name}")
+    res = knn_build(w.R.cuda(), w.k, w.metric)
+    torch.cuda.synchronize()
+    _check_rows(w.R.numpy(), np.arange(w.n), 0, w.k, w.metric, res.idx.cpu().numpy(),
+                res.dist.cpu().numpy())
+
+
+def _full_size(which, sample):
+    w = workloads.config(which)
+    _say(f"  {w.name}: generated")
+    Rd = w.R.cuda()
+    if w.symmetric:
+        res = knn_build(Rd, w.k, w.metric, profile=True)
+    else:
+        res = knn_search(Rd[:w.nq], Rd, w.k, w.metric, self_offset=0, profile=True)
+    torch.cuda.synchronize()
+    _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms fused kernel")
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    del Rd
+    rows = _sample_rows(w.nq, sample, seed=which)
+    _check_rows(w.R.numpy(), rows, 0, w.k, w.metric, gi, gd)
+    # properties that hold at any size, on every row
+    assert np.all(np.diff(gd, axis=1) >= 0)
+    assert not np.any(gi == np.arange(w.nq, dtype=np.int64)[:, None])
+    assert gi.min() >= 0 and gi.max() < w.n
+    s = np.sort(gi, axis=1)
+    assert np.all(s[:, 1:] != s[:, :-1])
+
+
+def test_config2_full():
+    _full_size(2, 1024)
+
+
+def test_config3_full():
+    _full_size(3, 256)
+
+
+def test_config4_full():
+    _full_size(4, 128)
+
+
+def test_config5_full():
+    _full_size(5, 48)

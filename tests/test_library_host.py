@@ -1,0 +1,75 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_0906_0231_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(api.LIB_PATH):
+        from paper_0906_0231_amd.build import build_library
+        build_library()
+    return api.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "knn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(knn_[a-z_]+)\s*\(", text))
+    assert declared == set(api.EXPORTS), declared ^ set(api.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    names = [lib.knn_status_string(i).decode() for i in range(5)]
+    assert names[0] == "ok" and len(set(names)) == 5
+    assert lib.knn_status_string(99).decode() == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    f = lib.knn_workspace_bytes
+    assert f(0, 1, 8, 1, 0, 0) == 0            # nq < 1
+    assert f(4, 4, 8, 4, 0, 1) == 0            # k > n - 1 for a self search
+    assert f(4, 4, 8, 4, 0, 0) > 0             # fine when queries are not references
+    assert f(10, 10, 8, 3, 7, 0) == 0          # unknown metric
+    assert f(10, 1000, 8, api.KNN_MAX_K + 1, 0, 0) == 0
+    n, d, k = 1 << 20, 256, 10
+    b = f(n, n, d, k, 0, 1)
+    # scaled query copy + norms + one 16-slot list per query, and not much more
+    assert n * d * 4 + n * 16 * 8 <= b <= n * d * 4 + n * 16 * 8 + n * 16 + (1 << 20)
+    assert f(n, n, d, k, 1, 1) >= b + n * d * 4   # cosine also keeps a normalised reference copy
+    assert f(n, n, d + 1, k, 0, 1) > b            # ragged d: padded copies of both sides
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    one = ctypes.c_void_p(256)                  # never dereferenced: checks fail first
+    ws = ctypes.c_void_p(4096)
+    call = lib.knn_build
+    assert call(None, 100, 8, 3, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL
+    assert call(one, 1, 8, 1, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL      # n < 2
+    assert call(one, 100, 0, 3, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # d < 1
+    assert call(one, 100, 8, 0, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # k < 1
+    assert call(one, 100, 8, 100, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL  # k > n-1
+    assert call(one, 1000, 8, 129, 0, one, one, ws, 1 << 30, None) == api.KNN_EUNSUPPORTED
+    assert call(one, 100, 8, 3, 5, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # metric
+    assert call(one, 100, 8, 3, 0, one, one, None, 1 << 30, None) == api.KNN_EINVAL  # no workspace
+    assert call(one, 100, 8, 3, 0, one, one, ws, 16, None) == api.KNN_ENOMEM
+    assert call(ctypes.c_void_p(260), 100, 8, 3, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL
+    s = lib.knn_search
+    assert s(one, 10, one, 100, 8, 3, 0, 95, one, one, ws, 1 << 30, None) == api.KNN_EINVAL  # self range
+    assert s(one, 10, one, 100, 8, 3, 0, -2, one, one, ws, 1 << 30, None) == api.KNN_EINVAL
+    assert s(one, 10, one, 1 << 31, 8, 3, 0, -1, one, one, ws, 1 << 30, None) == api.KNN_EUNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    with pytest.raises(ValueError):
+        api.knn_build(torch.zeros(10, 4), 2)
