@@ -32,6 +32,9 @@ def main() -> int:
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain elementwise copy of 1 GiB (for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -113,6 +116,15 @@ def main() -> int:
                      "traffic": None, "kernel": "knn_tiles",
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)       # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        out["config"]["copy_calibration_bytes_each_way"] = src.numel() * 4
+        del src, dst
 
     if not args.no_cpu_baseline:
         import oracle
