@@ -30,6 +30,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the headline one)")
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query-resident")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -59,17 +60,18 @@ def main() -> int:
     nq, nr, d, k = w.nq, w.n, w.d, w.k
     gen_s = time.time() - t0
 
-    ws = torch.empty(knn_workspace_bytes(nq, nr, d, k, w.metric, symmetric=w.symmetric),
+    ws = torch.empty(knn_workspace_bytes(nq, nr, d, k, w.metric, symmetric=w.symmetric,
+                                         variant=args.variant),
                      dtype=torch.uint8, device=dev)
     idx = torch.empty((nq, k), dtype=torch.int32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
     def step(profile):
         if w.symmetric:
-            return knn_build(R, k, w.metric, symmetric=args.symmetric, profile=profile,
-                             workspace=ws, out=(idx, dist))
-        return knn_search(Q, R, k, w.metric, self_offset=w.self_offset, profile=profile,
-                          workspace=ws, out=(idx, dist))
+            return knn_build(R, k, w.metric, symmetric=args.symmetric, variant=args.variant,
+                             profile=profile, workspace=ws, out=(idx, dist))
+        return knn_search(Q, R, k, w.metric, self_offset=w.self_offset, variant=args.variant,
+                          profile=profile, workspace=ws, out=(idx, dist))
 
     for _ in range(args.warmup):
         step(False)

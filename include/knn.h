@@ -78,7 +78,10 @@ typedef struct {
                            always done on the fp32 matrix-core values */
     int32_t r_splits;   /* 0 = auto.  Number of slices the reference range is cut
                            into per query tile (partial lists are merged at the end) */
-    int32_t reserved;
+    int32_t variant;    /* fused-kernel variant.  0 = auto (3 if d <= 256, else 1).
+                           1 = streaming: both operands through LDS chunk by chunk, any d.
+                           2 = query tile resident in LDS, 3 = query tile resident in
+                           registers; both need d <= 256 and fall back to 1 otherwise */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
                            kernels with events, waits for them and fills this in */
 } knn_options_t;

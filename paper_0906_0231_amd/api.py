@@ -36,7 +36,7 @@ class KnnProfile(ctypes.Structure):
 
 class KnnOptions(ctypes.Structure):
     _fields_ = [("symmetric", ctypes.c_int32), ("rescore", ctypes.c_int32),
-                ("r_splits", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("r_splits", ctypes.c_int32), ("variant", ctypes.c_int32),
                 ("profile", ctypes.POINTER(KnnProfile))]
 
 
@@ -94,9 +94,9 @@ def _metric(metric) -> int:
     return METRICS[metric] if isinstance(metric, str) else int(metric)
 
 
-def _options(symmetric: int, rescore: int, r_splits: int, profile: bool):
+def _options(symmetric: int, rescore: int, r_splits: int, profile: bool, variant: int = 0):
     opt = KnnOptions()
-    opt.symmetric, opt.rescore, opt.r_splits = symmetric, rescore, r_splits
+    opt.symmetric, opt.rescore, opt.r_splits, opt.variant = symmetric, rescore, r_splits, variant
     prof = KnnProfile() if profile else None
     if prof is not None:
         opt.profile = ctypes.pointer(prof)
@@ -114,9 +114,9 @@ def _dev_matrix(x: torch.Tensor, name: str) -> torch.Tensor:
 
 
 def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
-                        symmetric: bool = False, r_splits: int = 0) -> int:
+                        symmetric: bool = False, r_splits: int = 0, variant: int = 0) -> int:
     lib = load_library()
-    opt, _ = _options(0, 0, r_splits, False)
+    opt, _ = _options(0, 0, r_splits, False, variant)
     return int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), int(symmetric),
                                           ctypes.byref(opt)))
 
@@ -129,7 +129,7 @@ class KnnResult:
 
 
 def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int = 0,
-              rescore: int = 0, r_splits: int = 0, profile: bool = False,
+              rescore: int = 0, r_splits: int = 0, variant: int = 0, profile: bool = False,
               workspace: Optional[torch.Tensor] = None,
               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
     """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h."""
@@ -140,7 +140,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
         idx, dist = out if out is not None else (
             torch.empty((n, k), dtype=torch.int32, device=X.device),
             torch.empty((n, k), dtype=torch.float32, device=X.device))
-        opt, prof = _options(symmetric, rescore, r_splits, profile)
+        opt, prof = _options(symmetric, rescore, r_splits, profile, variant)
         if workspace is None:
             nbytes = int(lib.knn_workspace_bytes_ex(n, n, d, k, _metric(metric), 1, ctypes.byref(opt)))
             workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
@@ -152,7 +152,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
 
 
 def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
-               self_offset: int = -1, *, rescore: int = 0, r_splits: int = 0,
+               self_offset: int = -1, *, rescore: int = 0, r_splits: int = 0, variant: int = 0,
                profile: bool = False, workspace: Optional[torch.Tensor] = None,
                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
     """Neighbours of every row of Q among the rows of R; see knn_search in knn.h."""
@@ -167,7 +167,7 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
         idx, dist = out if out is not None else (
             torch.empty((nq, k), dtype=torch.int32, device=Q.device),
             torch.empty((nq, k), dtype=torch.float32, device=Q.device))
-        opt, prof = _options(0, rescore, r_splits, profile)
+        opt, prof = _options(0, rescore, r_splits, profile, variant)
         if workspace is None:
             nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), 0, ctypes.byref(opt)))
             workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=Q.device)

@@ -31,6 +31,9 @@ struct Plan {
     int64_t nq_pad, n_cpad;
     bool self;      // knn_build: one matrix serves as queries and references
     bool rcopy;     // references need a scaled / padded copy
+    bool qres;      // query tile resident in LDS (knn_tiles_qres): two lists per slice
+    bool qreg;      // query tile resident in registers (knn_tiles_qreg)
+    int32_t nlists; // partial lists per query
     size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
 };
 
@@ -44,16 +47,21 @@ int32_t list_capacity(int32_t k)
 // Sizes are assumed validated.  r_splits == 0 picks a split count that gives
 // the 256 compute units at least two workgroups each when query tiles are few.
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
-               int32_t r_splits, Plan &p)
+               int32_t r_splits, int32_t variant, Plan &p)
 {
     p.self = self;
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
+    const int32_t dpad32 = (int32_t)align_up((size_t)d, 32);
+    p.qreg = (variant == 0 || variant == 3) && dpad32 <= KNN_QRES_MAX_D;
+    if (p.qreg) p.dpad = dpad32;
     p.kcap = list_capacity(k);
     p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
     p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
     p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
     p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
-    int32_t smax = KNN_FIN_MAX / p.kcap;
+    p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
+    const int32_t per_slice = p.qres ? 2 : 1;
+    int32_t smax = KNN_FIN_MAX / (p.kcap * per_slice);
     if (smax > p.n_rtiles) smax = p.n_rtiles;
     int32_t S = r_splits;
     if (S <= 0) S = p.n_qtiles >= 512 ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
@@ -61,6 +69,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     if (S < 1) S = 1;
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
+    p.nlists = p.S * per_slice;
     p.rcopy = metric == KNN_COSINE || p.dpad != d;
 
     size_t o = 0;
@@ -73,7 +82,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.off_sq = o;
     o = align_up(o + (size_t)nq * sizeof(float), 256);
     p.off_lists = o;
-    o = align_up(o + (size_t)p.S * p.nq_pad * p.kcap * sizeof(u64), 256);
+    o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
     return true;
 }
@@ -128,11 +137,12 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     knn_options_t o;
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
-    if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0)
+    if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
+        o.variant < 0 || o.variant > 3)
         return KNN_EINVAL;
 
     Plan p;
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, p);
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, p);
     if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
     if (workspace_bytes < p.total) return KNN_ENOMEM;
 
@@ -189,8 +199,11 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     t.n_rtiles = p.n_rtiles;
     t.S = p.S;
     t.rt_per_split = p.rt_per_split;
-    e = launch_tiles(t, stream);
-    if (e != hipSuccess) { set_error("knn_tiles", e); return KNN_EDEVICE; }
+    e = p.qreg ? launch_tiles_qreg(t, stream) : p.qres ? launch_tiles_qres(t, stream) : launch_tiles(t, stream);
+    if (e != hipSuccess) {
+        set_error(p.qreg ? "knn_tiles_qreg" : p.qres ? "knn_tiles_qres" : "knn_tiles", e);
+        return KNN_EDEVICE;
+    }
     ev.record(2, stream);
 
     // ---- merge partial lists, re-score, final order ----
@@ -206,7 +219,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.d = d;
     f.k = k;
     f.kcap = p.kcap;
-    f.S = p.S;
+    f.S = p.nlists;
     if (metric == KNN_COSINE)
         f.mode = o.rescore == 2 ? FIN_ADD_ONE : FIN_RESCORE_COS;
     else
@@ -275,7 +288,7 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     if (symmetric && nr < 2) return 0;
     if (check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1) != KNN_OK) return 0;
     Plan p;
-    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, p);
+    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, opt ? opt->variant : 0, p);
     return p.total;
 }
 

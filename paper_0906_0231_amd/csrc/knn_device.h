@@ -11,6 +11,7 @@
 #endif
 #define KNN_MAX_KCAP 128   // largest list capacity (>= KNN_MAX_K of the ABI)
 #define KNN_FIN_MAX 2048   // most keys per query finalize_rows can merge (S * kcap)
+#define KNN_QRES_MAX_D 256 // largest padded d whose query tile is kept resident in LDS
 #define KNN_TILE 128       // queries per workgroup tile == references per tile
 
 namespace knn {
@@ -56,6 +57,8 @@ struct FinArgs {
 
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
+hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
+hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
 
 }  // namespace knn

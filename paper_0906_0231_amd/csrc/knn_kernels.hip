@@ -186,6 +186,86 @@ __device__ __forceinline__ u64 merge_one(u64 *L, int kcap, int k, const u64 *cq,
     return readlane64(tk, src);
 }
 
+// State a wave keeps for the selection of its 32 queries.
+struct SelState {
+    u64 tau_key;      // current k-th best (distance, index) key of the lane's query; KEY_INF if fewer than k
+    float tau_p;      // its distance part (+inf while the list is not full)
+    int32_t selfj;    // reference index that is the lane's query itself, or -1
+    u64 *Lw;          // the wave's 32 lists in global memory, kcap entries each
+    u64 *cq;          // the wave's candidate queues in LDS: [32][QCAP]
+    uint32_t *cnt;    // their fill counts: [32]
+    u64 *shared_tau;  // LDS [32]: bound shared with the other waves serving the same queries, or null
+};
+
+constexpr int QCAP_MAX = 16;
+
+// The rare path of the selection: some accumulator of this wave is below its query's
+// threshold.  One 32x32 block at a time, its 16 registers are walked with a run-time
+// index (small code, no extra register pressure in the hot loop).  A survivor is tested
+// exactly on the packed (distance, index) key, with the query itself and padding rows
+// excluded, and appended to the query's queue; the queues are then rank-merged into the
+// lists.  A full queue loses nothing: the value stays in the block copy and the block
+// is walked again after the merge.
+//   jb0: reference row of register 0 of block 0 for this lane (tile base + 4*(lane/32));
+//   block t adds 32t.
+template <int NB, int QC>
+__device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0, int64_t nr, int kcap,
+                                            int k, SelState &st, int lane)
+{
+    const int ql = lane & 31;
+#pragma unroll 1
+    for (int t = 0; t < NB; ++t) {
+        f32x16 v = acc[0];
+#pragma unroll
+        for (int b = 1; b < NB; ++b)
+            if (t == b) v = acc[b];
+        if (__ballot(min16(v) <= st.tau_p) == 0) continue;
+        const int32_t jbase = jb0 + t * 32;
+        bool again;
+        do {
+            bool ovf = false;
+#pragma unroll 1
+            for (int r = 0; r < 16; ++r) {
+                float p = v[r];
+                bool c = p <= st.tau_p;
+                if (__ballot(c)) {
+                    int32_t j = jbase + 8 * (r >> 2) + (r & 3);
+                    u64 key = make_key(p, j);
+                    if (c && key < st.tau_key && j < nr && j != st.selfj) {
+                        uint32_t slot = atomicAdd(&st.cnt[ql], 1u);
+                        if (slot < (uint32_t)QC) {
+                            st.cq[ql * QC + slot] = key;
+                            p = __builtin_inff();          // taken: a re-walk must not see it again
+                        } else {
+                            ovf = true;
+                        }
+                    }
+                    v[r] = p;
+                }
+            }
+            again = __ballot(ovf) != 0;
+            // merge every non-empty queue of this wave into its list
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            uint32_t mycnt = *(volatile uint32_t *)&st.cnt[ql];
+            u64 pend = __ballot(mycnt > 0) & 0xffffffffull;
+            while (pend) {
+                int qi = __builtin_ctzll(pend);
+                pend &= pend - 1;
+                int nc = min((int)__builtin_amdgcn_readlane(mycnt, qi), QC);
+                u64 nt = merge_one(st.Lw + (int64_t)qi * kcap, kcap, k, st.cq + qi * QC, nc, lane);
+                if (ql == qi && nt < st.tau_key) st.tau_key = nt;
+            }
+            st.tau_p = st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            if (lane < 32) {
+                st.cnt[lane] = 0;
+                if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        } while (again);
+    }
+}
+
 __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
 {
     __shared__ TileSmem sm;
@@ -209,9 +289,14 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
 
     const int64_t myq = qbase + 32 * w + ql;
     const bool qvalid = myq < a.nq;
-    u64 tau_key = qvalid ? KEY_INF : 0ull;
-    float tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
-    const int32_t selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    SelState st;
+    st.tau_key = qvalid ? KEY_INF : 0ull;
+    st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
+    st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    st.Lw = Lw;
+    st.cq = &sm.cq[w][0][0];
+    st.cnt = &sm.cnt[w][0];
+    st.shared_tau = nullptr;
 
     // staging: thread -> (row, 16-byte column) of the DC-wide chunk
     const int lcol = (tid % LD_PER_ROW) * 4;
@@ -299,63 +384,354 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
             m4 = fminf(m4, min16(acc[1]));
             m4 = fminf(m4, min16(acc[2]));
             m4 = fminf(m4, min16(acc[3]));
-            if (__ballot(m4 <= tau_p)) {
-                // Rare path, kept small on purpose: one 32x32 block at a time, its
-                // 16 registers walked with a run-time index.
-#pragma unroll 1
-                for (int t = 0; t < 4; ++t) {
-                    f32x16 v = t == 0 ? acc[0] : t == 1 ? acc[1] : t == 2 ? acc[2] : acc[3];
-                    if (__ballot(min16(v) <= tau_p) == 0) continue;
-                    const int32_t jbase = rt * TR + t * 32 + 4 * h;
-                    bool again;
-                    do {
-                        bool ovf = false;
-#pragma unroll 1
-                        for (int r = 0; r < 16; ++r) {
-                            float p = v[r];
-                            bool c = p <= tau_p;
-                            if (__ballot(c)) {
-                                int32_t j = jbase + 8 * (r >> 2) + (r & 3);
-                                u64 key = make_key(p, j);
-                                if (c && key < tau_key && j < a.nr && j != selfj) {
-                                    uint32_t slot = atomicAdd(&sm.cnt[w][ql], 1u);
-                                    if (slot < (uint32_t)QCAP) {
-                                        sm.cq[w][ql][slot] = key;
-                                        p = __builtin_inff();     // taken: a re-scan must not see it again
-                                    } else {
-                                        ovf = true;
-                                    }
-                                }
-                                v[r] = p;
-                            }
-                        }
-                        again = __ballot(ovf) != 0;
-                        // merge every non-empty queue of this wave into its list
-                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                        uint32_t mycnt = *(volatile uint32_t *)&sm.cnt[w][ql];
-                        u64 pend = __ballot(mycnt > 0) & 0xffffffffull;
-                        while (pend) {
-                            int qi = __builtin_ctzll(pend);
-                            pend &= pend - 1;
-                            int nc = min((int)__builtin_amdgcn_readlane(mycnt, qi), QCAP);
-                            u64 nt = merge_one(Lw + (int64_t)qi * a.kcap, a.kcap, a.k, &sm.cq[w][qi][0], nc, lane);
-                            if (ql == qi) {
-                                tau_key = nt;
-                                tau_p = nt == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(nt >> 32));
-                            }
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                        if (lane < 32) sm.cnt[w][lane] = 0;
-                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                    } while (again);
-                }
-            }
+            if (__ballot(m4 <= st.tau_p)) select_rare<4, QCAP>(acc, rt * TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
         }
 
         if (more) stash(buf ^ 1, nkc);
         __syncthreads();
         rt = nrt;
         kc = nkc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// knn_tiles_qres: the fused kernel with the query tile stationary in LDS
+// (d padded <= 256).
+//
+// The streaming kernel above re-reads its 128 x d query tile for every reference
+// tile; with 64 workgroups per XCD those tiles do not fit the 4 MB L2 and evict the
+// shared reference stream as well, so every tile load misses.  Here the scaled query
+// tile is loaded into LDS once per sweep (128 rows x (d+4) floats <= 130 KB of the
+// 160 KB) and only reference rows stream.  One workgroup of 8 waves per CU:
+//   wave = (query group i of 32 queries) x (reference half g of 64 rows of the tile),
+//   two 32x32 accumulator blocks per wave.
+// The two halves are independent pipelines: each stages only its own 64 reference rows
+// (own LDS buffers) and synchronises only its own 4 waves, through a counter in LDS, so
+// that a half waiting for its slowest wave (or walking a rare path) leaves the matrix
+// pipe of every SIMD to the wave of the other half.  s_barrier would couple all 8.
+// Each wave keeps its own partial list per query (its half of every reference tile);
+// the two halves share the tighter of their two thresholds through LDS.
+// ---------------------------------------------------------------------------
+constexpr int QR_QCAP = 4;
+constexpr int QR_HALF = 64;                       // reference rows per half tile
+constexpr int QR_RBUF = QR_HALF * DC;             // floats per staging buffer
+
+// R staging layout: 64-byte rows, 16-byte units XOR-swizzled so that both the
+// row-contiguous stores and the 16-rows-same-unit fragment reads are conflict free.
+__device__ __forceinline__ int qr_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ void group_sync(uint32_t *bar, uint32_t target, int lane)
+{
+    // LDS operations of a wave complete in order, so once this wave's counter update is
+    // performed its staging stores are visible.  No global-memory wait: loads issued for
+    // later steps stay in flight.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    if (lane == 0) atomicAdd(bar, 1u);
+    while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
+        __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const int qstr = a.dpad + 4;                  // odd number of 16-byte units per row
+    float *sQ = (float *)smem_raw;                // [128][qstr]
+    float *sR = sQ + TQ * qstr;                   // [2 halves][2 buffers][QR_RBUF]
+    float *sC = sR + 4 * QR_RBUF;                 // [2][2][64]
+    u64 *sCq = (u64 *)(sC + 4 * QR_HALF);         // [8 waves][32][QR_QCAP]
+    u64 *sTau = sCq + 8 * 32 * QR_QCAP;           // [4 query groups][32]
+    uint32_t *sCnt = (uint32_t *)(sTau + 4 * 32); // [8][32]
+    uint32_t *sBar = sCnt + 8 * 32;               // [2]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int g = w >> 2;                         // reference half
+    const int qi = w & 3;                         // query group
+    const int gt = tid & 255;                     // thread index inside the half
+    const int h = lane >> 5;
+    const int ql = lane & 31;
+
+    const int qt = blockIdx.x / a.S;
+    const int split = blockIdx.x - qt * a.S;
+    const int64_t qbase = (int64_t)qt * TQ;
+    const int rt0 = split * a.rt_per_split;
+    const int rt1 = min(rt0 + a.rt_per_split, a.n_rtiles);
+    const int nk = a.dpad / DC;
+
+    u64 *Lw = a.lists + ((int64_t)(split * 2 + g) * a.nq_pad + qbase + 32 * qi) * a.kcap;
+    for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
+    const int64_t myq = qbase + 32 * qi + ql;
+    const bool qvalid = myq < a.nq;
+    if (lane < 32) {
+        sCnt[w * 32 + lane] = 0;
+        if (g == 0) sTau[qi * 32 + lane] = qvalid ? KEY_INF : 0ull;
+    }
+    if (tid < 2) sBar[tid] = 0;
+
+    SelState st;
+    st.tau_key = qvalid ? KEY_INF : 0ull;
+    st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
+    st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    st.Lw = Lw;
+    st.cq = sCq + w * 32 * QR_QCAP;
+    st.cnt = sCnt + w * 32;
+    st.shared_tau = sTau + qi * 32;
+
+    // query tile -> LDS, once
+    {
+        const int upr = a.dpad >> 2;              // 16-byte units per row
+        for (int u = tid; u < TQ * upr; u += 512) {
+            int row = u / upr, c4 = u - row * upr;
+            int64_t grow = min(qbase + row, a.nq - 1);
+            *(f32x4 *)&sQ[row * qstr + c4 * 4] = *(const f32x4 *)(a.Qp + grow * a.ldq + c4 * 4);
+        }
+    }
+    __syncthreads();
+
+    // staging of this half's 64 reference rows: thread -> (row, 16-byte unit)
+    const int lrow = gt >> 2, lunit = gt & 3;
+    float *myR = sR + g * 2 * QR_RBUF;
+    float *myC = sC + g * 2 * QR_HALF;
+    uint32_t *myBar = sBar + g;
+    const int st_off = lrow * DC + ((lunit ^ qr_swz(lrow)) << 2);
+    f32x4 pre[2];
+    float prec[2] = {0.f, 0.f};
+    int irt = rt0, ikc = 0;                       // (tile, chunk) of the next load to issue
+
+    auto issue = [&](int slot) {
+        int64_t row = min((int64_t)irt * TR + g * QR_HALF + lrow, a.nr - 1);
+        pre[slot] = *(const f32x4 *)(a.Rp + row * a.ldr + ikc * DC + lunit * 4);
+        // every thread, every step: a fixed number of loads in flight lets the compiler
+        // wait for exactly the older pair instead of draining the queue
+        prec[slot] = a.cR[(int64_t)irt * TR + g * QR_HALF + (gt & (QR_HALF - 1))];
+        if (++ikc == nk) { ikc = 0; ++irt; }
+    };
+    auto stash = [&](int slot, int buf, bool first_chunk) {
+        *(f32x4 *)&myR[buf * QR_RBUF + st_off] = pre[slot];
+        if (first_chunk && gt < QR_HALF) myC[buf * QR_HALF + gt] = prec[slot];
+    };
+
+    const int total = (rt1 - rt0) * nk;
+    uint32_t epoch = 0;
+    if (total > 0) {
+        issue(0);
+        if (total > 1) issue(1);
+        stash(0, 0, true);
+    }
+    epoch += 4;
+    group_sync(myBar, epoch, lane);
+
+    f32x16 acc[2];
+    const float *qp = sQ + (32 * qi + ql) * qstr + h * 4;
+    // fragment read offsets of the two 32-row blocks of this half (swizzled units)
+    int roff[2][NSLAB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < NSLAB; ++s) {
+            int row = t * 32 + ql;
+            roff[t][s] = row * DC + (((2 * s + h) ^ qr_swz(row)) << 2);
+        }
+
+    int rt = rt0, kc = 0;
+    auto step = [&](int it, int slot) {
+        // slot == it & 1: registers that held step `it` are free again, refill for it+2
+        if (it + 2 < total) issue(slot);
+        const int buf = it & 1;
+        if (kc == 0) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 cv = *(const f32x4 *)&myC[buf * QR_HALF + t * 32 + gg * 8 + h * 4];
+                    acc[t][4 * gg + 0] = cv[0];
+                    acc[t][4 * gg + 1] = cv[1];
+                    acc[t][4 * gg + 2] = cv[2];
+                    acc[t][4 * gg + 3] = cv[3];
+                }
+        }
+        const float *rb = myR + buf * QR_RBUF;
+        const float *qk = qp + kc * DC;
+#pragma unroll
+        for (int s = 0; s < NSLAB; ++s) {
+            f32x4 qf = *(const f32x4 *)(qk + s * 8);
+            f32x4 rf0 = *(const f32x4 *)(rb + roff[0][s]);
+            f32x4 rf1 = *(const f32x4 *)(rb + roff[1][s]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc[1], 0, 0, 0);
+            }
+        }
+        if (kc == nk - 1) {
+            u64 sh = st.shared_tau[ql];            // the other half may have tightened the bound
+            if (sh < st.tau_key) {
+                st.tau_key = sh;
+                st.tau_p = ord2f((uint32_t)(sh >> 32));
+            }
+            float m2 = fminf(min16(acc[0]), min16(acc[1]));
+            if (__ballot(m2 <= st.tau_p))
+                select_rare<2, QR_QCAP>(acc, rt * TR + g * QR_HALF + 4 * h, a.nr, a.kcap, a.k, st, lane);
+        }
+        int nkc = kc + 1, nrt = rt;
+        if (nkc == nk) { nkc = 0; nrt = rt + 1; }
+        if (it + 1 < total) stash(slot ^ 1, buf ^ 1, nkc == 0);
+        epoch += 4;
+        group_sync(myBar, epoch, lane);
+        rt = nrt;
+        kc = nkc;
+    };
+    for (int it = 0; it < total; it += 2) {
+        step(it, 0);
+        if (it + 1 < total) step(it + 1, 1);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// knn_tiles_qreg<DPAD>: the fused kernel with the query tile stationary in REGISTERS.
+//
+// Same ownership as knn_tiles (4 waves, wave = 32 queries, two independent workgroups
+// per CU), but a wave loads the B operands of its 32 queries for all DPAD coordinates
+// once per sweep: lane (q, h) keeps coordinates 8s+4h .. 8s+4h+3 of every 8-wide slab s,
+// DPAD/2 floats per lane (128 VGPRs at d = 256).  Only reference rows are staged through
+// LDS (64 rows x 32 coordinates per step, two 32x32 accumulator blocks per wave), so per
+// reference row the workgroup reads d floats instead of 2d, the 64 workgroups of an XCD
+// all stream the same reference rows through the L2, and no query tile competes for it.
+// The d-loop is fully unrolled so that the query registers are addressed statically.
+// ---------------------------------------------------------------------------
+constexpr int QG_TR = 64;                         // reference rows per tile
+constexpr int QG_DC = 32;                         // coordinates per step
+constexpr int QG_NSLAB = QG_DC / 8;
+constexpr int QG_RBUF = QG_TR * QG_DC;            // floats per staging buffer (128-byte rows)
+
+// 128-byte rows of eight 16-byte units, XOR-swizzled: a row is stored contiguously, and
+// 16 consecutive rows reading the same logical unit touch 16 different bank groups.
+__device__ __forceinline__ int qg_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+struct __attribute__((aligned(16))) QregSmem {
+    float r[2][QG_RBUF];
+    float c[2][QG_TR];
+    u64 cq[4][32][QCAP];
+    uint32_t cnt[4][32];
+};
+
+template <int DPAD>
+__global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
+{
+    constexpr int NK = DPAD / QG_DC;
+    constexpr int NS = DPAD / 8;
+    __shared__ QregSmem sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int h = lane >> 5;
+    const int ql = lane & 31;
+
+    const int qt = blockIdx.x / a.S;
+    const int split = blockIdx.x - qt * a.S;
+    const int64_t qbase = (int64_t)qt * TQ;
+    // slices are cut in units of 128 reference rows; this kernel walks them 64 at a time
+    const int rt0 = split * a.rt_per_split * 2;
+    const int rt1 = min(rt0 + a.rt_per_split * 2, (int)((a.nr + QG_TR - 1) / QG_TR));
+
+    u64 *Lw = a.lists + ((int64_t)split * a.nq_pad + qbase + 32 * w) * a.kcap;
+    for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
+    if (lane < 32) sm.cnt[w][lane] = 0;
+
+    const int64_t myq = qbase + 32 * w + ql;
+    const bool qvalid = myq < a.nq;
+    SelState st;
+    st.tau_key = qvalid ? KEY_INF : 0ull;
+    st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
+    st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    st.Lw = Lw;
+    st.cq = &sm.cq[w][0][0];
+    st.cnt = &sm.cnt[w][0];
+    st.shared_tau = nullptr;
+
+    // the wave's query operands, once
+    f32x4 qreg[NS];
+    {
+        const float *qrow = a.Qp + min(myq, a.nq - 1) * a.ldq + h * 4;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) qreg[s] = *(const f32x4 *)(qrow + s * 8);
+    }
+
+    // staging of the 64 reference rows: thread -> 16-byte unit lunit of rows lrow and lrow+32
+    const int lrow = tid >> 3, lunit = tid & 7;
+    const int st_off = lrow * QG_DC + ((lunit ^ qg_swz(lrow)) << 2);   // rows r and r+32 swizzle alike
+    f32x4 g0, g1;
+    float gc = 0.f;
+    auto issue = [&](int rt, int kc) {
+        int64_t r0 = min((int64_t)rt * QG_TR + lrow, a.nr - 1);
+        int64_t r1 = min((int64_t)rt * QG_TR + lrow + 32, a.nr - 1);
+        g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
+        g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
+        if (kc == 0 && tid < QG_TR) gc = a.cR[(int64_t)rt * QG_TR + tid];
+    };
+    auto stash = [&](int buf, int kc) {
+        *(f32x4 *)&sm.r[buf][st_off] = g0;
+        *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
+        if (kc == 0 && tid < QG_TR) sm.c[buf][tid] = gc;
+    };
+    // fragment read offsets: block t (rows 32t + ql), slab s -> unit 2s + h
+    const int rbase0 = ql * QG_DC, rbase1 = (32 + ql) * QG_DC;
+    const int sw = qg_swz(ql);                    // rows ql and 32+ql swizzle alike
+
+    f32x16 acc0, acc1;
+    if (rt0 < rt1) {
+        issue(rt0, 0);
+        stash(0, 0);
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int rt = rt0; rt < rt1; ++rt) {
+#pragma unroll
+        for (int kc = 0; kc < NK; ++kc) {
+            const bool last = kc == NK - 1;
+            const bool more = !last || rt + 1 < rt1;
+            if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
+            // keep the loads up here: their latency must overlap this step's matrix work
+            __builtin_amdgcn_sched_barrier(0);
+            if (kc == 0) {
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 c0 = *(const f32x4 *)&sm.c[buf][gg * 8 + h * 4];
+                    f32x4 c1 = *(const f32x4 *)&sm.c[buf][32 + gg * 8 + h * 4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc0[4 * gg + e] = c0[e];
+                        acc1[4 * gg + e] = c1[e];
+                    }
+                }
+            }
+            const float *rb = &sm.r[buf][0];
+#pragma unroll
+            for (int s = 0; s < QG_NSLAB; ++s) {
+                const int u = ((2 * s + h) ^ sw) << 2;
+                f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+                f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+                const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+                }
+            }
+            if (last) {
+                float m2 = fminf(min16(acc0), min16(acc1));
+                if (__ballot(m2 <= st.tau_p)) {
+                    f32x16 blocks[2] = {acc0, acc1};
+                    select_rare<2, QCAP>(blocks, rt * QG_TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
+                }
+            }
+            if (more) stash(buf ^ 1, last ? 0 : kc + 1);
+            __syncthreads();
+            buf ^= 1;
+        }
     }
 }
 
@@ -494,6 +870,48 @@ hipError_t launch_tiles(const TileArgs &a, hipStream_t stream)
 {
     int64_t blocks = (int64_t)a.n_qtiles * a.S;
     hipLaunchKernelGGL(knn_tiles, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+size_t qres_lds_bytes(int dpad)
+{
+    return (size_t)TQ * (dpad + 4) * 4 + 4 * QR_RBUF * 4 + 4 * QR_HALF * 4 + 8 * 32 * QR_QCAP * 8 +
+           4 * 32 * 8 + 8 * 32 * 4 + 16;
+}
+
+hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream)
+{
+    static thread_local int configured_dev = -1;
+    size_t lds = qres_lds_bytes(a.dpad);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (configured_dev != dev) {
+        e = hipFuncSetAttribute((const void *)knn_tiles_qres, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)qres_lds_bytes(KNN_QRES_MAX_D));
+        if (e != hipSuccess) return e;
+        configured_dev = dev;
+    }
+    int64_t blocks = (int64_t)a.n_qtiles * a.S;
+    hipLaunchKernelGGL(knn_tiles_qres, dim3((unsigned)blocks), dim3(512), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
+{
+    int64_t blocks = (int64_t)a.n_qtiles * a.S;
+    dim3 grid((unsigned)blocks), block(256);
+    switch (a.dpad) {
+    case 32: hipLaunchKernelGGL(knn_tiles_qreg<32>, grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL(knn_tiles_qreg<64>, grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL(knn_tiles_qreg<96>, grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL(knn_tiles_qreg<128>, grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL(knn_tiles_qreg<160>, grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL(knn_tiles_qreg<192>, grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL(knn_tiles_qreg<224>, grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL(knn_tiles_qreg<256>, grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -65,23 +65,25 @@ def _sample_rows(n, count, seed):
     (2, 5, 1, "sqeuclidean"),
     (70, 3, 69, "cosine"),
 ])
-def test_build_small(n, d, k, metric):
-    _say(f"  build n={n} d={d} k={k} {metric}")
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_build_small(n, d, k, metric, variant):
+    _say(f"  build n={n} d={d} k={k} {metric} variant={variant}")
     X = workloads.gaussian(n, d, seed=1000 + n + d)
-    res = knn_build(X.cuda(), k, metric)
+    res = knn_build(X.cuda(), k, metric, variant=variant)
     torch.cuda.synchronize()
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("splits", [1, 3, 16])
 @pytest.mark.parametrize("rescore", [1, 2])
-def test_split_reference_range_and_rescore(splits, rescore):
+def test_split_reference_range_and_rescore(splits, rescore, variant):
     """Partial lists from several reference slices merge to the same answer; the answer
     without the re-score still meets the tolerance."""
     n, d, k = 2100, 32, 12
     _say(f"  splits={splits} rescore={rescore}")
     X = workloads.mixture(n, d, 8, seed=77)
-    res = knn_build(X.cuda(), k, "sqeuclidean", r_splits=splits, rescore=rescore)
+    res = knn_build(X.cuda(), k, "sqeuclidean", r_splits=splits, rescore=rescore, variant=variant)
     torch.cuda.synchronize()
     _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", res.idx.cpu().numpy(),
                 res.dist.cpu().numpy())
@@ -94,7 +96,8 @@ def test_split_reference_range_and_rescore(splits, rescore):
     (1, 513, 512, "cosine"),
     (640, 200, -1, "sqeuclidean"),
 ])
-def test_search_small(nq, nr, off, metric):
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_search_small(nq, nr, off, metric, variant):
     d, k = 24, 9
     _say(f"  search nq={nq} nr={nr} self_offset={off} {metric}")
     R = workloads.gaussian(nr, d, seed=5 + nr)
@@ -104,7 +107,7 @@ def test_search_small(nq, nr, off, metric):
     else:
         Q = workloads.gaussian(nq, d, seed=6 + nq)
         self_idx = None
-    res = knn_search(Q.cuda(), R.cuda(), k, metric, self_offset=off)
+    res = knn_search(Q.cuda(), R.cuda(), k, metric, self_offset=off, variant=variant)
     torch.cuda.synchronize()
     o_idx, o_dist, o_next = oracle.search(Q.numpy(), R.numpy(), k, metric, self_idx=self_idx)
     rep = compare.check(Q.numpy(), R.numpy(), metric, o_idx, o_dist, o_next,
@@ -125,10 +128,11 @@ def test_search_equals_build():
 # ---------------------------------------------------------------------------
 # exact cases: ties must go to the lower index, bit-exact distances
 # ---------------------------------------------------------------------------
-def test_lattice_exact():
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_lattice_exact(variant):
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
-    res = knn_build(X.cuda(), k)
+    res = knn_build(X.cuda(), k, variant=variant)
     torch.cuda.synchronize()
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", gi, gd, strict=True)
@@ -136,11 +140,12 @@ def test_lattice_exact():
     assert gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("metric", ["sqeuclidean", "cosine"])
-def test_all_equidistant(metric):
+def test_all_equidistant(metric, variant):
     n, k = 200, 17
     X = torch.eye(n, dtype=torch.float32)
-    res = knn_build(X.cuda(), k, metric)
+    res = knn_build(X.cuda(), k, metric, variant=variant)
     torch.cuda.synchronize()
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     for i in (0, 1, 16, 17, 18, 127, 128, 199):
@@ -149,10 +154,11 @@ def test_all_equidistant(metric):
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, gi, gd, strict=True)
 
 
-def test_duplicate_rows():
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_duplicate_rows(variant):
     base = workloads.gaussian(300, 20, seed=9)
     X = base.repeat_interleave(2, dim=0).contiguous()
-    res = knn_build(X.cuda(), 4)
+    res = knn_build(X.cuda(), 4, variant=variant)
     torch.cuda.synchronize()
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     assert np.array_equal(gi[:, 0], np.arange(600) ^ 1)
@@ -162,10 +168,11 @@ def test_duplicate_rows():
     _check_rows(X.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
 
 
-def test_deterministic():
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_deterministic(variant):
     X = workloads.mixture(3000, 64, 16, seed=4).cuda()
-    a = knn_build(X, 10)
-    b = knn_build(X, 10)
+    a = knn_build(X, 10, variant=variant)
+    b = knn_build(X, 10, variant=variant)
     torch.cuda.synchronize()
     assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
 
@@ -199,10 +206,11 @@ def test_device_error_paths():
 # the benchmark configurations at full size (oracle on sampled rows where the full
 # oracle would take hours)
 # ---------------------------------------------------------------------------
-def test_config1_full():
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_config1_full(variant):
     w = workloads.config(1)
-    _say(f"  {w.name}")
-    res = knn_build(w.R.cuda(), w.k, w.metric)
+    _say(f"  {w.name} variant={variant}")
+    res = knn_build(w.R.cuda(), w.k, w.metric, variant=variant)
     torch.cuda.synchronize()
     _check_rows(w.R.numpy(), np.arange(w.n), 0, w.k, w.metric, res.idx.cpu().numpy(),
                 res.dist.cpu().numpy())
