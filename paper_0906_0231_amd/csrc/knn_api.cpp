@@ -33,6 +33,8 @@ struct Plan {
     bool rcopy;     // references need a scaled / padded copy
     bool qres;      // query tile resident in LDS (knn_tiles_qres): two lists per slice
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
+    bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
+    int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
     int32_t nlists; // partial lists per query
     size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
 };
@@ -46,8 +48,19 @@ int32_t list_capacity(int32_t k)
 
 // Sizes are assumed validated.  r_splits == 0 picks a split count that gives
 // the 256 compute units at least two workgroups each when query tiles are few.
+// Symmetric schedule: rows per block.  At least 512 disjoint pairs per round keep two
+// workgroups on every CU, so B = n/1024 rounded down to a multiple of the query tile;
+// never below one tile.
+int32_t pair_block_rows(int64_t n)
+{
+    int64_t b = n / 1024 / KNN_TILE * KNN_TILE;
+    if (b < KNN_TILE) b = KNN_TILE;
+    if (b > 8192) b = 8192;
+    return (int32_t)b;
+}
+
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
-               int32_t r_splits, int32_t variant, Plan &p)
+               int32_t r_splits, int32_t variant, int32_t symmetric, Plan &p)
 {
     p.self = self;
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
@@ -60,6 +73,12 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
     p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
     p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
+    // symmetric schedule: only for knn_build, only with the register-resident kernel;
+    // by default only when a round has enough pairs to fill the GPU
+    p.tri = self && p.qreg && symmetric != 2 && (symmetric == 1 || nr >= 1024 * KNN_TILE);
+    p.B = pair_block_rows(nr);
+    p.NB = (int32_t)((nr + p.B - 1) / p.B);
+    p.NBp = p.NB + (p.NB & 1);
     const int32_t per_slice = p.qres ? 2 : 1;
     int32_t smax = KNN_FIN_MAX / (p.kcap * per_slice);
     if (smax > p.n_rtiles) smax = p.n_rtiles;
@@ -67,6 +86,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     if (S <= 0) S = p.n_qtiles >= 512 ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
     if (S > smax) S = smax;
     if (S < 1) S = 1;
+    if (p.tri) S = 1;
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
     p.nlists = p.S * per_slice;
@@ -80,7 +100,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.off_c = o;
     o = align_up(o + (size_t)p.n_cpad * sizeof(float), 256);
     p.off_sq = o;
-    o = align_up(o + (size_t)nq * sizeof(float), 256);
+    o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;   // + one scalar (max c_j)
     p.off_lists = o;
     o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
@@ -142,7 +162,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         return KNN_EINVAL;
 
     Plan p;
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, p);
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, p);
     if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
     if (workspace_bytes < p.total) return KNN_ENOMEM;
 
@@ -181,28 +201,72 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     ev.record(1, stream);
 
     // ---- fused distance + selection ----
-    TileArgs t;
-    t.Qp = qp;
-    t.Rp = p.rcopy ? rp : R;
-    t.cR = cr;
-    t.lists = lists;
-    t.ldq = p.dpad;
-    t.ldr = p.rcopy ? p.dpad : d;
-    t.nq = nq;
-    t.nr = nr;
-    t.nq_pad = p.nq_pad;
-    t.self_offset = self_offset;
-    t.dpad = p.dpad;
-    t.k = k;
-    t.kcap = p.kcap;
-    t.n_qtiles = p.n_qtiles;
-    t.n_rtiles = p.n_rtiles;
-    t.S = p.S;
-    t.rt_per_split = p.rt_per_split;
-    e = p.qreg ? launch_tiles_qreg(t, stream) : p.qres ? launch_tiles_qres(t, stream) : launch_tiles(t, stream);
-    if (e != hipSuccess) {
-        set_error(p.qreg ? "knn_tiles_qreg" : p.qres ? "knn_tiles_qres" : "knn_tiles", e);
-        return KNN_EDEVICE;
+    int32_t launches = 1;
+    int64_t pairs_computed = p.nq_pad * p.n_cpad;
+    if (p.tri) {
+        // one launch for the diagonal blocks, then one per round of disjoint block pairs
+        float *cmax = (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
+        e = launch_reduce_max(cr, nr, cmax, stream);
+        if (e != hipSuccess) { set_error("reduce_max", e); return KNN_EDEVICE; }
+        ev.record(1, stream);
+        PairArgs pa;
+        pa.Qp = qp;
+        pa.Rp = p.rcopy ? rp : R;
+        pa.cR = cr;
+        pa.cmax = cmax;
+        pa.lists = lists;
+        pa.ldq = p.dpad;
+        pa.ldr = p.rcopy ? p.dpad : d;
+        pa.n = nr;
+        pa.dpad = p.dpad;
+        pa.k = k;
+        pa.kcap = p.kcap;
+        pa.metric = (int32_t)metric;
+        pa.B = p.B;
+        pa.NB = p.NB;
+        pa.NBp = p.NBp;
+        pa.round = -1;
+        e = launch_pairs_qreg(pa, p.NB, stream);
+        if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
+        for (int32_t r = 0; r + 1 < p.NBp; ++r) {
+            pa.round = r;
+            e = launch_pairs_qreg(pa, p.NBp / 2, stream);
+            if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
+        }
+        launches = p.NBp;
+        // padded rows actually contracted: queries in tiles of 128, references in tiles of 64
+        const int64_t last = nr - (int64_t)(p.NB - 1) * p.B;
+        const int64_t lq = (last + KNN_TILE - 1) / KNN_TILE * KNN_TILE, lr = (last + 63) / 64 * 64;
+        const int64_t full = p.NB - 1;
+        pairs_computed = full * (int64_t)p.B * p.B + lq * lr                  // diagonal blocks
+                         + full * (full - 1) / 2 * (int64_t)p.B * p.B;       // pairs of full blocks
+        // pairs with the ragged last block: it is the query side when it is `ba` of the circle
+        // method; count the larger of the two paddings (an upper bound within 64 rows per pair)
+        pairs_computed += full * (int64_t)p.B * (lq > lr ? lq : lr);
+    } else {
+        TileArgs t;
+        t.Qp = qp;
+        t.Rp = p.rcopy ? rp : R;
+        t.cR = cr;
+        t.lists = lists;
+        t.ldq = p.dpad;
+        t.ldr = p.rcopy ? p.dpad : d;
+        t.nq = nq;
+        t.nr = nr;
+        t.nq_pad = p.nq_pad;
+        t.self_offset = self_offset;
+        t.dpad = p.dpad;
+        t.k = k;
+        t.kcap = p.kcap;
+        t.n_qtiles = p.n_qtiles;
+        t.n_rtiles = p.n_rtiles;
+        t.S = p.S;
+        t.rt_per_split = p.rt_per_split;
+        e = p.qreg ? launch_tiles_qreg(t, stream) : p.qres ? launch_tiles_qres(t, stream) : launch_tiles(t, stream);
+        if (e != hipSuccess) {
+            set_error(p.qreg ? "knn_tiles_qreg" : p.qres ? "knn_tiles_qres" : "knn_tiles", e);
+            return KNN_EDEVICE;
+        }
     }
     ev.record(2, stream);
 
@@ -238,9 +302,9 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         (void)hipEventElapsedTime(&pr->ms_main, ev.e[1], ev.e[2]);
         (void)hipEventElapsedTime(&pr->ms_finalize, ev.e[2], ev.e[3]);
         (void)hipEventElapsedTime(&pr->ms_total, ev.e[0], ev.e[3]);
-        pr->main_launches = 1;
-        pr->symmetric = 0;
-        pr->pairs_computed = p.nq_pad * p.n_cpad;
+        pr->main_launches = launches;
+        pr->symmetric = p.tri ? 1 : 0;
+        pr->pairs_computed = pairs_computed;
     }
     return KNN_OK;
 }
@@ -288,7 +352,8 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     if (symmetric && nr < 2) return 0;
     if (check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1) != KNN_OK) return 0;
     Plan p;
-    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, opt ? opt->variant : 0, p);
+    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, opt ? opt->variant : 0,
+              opt ? opt->symmetric : 0, p);
     return p.total;
 }
 

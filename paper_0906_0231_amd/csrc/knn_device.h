@@ -42,6 +42,21 @@ struct TileArgs {
     int32_t n_qtiles, n_rtiles, S, rt_per_split;
 };
 
+// symmetric schedule: one launch = one round of block pairs (round < 0: the diagonal blocks)
+struct PairArgs {
+    const float *Qp;   // [n, ldq] query-side copy
+    const float *Rp;   // [n, ldr] reference-side rows
+    const float *cR;   // [ceil(n/128)*128]
+    const float *cmax; // device scalar: max_j c_j
+    u64 *lists;        // [ceil(n/128)*128, kcap]
+    int64_t ldq, ldr, n;
+    int32_t dpad, k, kcap, metric;
+    int32_t B;         // rows per block, multiple of 128
+    int32_t NB;        // number of blocks
+    int32_t NBp;       // NB rounded up to even
+    int32_t round;     // 0 .. NBp-2, or -1
+};
+
 enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3 };
 
 struct FinArgs {
@@ -60,6 +75,8 @@ hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
+hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream);
+hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream);
 
 }  // namespace knn
 #endif

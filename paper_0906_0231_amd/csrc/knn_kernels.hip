@@ -736,6 +736,289 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// knn_pairs_qreg<DPAD>: the symmetric schedule (Sect. 3-4 of the paper: delta(u,v) =
+// delta(v,u), so each unordered pair is evaluated once and pushed to both rows).
+//
+// Rows are cut into blocks of B.  One workgroup evaluates one unordered pair of blocks
+// (a, b): every tile is used in both directions -- "direct": rows of a are the queries
+// (lane axis), rows of b the references; "mirror": the same accumulator, read along the
+// register axis, is a candidate for the list of reference row j with the query as its
+// neighbour.  A launch is one round of a round-robin tournament over the blocks: its
+// pairs are disjoint, so within a launch every row's list is touched by exactly one
+// workgroup and ownership changes hands only at kernel boundaries.  No locks, no
+// atomics on global memory; as in the paper the only synchronisation between
+// workgroups is the return to the host queue (Sect. 2), and the work per launch is
+// balanced by construction where the paper uses its zig-zag assignment (Sect. 4).
+// round < 0 is the launch for the diagonal blocks (a, a): direct only, whole block.
+//
+// Mirror values: the accumulator is p = c_j + sum(Q'[q] R[j]); the row-j value of the
+// same pair is p' = (p - c_j) + c_q.  The common-case test must not cost a pass over
+// the registers per row, so it is one-sided: with T_j >= tau'_j + c_j + slack (the
+// row's current k-th best plus its norm, rounded up generously) the lane keeps
+// max_r (T_r - p_r) and compares it once with its own c_q; anything that could pass
+// the exact test passes this one.  Survivors are tested exactly, queued per row in LDS
+// and merged after the step barrier by the wave that serves the row.
+// ---------------------------------------------------------------------------
+constexpr int MQCAP = 8;                          // mirror queue slots per reference row of the tile
+
+struct __attribute__((aligned(16))) PairSmem {
+    float r[2][QG_RBUF];
+    float c[2][QG_TR];
+    float T[2][QG_TR];                            // one-sided mirror thresholds
+    u64 mtau[2][QG_TR];                           // exact k-th best keys of the tile's reference rows
+    u64 cq[4][32][QCAP];
+    u64 mq[QG_TR][MQCAP];
+    uint32_t cnt[4][32];
+    uint32_t mcnt[QG_TR];
+    uint32_t mflag;                               // bit 0: some mirror queue is non-empty, bit 1: one overflowed
+};
+
+__device__ __forceinline__ float mirror_T(u64 tkey, float cj, float cmax, float abound)
+{
+    if (tkey == KEY_INF) return __builtin_inff();
+    if (tkey == 0ull) return -__builtin_inff();   // row past the end: nothing may pass
+    float t = ord2f((uint32_t)(tkey >> 32));
+    float slack = (fabsf(t) + cmax + abound) * 3.814697265625e-06f;   // 2^-18
+    return (t + cj) + slack + slack;
+}
+
+template <int DPAD>
+__global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
+{
+    constexpr int NK = DPAD / QG_DC;
+    constexpr int NS = DPAD / 8;
+    __shared__ PairSmem sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int h = lane >> 5;
+    const int ql = lane & 31;
+
+    // ---- which pair of blocks ----
+    int ba, bb;
+    const bool diag = a.round < 0;
+    if (diag) {
+        ba = bb = blockIdx.x;
+    } else {
+        const int M = a.NBp, p = blockIdx.x;       // circle method: M even, rounds 0..M-2
+        if (p == 0) {
+            ba = M - 1;
+            bb = a.round;
+        } else {
+            ba = (a.round + p) % (M - 1);
+            bb = (a.round - p + (M - 1)) % (M - 1);
+        }
+    }
+    if (ba >= a.NB || bb >= a.NB) return;          // the dummy block of an odd count (whole workgroup)
+    const int64_t qrow0 = (int64_t)ba * a.B, rrow0 = (int64_t)bb * a.B;
+    const int nq_rows = (int)min((int64_t)a.B, a.n - qrow0);
+    const int nr_rows = (int)min((int64_t)a.B, a.n - rrow0);
+    const int n_qt = (nq_rows + TQ - 1) / TQ;
+    const int n_rt = (nr_rows + QG_TR - 1) / QG_TR;
+    const float cmax = *a.cmax;
+    const float abound = a.metric == 1 ? 1.5f : 3.f * cmax;
+
+    if (lane < 32) sm.cnt[w][lane] = 0;
+    if (tid < QG_TR) sm.mcnt[tid] = 0;
+    if (tid == 0) sm.mflag = 0;
+
+    const int lrow = tid >> 3, lunit = tid & 7;
+    const int st_off = lrow * QG_DC + ((lunit ^ qg_swz(lrow)) << 2);
+    const int rbase0 = ql * QG_DC, rbase1 = (32 + ql) * QG_DC;
+    const int sw = qg_swz(ql);
+
+    f32x4 g0, g1;
+    float gc = 0.f;
+    u64 gmt = 0;
+    auto issue = [&](int rt, int kc) {
+        int64_t r0 = min(rrow0 + (int64_t)rt * QG_TR + lrow, a.n - 1);
+        int64_t r1 = min(rrow0 + (int64_t)rt * QG_TR + lrow + 32, a.n - 1);
+        g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
+        g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
+        if (kc == 0 && tid < QG_TR) {
+            int64_t row = rrow0 + (int64_t)rt * QG_TR + tid;     // < n_cpad: c is padded with +inf
+            gc = a.cR[row];
+            gmt = (!diag && row < a.n) ? a.lists[row * a.kcap + (a.k - 1)] : 0ull;
+        }
+    };
+    // staging buffers alternate per step; the per-tile arrays (c, T, mtau) alternate per
+    // tile (tb = tile parity), because a tile's mirror values are still needed after the
+    // next tile's first chunk has been staged
+    auto stash = [&](int buf, int kc, int tb) {
+        *(f32x4 *)&sm.r[buf][st_off] = g0;
+        *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
+        if (kc == 0 && tid < QG_TR) {
+            sm.c[tb][tid] = gc;
+            sm.mtau[tb][tid] = gmt;
+            sm.T[tb][tid] = mirror_T(gmt, gc, cmax, abound);
+        }
+    };
+
+    for (int qt = 0; qt < n_qt; ++qt) {
+        const int64_t qbase = qrow0 + (int64_t)qt * TQ;
+        const int64_t myq = qbase + 32 * w + ql;
+        const bool qvalid = myq < a.n;
+        u64 *Lw = a.lists + (qbase + 32 * w) * a.kcap;
+        if (diag)
+            for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        SelState st;
+        st.tau_key = qvalid ? Lw[(int64_t)ql * a.kcap + (a.k - 1)] : 0ull;
+        st.tau_p = !qvalid ? -__builtin_inff()
+                           : st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
+        st.selfj = (diag && qvalid) ? (int32_t)myq : -1;
+        st.Lw = Lw;
+        st.cq = &sm.cq[w][0][0];
+        st.cnt = &sm.cnt[w][0];
+        st.shared_tau = nullptr;
+        const float cq = qvalid ? a.cR[myq] : __builtin_inff();   // the query's own c, for the mirror values
+
+        f32x4 qreg[NS];
+        {
+            const float *qrow = a.Qp + min(myq, a.n - 1) * a.ldq + h * 4;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) qreg[s] = *(const f32x4 *)(qrow + s * 8);
+        }
+
+        f32x16 acc0, acc1;
+        issue(0, 0);
+        stash(0, 0, 0);
+        __syncthreads();
+
+        // Mirror candidates of one tile: scan (cheap one-sided test per register, exact test
+        // for survivors, per-row queue), flagged in sm.mflag.  Entries taken are overwritten
+        // with +inf in the accumulators so that a re-scan after an overflow skips them.
+        auto mirror_scan = [&](int rt) {
+            const int buf = rt & 1;
+            float dmax = -__builtin_inff();
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 t0 = *(const f32x4 *)&sm.T[buf][gg * 8 + h * 4];
+                f32x4 t1 = *(const f32x4 *)&sm.T[buf][32 + gg * 8 + h * 4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dmax = fmaxf(dmax, t0[e] - acc0[4 * gg + e]);
+                    dmax = fmaxf(dmax, t1[e] - acc1[4 * gg + e]);
+                }
+            }
+            if (__ballot(qvalid && dmax >= cq) == 0) return;
+            uint32_t fl = 0;
+#pragma unroll 1
+            for (int t = 0; t < 2; ++t) {
+                f32x16 v = t == 0 ? acc0 : acc1;
+#pragma unroll 1
+                for (int r = 0; r < 16; ++r) {
+                    const int m = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    float p = v[r];
+                    bool c = qvalid && sm.T[buf][m] - p >= cq;
+                    if (__ballot(c)) {
+                        if (c) {
+                            float p2 = (p - sm.c[buf][m]) + cq;          // this pair seen from row m
+                            u64 key = make_key(p2, (int32_t)myq);
+                            if (key < sm.mtau[buf][m]) {
+                                uint32_t slot = atomicAdd(&sm.mcnt[m], 1u);
+                                if (slot < (uint32_t)MQCAP) {
+                                    sm.mq[m][slot] = key;
+                                    p = __builtin_inff();
+                                    fl |= 1u;
+                                } else {
+                                    fl |= 3u;
+                                }
+                            }
+                        }
+                        v[r] = p;
+                    }
+                }
+                if (t == 0) acc0 = v; else acc1 = v;
+            }
+            if (fl) atomicOr(&sm.mflag, fl);
+        };
+        // After the barrier that ends a tile: if any mirror queue holds candidates, the waves
+        // merge them (wave w serves rows 16w..16w+15 of the tile), and after an overflow the
+        // tile is scanned again against the tightened thresholds.  Workgroup-uniform.
+        auto mirror_service = [&](int rt) {
+            const int buf = rt & 1;
+            while (true) {
+                const uint32_t fl = *(volatile uint32_t *)&sm.mflag;
+                if (fl == 0) break;
+                uint32_t mc = lane < QG_TR ? *(volatile uint32_t *)&sm.mcnt[lane] : 0u;
+                u64 pend = __ballot(mc > 0) & (0xffffull << (16 * w));
+                while (pend) {
+                    int m = __builtin_ctzll(pend);
+                    pend &= pend - 1;
+                    int nc = min((int)__builtin_amdgcn_readlane(mc, m), MQCAP);
+                    int64_t row = rrow0 + (int64_t)rt * QG_TR + m;
+                    u64 nt = merge_one(a.lists + row * a.kcap, a.kcap, a.k, &sm.mq[m][0], nc, lane);
+                    if (lane == 0) {
+                        sm.mtau[buf][m] = nt;
+                        sm.T[buf][m] = mirror_T(nt, sm.c[buf][m], cmax, abound);
+                        sm.mcnt[m] = 0;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                __syncthreads();
+                if (tid == 0) sm.mflag = 0;
+                __syncthreads();
+                if (!(fl & 2u)) break;
+                mirror_scan(rt);
+                __syncthreads();
+            }
+        };
+
+        int buf = 0;
+        for (int rt = 0; rt < n_rt; ++rt) {
+#pragma unroll
+            for (int kc = 0; kc < NK; ++kc) {
+                const bool last = kc == NK - 1;
+                const bool more = !last || rt + 1 < n_rt;
+                if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (kc == 0) {
+                    if (!diag && rt > 0) mirror_service(rt - 1);
+#pragma unroll
+                    for (int gg = 0; gg < 4; ++gg) {
+                        f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
+                        f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            acc0[4 * gg + e] = c0[e];
+                            acc1[4 * gg + e] = c1[e];
+                        }
+                    }
+                }
+                const float *rb = &sm.r[buf][0];
+#pragma unroll
+                for (int s = 0; s < QG_NSLAB; ++s) {
+                    const int u = ((2 * s + h) ^ sw) << 2;
+                    f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+                    f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+                    const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+                    }
+                }
+                if (last) {
+                    float m2 = fminf(min16(acc0), min16(acc1));
+                    if (__ballot(m2 <= st.tau_p)) {
+                        f32x16 blocks[2] = {acc0, acc1};
+                        select_rare<2, QCAP>(blocks, (int32_t)(rrow0 + (int64_t)rt * QG_TR) + 4 * h, a.n,
+                                             a.kcap, a.k, st, lane);
+                    }
+                    if (!diag) mirror_scan(rt);
+                }
+                if (more) stash(buf ^ 1, last ? 0 : kc + 1, (rt + 1) & 1);
+                __syncthreads();
+                buf ^= 1;
+            }
+        }
+        if (!diag) mirror_service(n_rt - 1);
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
 // finalize_rows: one wave per query.
 // ---------------------------------------------------------------------------
 constexpr int FIN_MAX = KNN_FIN_MAX;   // most keys one query can bring (S * kcap)
@@ -910,6 +1193,45 @@ hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
     case 192: hipLaunchKernelGGL(knn_tiles_qreg<192>, grid, block, 0, stream, a); break;
     case 224: hipLaunchKernelGGL(knn_tiles_qreg<224>, grid, block, 0, stream, a); break;
     case 256: hipLaunchKernelGGL(knn_tiles_qreg<256>, grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// largest c_j (squared norm) of the data set: scale of the mirror slack
+__global__ __launch_bounds__(1024) void reduce_max(const float *c, int64_t n, float *out)
+{
+    __shared__ float part[16];
+    float m = 0.f;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, c[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 16; ++i) m = fmaxf(m, part[i]);
+        *out = m;
+    }
+}
+
+hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(reduce_max, dim3(1), dim3(1024), 0, stream, c, n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
+{
+    dim3 grid((unsigned)blocks), block(256);
+    switch (a.dpad) {
+    case 32: hipLaunchKernelGGL(knn_pairs_qreg<32>, grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL(knn_pairs_qreg<64>, grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL(knn_pairs_qreg<96>, grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL(knn_pairs_qreg<128>, grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL(knn_pairs_qreg<160>, grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL(knn_pairs_qreg<192>, grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL(knn_pairs_qreg<224>, grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL(knn_pairs_qreg<256>, grid, block, 0, stream, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -116,6 +116,65 @@ def test_search_small(nq, nr, off, metric, variant):
     assert rep.ok, str(rep)
 
 
+# ---------------------------------------------------------------------------
+# symmetric schedule (each unordered block pair evaluated once, both rows updated)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,k,metric", [
+    (1500, 64, 10, "sqeuclidean"),
+    (777, 37, 5, "sqeuclidean"),
+    (1000, 48, 20, "cosine"),
+    (600, 130, 100, "sqeuclidean"),
+    (515, 16, 64, "cosine"),
+    (300, 1, 7, "sqeuclidean"),
+    (129, 8, 128, "sqeuclidean"),
+    (2, 5, 1, "sqeuclidean"),
+    (2100, 256, 12, "sqeuclidean"),
+    (4096, 64, 10, "sqeuclidean"),
+])
+def test_build_symmetric(n, d, k, metric):
+    _say(f"  symmetric build n={n} d={d} k={k} {metric}")
+    X = workloads.gaussian(n, d, seed=2000 + n + d)
+    res = knn_build(X.cuda(), k, metric, symmetric=1, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.symmetric == 1 and res.profile.main_launches >= 2
+    _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+def test_symmetric_equals_full_square():
+    """Both schedules select from the same fp32 products; on data without near-ties the
+    answers are identical."""
+    X = workloads.mixture(5000, 96, 12, seed=31).cuda()
+    a = knn_build(X, 15, symmetric=1)
+    b = knn_build(X, 15, symmetric=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+    c = knn_build(X, 15, symmetric=1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, c.idx) and torch.equal(a.dist, c.dist)     # and deterministic
+
+
+def test_symmetric_exact_ties():
+    n, k = 2000, 6
+    X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
+    res = knn_build(X.cuda(), k, symmetric=1)
+    torch.cuda.synchronize()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", res.idx.cpu().numpy(),
+                res.dist.cpu().numpy(), strict=True)
+    E = torch.eye(200, dtype=torch.float32)
+    for metric in ("sqeuclidean", "cosine"):
+        res = knn_build(E.cuda(), 17, metric, symmetric=1)
+        torch.cuda.synchronize()
+        _check_rows(E.numpy(), np.arange(200), 0, 17, metric, res.idx.cpu().numpy(),
+                    res.dist.cpu().numpy(), strict=True)
+    base = workloads.gaussian(300, 20, seed=9)
+    D = base.repeat_interleave(2, dim=0).contiguous()
+    res = knn_build(D.cuda(), 4, symmetric=1)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    assert np.array_equal(gi[:, 0], np.arange(600) ^ 1) and np.all(gd[:, 0] == 0.0)
+    _check_rows(D.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
+
+
 def test_search_equals_build():
     """knn_build(X) == knn_search(X, X, self_offset=0), bit for bit."""
     X = workloads.gaussian(900, 40, seed=3).cuda()
