@@ -21,6 +21,14 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
 
+# HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md).
+# Keyed by (workload, schedule); reported per launch next to `achieved`.
+MEASURED_TRAFFIC_BYTES_PER_STEP = {
+    ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.65e12 + 1.64e10,
+    ("c3_lowrank32_n1048576_d256_k10", "full-square"): 6.78e12 + 8.57e9,
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -31,6 +39,7 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query-resident")
+    ap.add_argument("--block-rows", type=int, default=0, help="symmetric schedule: rows per block")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -69,7 +78,8 @@ def main() -> int:
     def step(profile):
         if w.symmetric:
             return knn_build(R, k, w.metric, symmetric=args.symmetric, variant=args.variant,
-                             profile=profile, workspace=ws, out=(idx, dist))
+                             block_rows=args.block_rows, profile=profile, workspace=ws,
+                             out=(idx, dist))
         return knn_search(Q, R, k, w.metric, self_offset=w.self_offset, variant=args.variant,
                           profile=profile, workspace=ws, out=(idx, dist))
 
@@ -115,9 +125,14 @@ def main() -> int:
                    "datagen_s": round(gen_s, 2)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                     "traffic": None, "kernel": "knn_tiles",
+                     "traffic": None, "kernel": "knn_pairs_qreg" if symmetric else "knn_tiles",
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
+
+    tkey = (w.name, out["config"]["schedule"])
+    if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3) and not args.block_rows:
+        out["roofline"]["traffic"] = MEASURED_TRAFFIC_BYTES_PER_STEP[tkey] / launches
+        out["roofline"]["traffic_unit"] = "bytes per launch (offline rocprofv3 FETCH_SIZE+WRITE_SIZE)"
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)

@@ -82,6 +82,10 @@ typedef struct {
                            1 = streaming: both operands through LDS chunk by chunk, any d.
                            2 = query tile resident in LDS, 3 = query tile resident in
                            registers; both need d <= 256 and fall back to 1 otherwise */
+    int32_t block_rows; /* symmetric schedule only.  0 = auto (n/1024 rounded down to a multiple
+                           of 128, at least 128).  Rows per block; rounded up to a multiple
+                           of 128.  A round launches floor(ceil(n/block_rows)/2) workgroups */
+    int32_t reserved;   /* must be 0 */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
                            kernels with events, waits for them and fills this in */
 } knn_options_t;

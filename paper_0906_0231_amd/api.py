@@ -37,6 +37,7 @@ class KnnProfile(ctypes.Structure):
 class KnnOptions(ctypes.Structure):
     _fields_ = [("symmetric", ctypes.c_int32), ("rescore", ctypes.c_int32),
                 ("r_splits", ctypes.c_int32), ("variant", ctypes.c_int32),
+                ("block_rows", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("profile", ctypes.POINTER(KnnProfile))]
 
 
@@ -94,9 +95,11 @@ def _metric(metric) -> int:
     return METRICS[metric] if isinstance(metric, str) else int(metric)
 
 
-def _options(symmetric: int, rescore: int, r_splits: int, profile: bool, variant: int = 0):
+def _options(symmetric: int, rescore: int, r_splits: int, profile: bool, variant: int = 0,
+             block_rows: int = 0):
     opt = KnnOptions()
     opt.symmetric, opt.rescore, opt.r_splits, opt.variant = symmetric, rescore, r_splits, variant
+    opt.block_rows = block_rows
     prof = KnnProfile() if profile else None
     if prof is not None:
         opt.profile = ctypes.pointer(prof)
@@ -129,8 +132,8 @@ class KnnResult:
 
 
 def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int = 0,
-              rescore: int = 0, r_splits: int = 0, variant: int = 0, profile: bool = False,
-              workspace: Optional[torch.Tensor] = None,
+              rescore: int = 0, r_splits: int = 0, variant: int = 0, block_rows: int = 0,
+              profile: bool = False, workspace: Optional[torch.Tensor] = None,
               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
     """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h."""
     lib = load_library()
@@ -140,7 +143,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
         idx, dist = out if out is not None else (
             torch.empty((n, k), dtype=torch.int32, device=X.device),
             torch.empty((n, k), dtype=torch.float32, device=X.device))
-        opt, prof = _options(symmetric, rescore, r_splits, profile, variant)
+        opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows)
         if workspace is None:
             nbytes = int(lib.knn_workspace_bytes_ex(n, n, d, k, _metric(metric), 1, ctypes.byref(opt)))
             workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)

@@ -60,7 +60,7 @@ int32_t pair_block_rows(int64_t n)
 }
 
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
-               int32_t r_splits, int32_t variant, int32_t symmetric, Plan &p)
+               int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, Plan &p)
 {
     p.self = self;
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
@@ -76,7 +76,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     // symmetric schedule: only for knn_build, only with the register-resident kernel;
     // by default only when a round has enough pairs to fill the GPU
     p.tri = self && p.qreg && symmetric != 2 && (symmetric == 1 || nr >= 1024 * KNN_TILE);
-    p.B = pair_block_rows(nr);
+    p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr);
     p.NB = (int32_t)((nr + p.B - 1) / p.B);
     p.NBp = p.NB + (p.NB & 1);
     const int32_t per_slice = p.qres ? 2 : 1;
@@ -158,11 +158,11 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
     if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
-        o.variant < 0 || o.variant > 3)
+        o.variant < 0 || o.variant > 3 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
         return KNN_EINVAL;
 
     Plan p;
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, p);
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
     if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
     if (workspace_bytes < p.total) return KNN_ENOMEM;
 
@@ -353,7 +353,7 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     if (check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1) != KNN_OK) return 0;
     Plan p;
     make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, opt ? opt->variant : 0,
-              opt ? opt->symmetric : 0, p);
+              opt ? opt->symmetric : 0, opt ? opt->block_rows : 0, p);
     return p.total;
 }
 
