@@ -55,6 +55,10 @@ def _load():
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
             ctypes.c_void_p]
+        lib.knn_oracle_select.restype = ctypes.c_int32
+        lib.knn_oracle_select.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p,
+                                          ctypes.c_void_p]
         lib.knn_oracle_threads.restype = ctypes.c_int32
         lib.knn_oracle_threads.argtypes = []
         _lib = lib
@@ -141,3 +145,17 @@ def pair_dists(Q, R, idx, metric: str = "sqeuclidean") -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"knn_oracle_pair_dists failed with code {rc}")
     return out
+
+
+def select(A, k: int):
+    """k smallest entries of every row of A (Sect. 6 of the paper), ascending, ties to the
+    lower column.  Returns (idx int32 [m,k], val float32 [m,k])."""
+    lib = _load()
+    A = _f32(A)
+    m, n = A.shape
+    idx = np.empty((m, k), dtype=np.int32)
+    val = np.empty((m, k), dtype=np.float32)
+    rc = lib.knn_oracle_select(A.ctypes.data, m, n, n, k, idx.ctypes.data, val.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"knn_oracle_select failed with code {rc}")
+    return idx, val

@@ -124,6 +124,45 @@ int32_t knn_oracle_pair_dists(const float *Q, int64_t nq, const float *R, int64_
     return 0;
 }
 
+/*
+ * Batched partial sort (paper, Sect. 6 "Phase 2: taking k smallest elements", and its
+ * closing remark in Sect. 8 that the simultaneous partial sort of many arrays matters on
+ * its own): for every row of A[m, n] (row stride lda), the k smallest entries in
+ * non-decreasing order with their column numbers, ties to the lower column.
+ * Written as the definition: full sort of the row by (value, column), first k.
+ */
+int32_t knn_oracle_select(const float *A, int64_t m, int64_t n, int64_t lda, int32_t k,
+                          int32_t *idx, float *val)
+{
+    if (!A || !idx || !val) return 1;
+    if (m < 1 || n < 1 || lda < n || k < 1 || k > n) return 1;
+    if (n > (int64_t)INT32_MAX) return 1;
+    int32_t failed = 0;
+#pragma omp parallel
+    {
+        pair_t *row = (pair_t *)malloc((size_t)n * sizeof(pair_t));
+        if (!row) {
+#pragma omp atomic write
+            failed = 2;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t i = 0; i < m; ++i) {
+            if (!row) continue;
+            for (int64_t j = 0; j < n; ++j) {
+                row[j].dist = (double)A[(size_t)i * (size_t)lda + (size_t)j];
+                row[j].idx = (int32_t)j;
+            }
+            qsort(row, (size_t)n, sizeof(pair_t), pair_less);
+            for (int32_t r = 0; r < k; ++r) {
+                idx[(size_t)i * (size_t)k + (size_t)r] = row[r].idx;
+                val[(size_t)i * (size_t)k + (size_t)r] = (float)row[r].dist;
+            }
+        }
+        free(row);
+    }
+    return failed;
+}
+
 int32_t knn_oracle_threads(void)
 {
 #ifdef _OPENMP

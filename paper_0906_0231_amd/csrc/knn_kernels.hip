@@ -18,12 +18,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "knn_device.h"
 
 namespace knn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_ptr;
 
 // ---------------------------------------------------------------------------
 // keys: (distance, index) packed so that unsigned 64-bit order == (dist, idx) order
@@ -159,8 +163,11 @@ __device__ __forceinline__ float min16(const f32x16 &v)
 // (only the first k entries are live).  Whole wave; returns the new k-th key.
 __device__ __forceinline__ u64 merge_one(u64 *L, int kcap, int k, const u64 *cq, int nc, int lane)
 {
-    u64 e0 = lane < kcap ? L[lane] : KEY_INF;
-    u64 e1 = lane + 64 < kcap ? L[lane + 64] : KEY_INF;
+    // device-scope loads: the list may have been written by another wave of this CU since
+    // this wave last looked at the same cache line; take it from the L2, not the vector L1
+    u64 e0 = lane < kcap ? __hip_atomic_load(&L[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : KEY_INF;
+    u64 e1 = lane + 64 < kcap ? __hip_atomic_load(&L[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : KEY_INF;
     u64 cm = lane < nc ? cq[lane] : KEY_INF;
     int inc0 = 0, inc1 = 0, crank = 0, cbase = 0;
     for (int i = 0; i < nc; ++i) {
@@ -186,6 +193,96 @@ __device__ __forceinline__ u64 merge_one(u64 *L, int kcap, int k, const u64 *cq,
     return readlane64(tk, src);
 }
 
+__device__ __forceinline__ u64 shfl64(u64 v, int src)
+{
+    uint32_t lo = __shfl((uint32_t)v, src, 64);
+    uint32_t hi = __shfl((uint32_t)(v >> 32), src, 64);
+    return ((u64)hi << 32) | lo;
+}
+
+// Several merges at once: the wave is cut into groups of gsz = kcap lanes (kcap <= 64) and
+// every group rank-merges one queue into one list, exactly as merge_one does with the
+// whole wave.  A merge is a dependent chain load -> rank -> store of L2 latency, so doing
+// 64/kcap of them per round trip is what makes the rare path cheap for small k.
+//   L, cq, nc: per lane, already those of the lane's group (L == nullptr: group idle).
+// Returns, per lane, the new k-th key of its group's list (KEY_INF while not full).
+__device__ __forceinline__ u64 merge_multi(u64 *L, const u64 *cq, int nc, int gsz, int k, int lane)
+{
+    const int e = lane & (gsz - 1);
+    const int gbase = lane - e;
+    const u64 gmask = (gsz >= 64 ? ~0ull : ((1ull << gsz) - 1ull)) << gbase;
+    const bool act = L != nullptr;
+    u64 e0 = act ? __hip_atomic_load(&L[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : KEY_INF;
+    u64 cm = (act && e < nc) ? cq[e] : KEY_INF;
+    int inc0 = 0, crank = 0, cbase = 0;
+    for (int i = 0; __ballot(act && i < nc); ++i) {
+        const bool live = act && i < nc;
+        u64 ci = live ? cq[i] : KEY_INF;                // one address per group
+        inc0 += live && ci < e0;
+        int below = __popcll(__ballot(live && e0 < ci) & gmask);
+        if (e == i) cbase = below;
+        crank += live && ci < cm;
+    }
+    const int p0 = e + inc0, pc = cbase + crank;
+    const bool w0 = act && p0 < k, wc = act && e < nc && pc < k;
+    if (w0) L[p0] = e0;
+    if (wc) L[pc] = cm;
+    u64 tk = KEY_INF;
+    bool has = false;
+    if (w0 && p0 == k - 1) { tk = e0; has = true; }
+    if (wc && pc == k - 1) { tk = cm; has = true; }
+    u64 m = __ballot(has) & gmask;
+    return shfl64(tk, m ? __builtin_ctzll(m) : lane);
+}
+
+// Merge every queue named by a bit of `pend` (bit i = item i, i < 64).  get(i, L, cq, nc)
+// resolves an item to its list, queue and fill count; done(i, key) receives the list's new
+// k-th key.  Items are taken 64/kcap at a time (one per lane group) when kcap <= 64.
+template <typename Get, typename Done>
+__device__ __forceinline__ void merge_pending(u64 pend, int kcap, int k, int lane, Get get, Done done)
+{
+    if (kcap > 64) {
+        while (pend) {
+            int i = __builtin_ctzll(pend);
+            pend &= pend - 1;
+            u64 *L;
+            const u64 *cq;
+            int nc;
+            get(i, L, cq, nc);
+            done(i, merge_one(L, kcap, k, cq, nc, lane));
+        }
+        return;
+    }
+    const int G = 64 / kcap;                            // 1, 2 or 4 groups
+    const int gi = lane / kcap;
+    while (pend) {
+        int item[4] = {-1, -1, -1, -1};
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            if (g < G && pend) {
+                item[g] = __builtin_ctzll(pend);
+                pend &= pend - 1;
+            }
+        int mine = item[0];
+#pragma unroll
+        for (int g = 1; g < 4; ++g)
+            if (gi == g) mine = item[g];
+        // get() may shuffle: every lane calls it (idle groups with item 0, then discarded)
+        u64 *L;
+        const u64 *cq;
+        int nc;
+        get(mine >= 0 ? mine : 0, L, cq, nc);
+        if (mine < 0) {
+            L = nullptr;
+            nc = 0;
+        }
+        u64 nt = merge_multi(L, cq, nc, kcap, k, lane);
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            if (g < G && item[g] >= 0) done(item[g], readlane64(nt, g * kcap));
+    }
+}
+
 // State a wave keeps for the selection of its 32 queries.
 struct SelState {
     u64 tau_key;      // current k-th best (distance, index) key of the lane's query; KEY_INF if fewer than k
@@ -197,15 +294,45 @@ struct SelState {
     u64 *shared_tau;  // LDS [32]: bound shared with the other waves serving the same queries, or null
 };
 
-constexpr int QCAP_MAX = 16;
+// Rank-merge every non-empty candidate queue of this wave into its list and refresh the
+// thresholds.  Whole wave.
+template <int QC>
+__device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int lane)
+{
+    const int ql = lane & 31;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    uint32_t mycnt = *(volatile uint32_t *)&st.cnt[ql];
+    u64 pend = __ballot(mycnt > 0) & 0xffffffffull;
+    if (pend == 0) return;
+    merge_pending(
+        pend, kcap, k, lane,
+        [&](int qi, u64 *&L, const u64 *&cq, int &nc) {
+            L = st.Lw + (int64_t)qi * kcap;
+            cq = st.cq + qi * QC;
+            nc = min((int)__shfl(mycnt, qi, 64), QC);
+        },
+        [&](int qi, u64 nt) {
+            if (ql == qi && nt < st.tau_key) st.tau_key = nt;
+        });
+    st.tau_p = st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    if (lane < 32) {
+        st.cnt[lane] = 0;
+        if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+}
 
 // The rare path of the selection: some accumulator of this wave is below its query's
 // threshold.  One 32x32 block at a time, its 16 registers are walked with a run-time
 // index (small code, no extra register pressure in the hot loop).  A survivor is tested
 // exactly on the packed (distance, index) key, with the query itself and padding rows
-// excluded, and appended to the query's queue; the queues are then rank-merged into the
-// lists.  A full queue loses nothing: the value stays in the block copy and the block
-// is walked again after the merge.
+// excluded, and appended to the query's queue in LDS.  Queues are merged into the lists
+// lazily: when one is half full, when a list is still short of k entries (no threshold
+// yet), or when the caller flushes at the end of its sweep; until then the threshold is
+// merely stale, i.e. looser, which only lets more candidates into the queue.  A full
+// queue loses nothing: the value stays in the block copy and the block is walked again
+// after the merge.
 //   jb0: reference row of register 0 of block 0 for this lane (tile base + 4*(lane/32));
 //   block t adds 32t.
 template <int NB, int QC>
@@ -223,7 +350,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
         const int32_t jbase = jb0 + t * 32;
         bool again;
         do {
-            bool ovf = false;
+            bool ovf = false, urgent = false;
 #pragma unroll 1
             for (int r = 0; r < 16; ++r) {
                 float p = v[r];
@@ -236,6 +363,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                         if (slot < (uint32_t)QC) {
                             st.cq[ql * QC + slot] = key;
                             p = __builtin_inff();          // taken: a re-walk must not see it again
+                            urgent |= slot + 1 >= (uint32_t)(QC / 2) || st.tau_key == KEY_INF;
                         } else {
                             ovf = true;
                         }
@@ -244,24 +372,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                 }
             }
             again = __ballot(ovf) != 0;
-            // merge every non-empty queue of this wave into its list
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-            uint32_t mycnt = *(volatile uint32_t *)&st.cnt[ql];
-            u64 pend = __ballot(mycnt > 0) & 0xffffffffull;
-            while (pend) {
-                int qi = __builtin_ctzll(pend);
-                pend &= pend - 1;
-                int nc = min((int)__builtin_amdgcn_readlane(mycnt, qi), QC);
-                u64 nt = merge_one(st.Lw + (int64_t)qi * kcap, kcap, k, st.cq + qi * QC, nc, lane);
-                if (ql == qi && nt < st.tau_key) st.tau_key = nt;
-            }
-            st.tau_p = st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-            if (lane < 32) {
-                st.cnt[lane] = 0;
-                if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            if (again || __ballot(urgent)) merge_queues<QC>(st, kcap, k, lane);
         } while (again);
     }
 }
@@ -310,7 +421,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
     f32x4 gq[NPASS], gr[NPASS];
     float gc = 0.f;
 
-    auto issue = [&](int rt, int kc) {
+    auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NPASS; ++i) {
             gq[i] = *(const f32x4 *)(qsrc[i] + kc * DC);
@@ -319,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
         }
         if (kc == 0 && tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
     };
-    auto stash = [&](int buf, int kc) {
+    auto stash = [&](int buf, int kc) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NPASS; ++i) {
             *(f32x4 *)&sm.q[buf][(lrow + i * ROWS_PER_PASS) * LSTR + lcol] = gq[i];
@@ -384,7 +495,11 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
             m4 = fminf(m4, min16(acc[1]));
             m4 = fminf(m4, min16(acc[2]));
             m4 = fminf(m4, min16(acc[3]));
-            if (__ballot(m4 <= st.tau_p)) select_rare<4, QCAP>(acc, rt * TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
+            if (__ballot(m4 <= st.tau_p)) {
+                // a copy, so that the address of the hot loop's accumulators is never taken
+                f32x16 blocks[4] = {acc[0], acc[1], acc[2], acc[3]};
+                select_rare<4, QCAP>(blocks, rt * TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
+            }
         }
 
         if (more) stash(buf ^ 1, nkc);
@@ -392,6 +507,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
         rt = nrt;
         kc = nkc;
     }
+    merge_queues<QCAP>(st, a.kcap, a.k, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -572,8 +688,10 @@ __global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
                 st.tau_p = ord2f((uint32_t)(sh >> 32));
             }
             float m2 = fminf(min16(acc[0]), min16(acc[1]));
-            if (__ballot(m2 <= st.tau_p))
-                select_rare<2, QR_QCAP>(acc, rt * TR + g * QR_HALF + 4 * h, a.nr, a.kcap, a.k, st, lane);
+            if (__ballot(m2 <= st.tau_p)) {
+                f32x16 blocks[2] = {acc[0], acc[1]};
+                select_rare<2, QR_QCAP>(blocks, rt * TR + g * QR_HALF + 4 * h, a.nr, a.kcap, a.k, st, lane);
+            }
         }
         int nkc = kc + 1, nrt = rt;
         if (nkc == nk) { nkc = 0; nrt = rt + 1; }
@@ -587,6 +705,7 @@ __global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
         step(it, 0);
         if (it + 1 < total) step(it + 1, 1);
     }
+    merge_queues<QR_QCAP>(st, a.kcap, a.k, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -601,6 +720,19 @@ __global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
 // all stream the same reference rows through the L2, and no query tile competes for it.
 // The d-loop is fully unrolled so that the query registers are addressed statically.
 // ---------------------------------------------------------------------------
+// Calls f(integral_constant<int, 0>, x), ..., f(integral_constant<int, N-1>, x): a loop whose
+// counter is a compile-time constant inside the body.
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_step_impl(F &f, int x, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}, x), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void for_each_step(F &f, int x)
+{
+    for_each_step_impl(f, x, std::make_integer_sequence<int, N>{});
+}
+
 constexpr int QG_TR = 64;                         // reference rows per tile
 constexpr int QG_DC = 32;                         // coordinates per step
 constexpr int QG_NSLAB = QG_DC / 8;
@@ -659,19 +791,21 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
         for (int s = 0; s < NS; ++s) qreg[s] = *(const f32x4 *)(qrow + s * 8);
     }
 
-    // staging of the 64 reference rows: thread -> 16-byte unit lunit of rows lrow and lrow+32
+    // staging of the 64 reference rows: thread -> 16-byte unit lunit of rows lrow and lrow+32,
+    // through registers (a direct global -> LDS deposit, global_load_lds_dwordx4, was measured
+    // 3 % slower here)
     const int lrow = tid >> 3, lunit = tid & 7;
     const int st_off = lrow * QG_DC + ((lunit ^ qg_swz(lrow)) << 2);   // rows r and r+32 swizzle alike
     f32x4 g0, g1;
     float gc = 0.f;
-    auto issue = [&](int rt, int kc) {
+    auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
         int64_t r0 = min((int64_t)rt * QG_TR + lrow, a.nr - 1);
         int64_t r1 = min((int64_t)rt * QG_TR + lrow + 32, a.nr - 1);
         g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
         g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
         if (kc == 0 && tid < QG_TR) gc = a.cR[(int64_t)rt * QG_TR + tid];
     };
-    auto stash = [&](int buf, int kc) {
+    auto stash = [&](int buf, int kc) __attribute__((always_inline)) {
         *(f32x4 *)&sm.r[buf][st_off] = g0;
         *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
         if (kc == 0 && tid < QG_TR) sm.c[buf][tid] = gc;
@@ -688,51 +822,53 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     __syncthreads();
 
     int buf = 0;
-    for (int rt = rt0; rt < rt1; ++rt) {
+    // one step = QG_DC coordinates; kc is a compile-time constant so that qreg[] is
+    // addressed statically (a run-time index would push the array to scratch memory)
+    auto step = [&](auto kc_tag, int rt) __attribute__((always_inline)) {
+        constexpr int kc = decltype(kc_tag)::value;
+        constexpr bool last = kc == NK - 1;
+        const bool more = !last || rt + 1 < rt1;
+        if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
+        // keep the loads up here: their latency must overlap this step's matrix work
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc == 0) {
 #pragma unroll
-        for (int kc = 0; kc < NK; ++kc) {
-            const bool last = kc == NK - 1;
-            const bool more = !last || rt + 1 < rt1;
-            if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
-            // keep the loads up here: their latency must overlap this step's matrix work
-            __builtin_amdgcn_sched_barrier(0);
-            if (kc == 0) {
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 c0 = *(const f32x4 *)&sm.c[buf][gg * 8 + h * 4];
+                f32x4 c1 = *(const f32x4 *)&sm.c[buf][32 + gg * 8 + h * 4];
 #pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    f32x4 c0 = *(const f32x4 *)&sm.c[buf][gg * 8 + h * 4];
-                    f32x4 c1 = *(const f32x4 *)&sm.c[buf][32 + gg * 8 + h * 4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        acc0[4 * gg + e] = c0[e];
-                        acc1[4 * gg + e] = c1[e];
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    acc0[4 * gg + e] = c0[e];
+                    acc1[4 * gg + e] = c1[e];
                 }
             }
-            const float *rb = &sm.r[buf][0];
-#pragma unroll
-            for (int s = 0; s < QG_NSLAB; ++s) {
-                const int u = ((2 * s + h) ^ sw) << 2;
-                f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
-                f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
-                const f32x4 qf = qreg[kc * QG_NSLAB + s];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
-                }
-            }
-            if (last) {
-                float m2 = fminf(min16(acc0), min16(acc1));
-                if (__ballot(m2 <= st.tau_p)) {
-                    f32x16 blocks[2] = {acc0, acc1};
-                    select_rare<2, QCAP>(blocks, rt * QG_TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
-                }
-            }
-            if (more) stash(buf ^ 1, last ? 0 : kc + 1);
-            __syncthreads();
-            buf ^= 1;
         }
-    }
+        const float *rb = &sm.r[buf][0];
+#pragma unroll
+        for (int s = 0; s < QG_NSLAB; ++s) {
+            const int u = ((2 * s + h) ^ sw) << 2;
+            f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+            f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+            const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+            }
+        }
+        if (last) {
+            float m2 = fminf(min16(acc0), min16(acc1));
+            if (__ballot(m2 <= st.tau_p)) {
+                f32x16 blocks[2] = {acc0, acc1};
+                select_rare<2, QCAP>(blocks, rt * QG_TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
+            }
+        }
+        if (more) stash(buf ^ 1, last ? 0 : kc + 1);
+        __syncthreads();
+        buf ^= 1;
+    };
+    for (int rt = rt0; rt < rt1; ++rt) for_each_step<NK>(step, rt);
+    merge_queues<QCAP>(st, a.kcap, a.k, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -767,10 +903,16 @@ struct __attribute__((aligned(16))) PairSmem {
     float T[2][QG_TR];                            // one-sided mirror thresholds
     u64 mtau[2][QG_TR];                           // exact k-th best keys of the tile's reference rows
     u64 cq[4][32][QCAP];
-    u64 mq[QG_TR][MQCAP];
+    u64 mq[2][QG_TR][MQCAP];                      // mirror queues, by tile parity
     uint32_t cnt[4][32];
-    uint32_t mcnt[QG_TR];
-    uint32_t mflag;                               // bit 0: some mirror queue is non-empty, bit 1: one overflowed
+    uint32_t mcnt[2][QG_TR];
+    uint32_t movf[2];                             // a mirror queue of the tile overflowed
+    // per-thread selection state, parked here between epilogues so that it does not occupy
+    // registers during the matrix loop (the d = 256 instance is at the 256-register limit)
+    u64 tkey[256];                                // threshold key of the thread's query
+    float tp[256];                                // its distance part
+    float cqv[256];                               // c of the thread's query (+inf: no valid query)
+    uint32_t taken[256];                          // mirror entries of the current tile already queued
 };
 
 __device__ __forceinline__ float mirror_T(u64 tkey, float cj, float cmax, float abound)
@@ -819,59 +961,74 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
     const float abound = a.metric == 1 ? 1.5f : 3.f * cmax;
 
     if (lane < 32) sm.cnt[w][lane] = 0;
-    if (tid < QG_TR) sm.mcnt[tid] = 0;
-    if (tid == 0) sm.mflag = 0;
+    if (tid < 2 * QG_TR) sm.mcnt[tid >> 6][tid & 63] = 0;
+    if (tid < 2) sm.movf[tid] = 0;
 
-    const int lrow = tid >> 3, lunit = tid & 7;
-    const int st_off = lrow * QG_DC + ((lunit ^ qg_swz(lrow)) << 2);
+    // Staging of the 64 reference rows, global -> LDS without passing through registers
+    // (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes at LDS base + 16 l;
+    // this instance has no registers to spare for staging).  Wave w fills rows 8w..8w+7 and
+    // 32+8w..32+8w+7; slot l of a 1 KB block is row l/8, physical unit l%8, so the lane
+    // fetches the logical unit that the swizzle puts there.
+    const int lrow = tid >> 3;
+    const int lunit = (tid & 7) ^ qg_swz(lrow);   // rows r and r+32 swizzle alike
     const int rbase0 = ql * QG_DC, rbase1 = (32 + ql) * QG_DC;
     const int sw = qg_swz(ql);
 
-    f32x4 g0, g1;
     float gc = 0.f;
     u64 gmt = 0;
-    auto issue = [&](int rt, int kc) {
+    auto issue = [&](int rt, int kc, int buf) __attribute__((always_inline)) {
         int64_t r0 = min(rrow0 + (int64_t)rt * QG_TR + lrow, a.n - 1);
         int64_t r1 = min(rrow0 + (int64_t)rt * QG_TR + lrow + 32, a.n - 1);
-        g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
-        g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
+        lds_ptr d0 = (lds_ptr)&sm.r[buf][(w * 8) * QG_DC];
+        lds_ptr d1 = (lds_ptr)&sm.r[buf][(32 + w * 8) * QG_DC];
+        __builtin_amdgcn_global_load_lds(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4, d0, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4, d1, 16, 0, 0);
         if (kc == 0 && tid < QG_TR) {
             int64_t row = rrow0 + (int64_t)rt * QG_TR + tid;     // < n_cpad: c is padded with +inf
             gc = a.cR[row];
             gmt = (!diag && row < a.n) ? a.lists[row * a.kcap + (a.k - 1)] : 0ull;
         }
     };
-    // staging buffers alternate per step; the per-tile arrays (c, T, mtau) alternate per
-    // tile (tb = tile parity), because a tile's mirror values are still needed after the
-    // next tile's first chunk has been staged
-    auto stash = [&](int buf, int kc, int tb) {
-        *(f32x4 *)&sm.r[buf][st_off] = g0;
-        *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
+    // The per-tile arrays (c, T, mtau) alternate per tile (tb = tile parity), not per step: a
+    // tile's mirror values are still needed after the next tile's first chunk has been staged.
+    auto stash = [&](int kc, int tb) __attribute__((always_inline)) {
         if (kc == 0 && tid < QG_TR) {
             sm.c[tb][tid] = gc;
             sm.mtau[tb][tid] = gmt;
             sm.T[tb][tid] = mirror_T(gmt, gc, cmax, abound);
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this step's deposits have landed
     };
 
     for (int qt = 0; qt < n_qt; ++qt) {
         const int64_t qbase = qrow0 + (int64_t)qt * TQ;
         const int64_t myq = qbase + 32 * w + ql;
         const bool qvalid = myq < a.n;
-        u64 *Lw = a.lists + (qbase + 32 * w) * a.kcap;
-        if (diag)
-            for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-        SelState st;
-        st.tau_key = qvalid ? Lw[(int64_t)ql * a.kcap + (a.k - 1)] : 0ull;
-        st.tau_p = !qvalid ? -__builtin_inff()
-                           : st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
-        st.selfj = (diag && qvalid) ? (int32_t)myq : -1;
-        st.Lw = Lw;
-        st.cq = &sm.cq[w][0][0];
-        st.cnt = &sm.cnt[w][0];
-        st.shared_tau = nullptr;
-        const float cq = qvalid ? a.cR[myq] : __builtin_inff();   // the query's own c, for the mirror values
+        {
+            u64 *Lw = a.lists + (qbase + 32 * w) * a.kcap;
+            if (diag)
+                for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            u64 tk = qvalid ? Lw[(int64_t)ql * a.kcap + (a.k - 1)] : 0ull;
+            sm.tkey[tid] = tk;
+            sm.tp[tid] = !qvalid ? -__builtin_inff() : tk == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(tk >> 32));
+            sm.cqv[tid] = qvalid ? a.cR[myq] : __builtin_inff();   // the query's own c, for the mirror values
+        }
+        auto load_state = [&]() __attribute__((always_inline)) {
+            SelState st;
+            st.tau_key = sm.tkey[tid];
+            st.tau_p = sm.tp[tid];
+            st.selfj = (diag && qvalid) ? (int32_t)myq : -1;
+            st.Lw = a.lists + (qbase + 32 * w) * a.kcap;
+            st.cq = &sm.cq[w][0][0];
+            st.cnt = &sm.cnt[w][0];
+            st.shared_tau = nullptr;
+            return st;
+        };
+        auto save_state = [&](const SelState &st) __attribute__((always_inline)) {
+            sm.tkey[tid] = st.tau_key;
+            sm.tp[tid] = st.tau_p;
+        };
 
         f32x4 qreg[NS];
         {
@@ -881,137 +1038,162 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
         }
 
         f32x16 acc0, acc1;
-        issue(0, 0);
-        stash(0, 0, 0);
+        issue(0, 0, 0);
+        stash(0, 0);
         __syncthreads();
 
-        // Mirror candidates of one tile: scan (cheap one-sided test per register, exact test
-        // for survivors, per-row queue), flagged in sm.mflag.  Entries taken are overwritten
-        // with +inf in the accumulators so that a re-scan after an overflow skips them.
-        auto mirror_scan = [&](int rt) {
-            const int buf = rt & 1;
+        // Mirror candidates of one tile: cheap one-sided test per register, exact test for
+        // survivors, per-row queue (by tile parity).  Entries that found a slot are recorded
+        // in a per-lane bit mask so that a re-scan after an overflow skips them (the
+        // accumulators themselves are only ever read here).
+        auto mirror_scan = [&](int rt, bool fresh) __attribute__((always_inline)) {
+            const int par = rt & 1;
+            const float cq = sm.cqv[tid];
             float dmax = -__builtin_inff();
 #pragma unroll
             for (int gg = 0; gg < 4; ++gg) {
-                f32x4 t0 = *(const f32x4 *)&sm.T[buf][gg * 8 + h * 4];
-                f32x4 t1 = *(const f32x4 *)&sm.T[buf][32 + gg * 8 + h * 4];
+                f32x4 t0 = *(const f32x4 *)&sm.T[par][gg * 8 + h * 4];
+                f32x4 t1 = *(const f32x4 *)&sm.T[par][32 + gg * 8 + h * 4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     dmax = fmaxf(dmax, t0[e] - acc0[4 * gg + e]);
                     dmax = fmaxf(dmax, t1[e] - acc1[4 * gg + e]);
                 }
             }
-            if (__ballot(qvalid && dmax >= cq) == 0) return;
-            uint32_t fl = 0;
+            if (__ballot(qvalid && dmax >= cq) == 0) {
+                if (fresh) sm.taken[tid] = 0;
+                return;
+            }
+            uint32_t taken = fresh ? 0u : sm.taken[tid];
+            bool ovf = false;
 #pragma unroll 1
             for (int t = 0; t < 2; ++t) {
-                f32x16 v = t == 0 ? acc0 : acc1;
+                const f32x16 v = t == 0 ? acc0 : acc1;
 #pragma unroll 1
                 for (int r = 0; r < 16; ++r) {
                     const int m = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    float p = v[r];
-                    bool c = qvalid && sm.T[buf][m] - p >= cq;
+                    const uint32_t bit = 1u << (t * 16 + r);
+                    const float p = v[r];
+                    bool c = qvalid && !(taken & bit) && sm.T[par][m] - p >= cq;
                     if (__ballot(c)) {
                         if (c) {
-                            float p2 = (p - sm.c[buf][m]) + cq;          // this pair seen from row m
+                            float p2 = (p - sm.c[par][m]) + cq;          // this pair seen from row m
                             u64 key = make_key(p2, (int32_t)myq);
-                            if (key < sm.mtau[buf][m]) {
-                                uint32_t slot = atomicAdd(&sm.mcnt[m], 1u);
+                            if (key < sm.mtau[par][m]) {
+                                uint32_t slot = atomicAdd(&sm.mcnt[par][m], 1u);
                                 if (slot < (uint32_t)MQCAP) {
-                                    sm.mq[m][slot] = key;
-                                    p = __builtin_inff();
-                                    fl |= 1u;
+                                    sm.mq[par][m][slot] = key;
+                                    taken |= bit;
                                 } else {
-                                    fl |= 3u;
+                                    ovf = true;
                                 }
                             }
                         }
-                        v[r] = p;
                     }
                 }
-                if (t == 0) acc0 = v; else acc1 = v;
             }
-            if (fl) atomicOr(&sm.mflag, fl);
+            sm.taken[tid] = taken;
+            if (ovf) atomicOr(&sm.movf[par], 1u);
         };
-        // After the barrier that ends a tile: if any mirror queue holds candidates, the waves
-        // merge them (wave w serves rows 16w..16w+15 of the tile), and after an overflow the
-        // tile is scanned again against the tightened thresholds.  Workgroup-uniform.
-        auto mirror_service = [&](int rt) {
-            const int buf = rt & 1;
-            while (true) {
-                const uint32_t fl = *(volatile uint32_t *)&sm.mflag;
-                if (fl == 0) break;
-                uint32_t mc = lane < QG_TR ? *(volatile uint32_t *)&sm.mcnt[lane] : 0u;
-                u64 pend = __ballot(mc > 0) & (0xffffull << (16 * w));
-                while (pend) {
-                    int m = __builtin_ctzll(pend);
-                    pend &= pend - 1;
-                    int nc = min((int)__builtin_amdgcn_readlane(mc, m), MQCAP);
-                    int64_t row = rrow0 + (int64_t)rt * QG_TR + m;
-                    u64 nt = merge_one(a.lists + row * a.kcap, a.kcap, a.k, &sm.mq[m][0], nc, lane);
+        // Wave w merges the queued mirror candidates of rows 16w..16w+15 of tile rt.
+        auto mirror_merge = [&](int rt, bool refresh) __attribute__((always_inline)) {
+            const int par = rt & 1;
+            uint32_t mc = lane < QG_TR ? *(volatile uint32_t *)&sm.mcnt[par][lane] : 0u;
+            u64 pend = __ballot(mc > 0) & (0xffffull << (16 * w));
+            merge_pending(
+                pend, a.kcap, a.k, lane,
+                [&](int m, u64 *&L, const u64 *&cq, int &nc) {
+                    L = a.lists + (rrow0 + (int64_t)rt * QG_TR + m) * a.kcap;
+                    cq = &sm.mq[par][m][0];
+                    nc = min((int)__shfl(mc, m, 64), MQCAP);
+                },
+                [&](int m, u64 nt) {
                     if (lane == 0) {
-                        sm.mtau[buf][m] = nt;
-                        sm.T[buf][m] = mirror_T(nt, sm.c[buf][m], cmax, abound);
-                        sm.mcnt[m] = 0;
+                        sm.mcnt[par][m] = 0;
+                        if (refresh) {
+                            sm.mtau[par][m] = nt;
+                            sm.T[par][m] = mirror_T(nt, sm.c[par][m], cmax, abound);
+                        }
                     }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                });
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        };
+        // Called by every wave after the barrier that ends tile rt.  Common case: each wave
+        // merges its own rows, no further synchronisation (the rows' new thresholds are read
+        // from the lists when the rows are visited again).  After an overflow the tile is
+        // re-scanned against refreshed thresholds until every candidate found a slot; that
+        // path is workgroup-uniform and uses barriers.
+        auto mirror_service = [&](int rt) __attribute__((always_inline)) {
+            const int par = rt & 1;
+            if (*(volatile uint32_t *)&sm.movf[par] == 0) {
+                mirror_merge(rt, false);
+                return;
+            }
+            while (true) {
+                mirror_merge(rt, true);
                 __syncthreads();
-                if (tid == 0) sm.mflag = 0;
+                const uint32_t ovf = *(volatile uint32_t *)&sm.movf[par];
                 __syncthreads();
-                if (!(fl & 2u)) break;
-                mirror_scan(rt);
+                if (!ovf) break;
+                if (tid == 0) sm.movf[par] = 0;
+                __syncthreads();
+                mirror_scan(rt, false);
                 __syncthreads();
             }
         };
 
         int buf = 0;
-        for (int rt = 0; rt < n_rt; ++rt) {
+        auto step = [&](auto kc_tag, int rt) __attribute__((always_inline)) {
+            constexpr int kc = decltype(kc_tag)::value;
+            constexpr bool last = kc == NK - 1;
+            const bool more = !last || rt + 1 < n_rt;
+            if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kc == 0) {
+                if (!diag && rt > 0) mirror_service(rt - 1);
 #pragma unroll
-            for (int kc = 0; kc < NK; ++kc) {
-                const bool last = kc == NK - 1;
-                const bool more = !last || rt + 1 < n_rt;
-                if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (kc == 0) {
-                    if (!diag && rt > 0) mirror_service(rt - 1);
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
+                    f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
 #pragma unroll
-                    for (int gg = 0; gg < 4; ++gg) {
-                        f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
-                        f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            acc0[4 * gg + e] = c0[e];
-                            acc1[4 * gg + e] = c1[e];
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        acc0[4 * gg + e] = c0[e];
+                        acc1[4 * gg + e] = c1[e];
                     }
                 }
-                const float *rb = &sm.r[buf][0];
-#pragma unroll
-                for (int s = 0; s < QG_NSLAB; ++s) {
-                    const int u = ((2 * s + h) ^ sw) << 2;
-                    f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
-                    f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
-                    const f32x4 qf = qreg[kc * QG_NSLAB + s];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
-                    }
-                }
-                if (last) {
-                    float m2 = fminf(min16(acc0), min16(acc1));
-                    if (__ballot(m2 <= st.tau_p)) {
-                        f32x16 blocks[2] = {acc0, acc1};
-                        select_rare<2, QCAP>(blocks, (int32_t)(rrow0 + (int64_t)rt * QG_TR) + 4 * h, a.n,
-                                             a.kcap, a.k, st, lane);
-                    }
-                    if (!diag) mirror_scan(rt);
-                }
-                if (more) stash(buf ^ 1, last ? 0 : kc + 1, (rt + 1) & 1);
-                __syncthreads();
-                buf ^= 1;
             }
+            const float *rb = &sm.r[buf][0];
+#pragma unroll
+            for (int s = 0; s < QG_NSLAB; ++s) {
+                const int u = ((2 * s + h) ^ sw) << 2;
+                f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+                f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+                const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+                }
+            }
+            if (last) {
+                float m2 = fminf(min16(acc0), min16(acc1));
+                if (__ballot(m2 <= sm.tp[tid])) {
+                    SelState st = load_state();
+                    f32x16 blocks[2] = {acc0, acc1};
+                    select_rare<2, QCAP>(blocks, (int32_t)(rrow0 + (int64_t)rt * QG_TR) + 4 * h, a.n,
+                                         a.kcap, a.k, st, lane);
+                    save_state(st);
+                }
+                if (!diag) mirror_scan(rt, true);
+            }
+            if (more) stash(last ? 0 : kc + 1, (rt + 1) & 1);
+            __syncthreads();
+            buf ^= 1;
+        };
+        for (int rt = 0; rt < n_rt; ++rt) for_each_step<NK>(step, rt);
+        {
+            SelState st = load_state();
+            merge_queues<QCAP>(st, a.kcap, a.k, lane);
         }
         if (!diag) mirror_service(n_rt - 1);
         __syncthreads();

@@ -281,3 +281,29 @@ def test_comparator_accepts_oracle_and_catches_mistakes():
     assert rep.ok and rep.rows_set_exempt == 1, str(rep)
     assert not compare.check(Y, Y, "sqeuclidean", oi, od, on, gi, gd, np.arange(4),
                              strict_ties=True).ok
+
+
+def test_select_pins():
+    """Batched partial sort (Sect. 6): hand example with ties, numpy's stable argsort (a
+    library routine), repeated minimum on a small input, rows independent of each other."""
+    A = np.array([[5, 1, 4, 1, 9, 0], [2, 2, 2, 2, 2, 2], [-1, 7, -3, 7, -3, 8]], dtype=np.float32)
+    idx, val = oracle.select(A, 4)
+    assert idx.tolist() == [[5, 1, 3, 2], [0, 1, 2, 3], [2, 4, 0, 1]]          # worked out by hand
+    assert val.tolist() == [[0, 1, 1, 4], [2, 2, 2, 2], [-3, -3, -1, 7]]
+    rng = np.random.default_rng(4)
+    B = np.round(rng.standard_normal((37, 501)) * 8).astype(np.float32) / 8      # many ties
+    idx, val = oracle.select(B, 23)
+    order = np.argsort(B, axis=1, kind="stable")[:, :23]
+    assert np.array_equal(idx, order)
+    assert np.array_equal(val, np.take_along_axis(B, order, axis=1))
+    for i in (0, 17, 36):
+        row, taken = B[i].tolist(), []
+        for _ in range(23):
+            best = None
+            for j, v in enumerate(row):
+                if j not in taken and (best is None or v < row[best]):
+                    best = j
+            taken.append(best)
+        assert idx[i].tolist() == taken
+    i2, v2 = oracle.select(B[5:6], 23)
+    assert np.array_equal(i2[0], idx[5]) and np.array_equal(v2[0], val[5])
