@@ -42,6 +42,7 @@ def main() -> int:
     ap.add_argument("--block-rows", type=int, default=0, help="symmetric schedule: rows per block")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-select", action="store_true", help="skip the stand-alone selection timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain elementwise copy of 1 GiB (for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -133,6 +134,35 @@ def main() -> int:
     if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3) and not args.block_rows:
         out["roofline"]["traffic"] = MEASURED_TRAFFIC_BYTES_PER_STEP[tkey] / launches
         out["roofline"]["traffic_unit"] = "bytes per launch (offline rocprofv3 FETCH_SIZE+WRITE_SIZE)"
+
+    if not args.no_select:
+        # Selection stage on its own (the paper's Phase 2 as stated in Sect. 6: rows of a
+        # materialised distance slab): HBM-bound, 4 bytes per element read once.
+        from paper_0906_0231_amd import knn_select
+        from paper_0906_0231_amd.api import load_library
+        sm_rows, sm_cols = 4096, 262144                      # 4 GiB slab
+        gsel = torch.Generator(device=dev).manual_seed(workloads.BASE_SEED)
+        slab = torch.randn(sm_rows, sm_cols, generator=gsel, device=dev, dtype=torch.float32)
+        sws = torch.empty(load_library().knn_select_workspace_bytes(sm_rows, sm_cols, k),
+                          dtype=torch.uint8, device=dev)
+        sout = (torch.empty((sm_rows, k), dtype=torch.int32, device=dev),
+                torch.empty((sm_rows, k), dtype=torch.float32, device=dev))
+        knn_select(slab, k, workspace=sws, out=sout)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            knn_select(slab, k, workspace=sws, out=sout)
+        e1.record()
+        torch.cuda.synchronize()
+        sel_ms = e0.elapsed_time(e1) / reps
+        gbs = 4.0 * sm_rows * sm_cols / (sel_ms * 1e-3) / 1e9
+        out["selection_stage"] = {"kernel": "select_rows", "bound": "hbm", "achieved": gbs,
+                                  "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                                  "workload": f"{sm_rows} x {sm_cols} fp32 slab, k={k}",
+                                  "ms": sel_ms, "elements_per_s": sm_rows * sm_cols / (sel_ms * 1e-3)}
+        del slab, sws, sout
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)

@@ -39,7 +39,10 @@ extern "C" {
 
 typedef enum {
     KNN_SQEUCLIDEAN = 0, /* sum_c (u_c - v_c)^2 */
-    KNN_COSINE = 1       /* 1 - u.v / (|u| |v|); 1 if either vector is all zero */
+    KNN_COSINE = 1,      /* 1 - u.v / (|u| |v|); 1 if either vector is all zero */
+    KNN_HELLINGER = 2    /* sum_c (sqrt u_c - sqrt v_c)^2, the distance of the paper's experiment
+                            (Sect. 7, Eq. 1, with the square its printed form lacks);
+                            inputs must be >= 0 */
 } knn_metric_t;
 
 typedef enum {
@@ -140,6 +143,24 @@ size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_met
 /* Same, for a given option block (a forced r_splits changes the partial-list area). */
 size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
                               int32_t symmetric, const knn_options_t *opt);
+
+/*
+ * Batched partial sort of a matrix that already exists in memory: the paper's Phase 2 as
+ * a routine of its own (Sect. 6, KSmallest(k, n, m, {h_i}, {a_ij}); Sect. 8 singles it out
+ * as useful beyond kNN).  For every row of A, the k smallest entries in non-decreasing
+ * order and their column numbers; equal values go to the lower column.
+ *   A   [m, lda] device, fp32, row stride lda >= n floats, read only (read exactly once)
+ *   idx [m, k]   device, int32, out: column numbers
+ *   val [m, k]   device, fp32, out: the values, bit-identical copies of entries of A
+ * Requires 1 <= m < 2^31, 1 <= k <= min(n, KNN_MAX_K), n < 2^31.  Rows whose start is
+ * 16-byte aligned (A aligned, lda % 4 == 0) are read with 128-bit loads.
+ */
+knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32_t k,
+                        int32_t *idx, float *val,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace knn_select needs (256-byte aligned); 0 if the sizes are invalid. */
+size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k);
 
 /* Static, human-readable name of a status code. */
 const char *knn_status_string(knn_status_t status);

@@ -19,12 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libknn.so")
 
 KNN_SQEUCLIDEAN = 0
 KNN_COSINE = 1
+KNN_HELLINGER = 2
 KNN_OK, KNN_EINVAL, KNN_EUNSUPPORTED, KNN_ENOMEM, KNN_EDEVICE = range(5)
 KNN_MAX_K = 128
-METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE}
+METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KNN_HELLINGER}
 
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
-           "knn_workspace_bytes_ex", "knn_status_string", "knn_last_device_error"]
+           "knn_workspace_bytes_ex", "knn_select", "knn_select_workspace_bytes",
+           "knn_status_string", "knn_last_device_error"]
 
 
 class KnnProfile(ctypes.Structure):
@@ -74,6 +76,10 @@ def load_library() -> ctypes.CDLL:
     lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
     lib.knn_workspace_bytes_ex.restype = sz
     lib.knn_workspace_bytes_ex.argtypes = [i64, i64, i32, i32, i32, i32, optp]
+    lib.knn_select.restype = i32
+    lib.knn_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+    lib.knn_select_workspace_bytes.restype = sz
+    lib.knn_select_workspace_bytes.argtypes = [i64, i64, i32]
     lib.knn_status_string.restype = ctypes.c_char_p
     lib.knn_status_string.argtypes = [i32]
     lib.knn_last_device_error.restype = ctypes.c_char_p
@@ -180,3 +186,26 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
                                  workspace.data_ptr(), workspace.numel(), stream,
                                  ctypes.byref(opt)))
     return KnnResult(idx, dist, prof)
+
+
+def knn_select(A: torch.Tensor, k: int, *, workspace: Optional[torch.Tensor] = None,
+               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """k smallest entries of every row of the device matrix A; see knn_select in knn.h.
+    A may be a row-strided view (stride(1) == 1).  Returns (idx int32 [m,k], val fp32 [m,k])."""
+    lib = load_library()
+    if not isinstance(A, torch.Tensor) or A.dim() != 2 or not A.is_cuda or A.dtype != torch.float32:
+        raise ValueError("A must be a 2-D fp32 tensor on the GPU")
+    if A.stride(1) != 1 or A.stride(0) < A.shape[1]:
+        raise ValueError("rows of A must be contiguous")
+    m, n = A.shape
+    with torch.cuda.device(A.device):
+        idx, val = out if out is not None else (
+            torch.empty((m, k), dtype=torch.int32, device=A.device),
+            torch.empty((m, k), dtype=torch.float32, device=A.device))
+        if workspace is None:
+            nbytes = int(lib.knn_select_workspace_bytes(m, n, k))
+            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=A.device)
+        stream = torch.cuda.current_stream(A.device).cuda_stream
+        _check(lib.knn_select(A.data_ptr(), m, n, A.stride(0), k, idx.data_ptr(), val.data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), stream))
+    return idx, val

@@ -90,7 +90,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
     p.nlists = p.S * per_slice;
-    p.rcopy = metric == KNN_COSINE || p.dpad != d;
+    p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
 
     size_t o = 0;
     p.off_qp = o;
@@ -111,7 +111,7 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
                          int64_t self_offset)
 {
     if (nq < 1 || nr < 1 || d < 1 || k < 1) return KNN_EINVAL;
-    if (metric != KNN_SQEUCLIDEAN && metric != KNN_COSINE) return KNN_EINVAL;
+    if (metric != KNN_SQEUCLIDEAN && metric != KNN_COSINE && metric != KNN_HELLINGER) return KNN_EINVAL;
     if (self_offset < -1) return KNN_EINVAL;
     if (self_offset >= 0 && self_offset + nq > nr) return KNN_EINVAL;
     if ((int64_t)k > nr - (self_offset >= 0 ? 1 : 0)) return KNN_EINVAL;
@@ -286,6 +286,8 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.S = p.nlists;
     if (metric == KNN_COSINE)
         f.mode = o.rescore == 2 ? FIN_ADD_ONE : FIN_RESCORE_COS;
+    else if (metric == KNN_HELLINGER)
+        f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_HEL;
     else
         f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_SQ;
     f.vec4 = (d % 4 == 0) ? 1 : 0;
@@ -343,6 +345,74 @@ knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, 
 {
     return knn_search_ex(Q, nq, R, nr, d, k, metric, self_offset, idx, dist, workspace,
                          workspace_bytes, stream, nullptr);
+}
+
+// knn_select: how the columns are cut.  Enough waves to fill the GPU when there are few rows,
+// segments no shorter than 16K columns, and no more partial lists than finalize can merge.
+static void select_plan(int64_t m, int64_t n, int32_t k, int32_t &kcap, int32_t &S, int64_t &seg)
+{
+    kcap = list_capacity(k);
+    int64_t want = (8192 + m - 1) / m;
+    int64_t most = n / 16384 > 0 ? n / 16384 : 1;
+    if (want > most) want = most;
+    if (want > KNN_FIN_MAX / kcap) want = KNN_FIN_MAX / kcap;
+    if (want < 1) want = 1;
+    seg = (n + want - 1) / want;
+    seg = (seg + 1023) / 1024 * 1024;
+    S = (int32_t)((n + seg - 1) / seg);
+}
+
+size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k)
+{
+    if (m < 1 || n < 1 || k < 1 || k > n || k > KNN_MAX_K || n >= ((int64_t)1 << 31)) return 0;
+    int32_t kcap, S;
+    int64_t seg;
+    select_plan(m, n, k, kcap, S, seg);
+    return align_up((size_t)S * m * kcap * sizeof(u64), 256);
+}
+
+knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32_t k, int32_t *idx,
+                        float *val, void *workspace, size_t workspace_bytes, void *stream_v)
+{
+    g_last_error[0] = 0;
+    if (!A || !idx || !val) return KNN_EINVAL;
+    if (m < 1 || n < 1 || lda < n || k < 1 || k > n) return KNN_EINVAL;
+    if (((uintptr_t)A & 3) || ((uintptr_t)idx & 3) || ((uintptr_t)val & 3)) return KNN_EINVAL;
+    if (k > KNN_MAX_K || n >= ((int64_t)1 << 31) || m >= ((int64_t)1 << 31)) return KNN_EUNSUPPORTED;
+    int32_t kcap, S;
+    int64_t seg;
+    select_plan(m, n, k, kcap, S, seg);
+    const size_t need = align_up((size_t)S * m * kcap * sizeof(u64), 256);
+    if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
+    if (workspace_bytes < need) return KNN_ENOMEM;
+    hipStream_t stream = (hipStream_t)stream_v;
+    SelectArgs a;
+    a.A = A;
+    a.lists = (u64 *)workspace;
+    a.m = m;
+    a.n = n;
+    a.lda = lda;
+    a.seg = seg;
+    a.k = k;
+    a.kcap = kcap;
+    a.S = S;
+    a.vec4 = (((uintptr_t)A & 15) == 0 && lda % 4 == 0) ? 1 : 0;
+    hipError_t e = launch_select(a, stream);
+    if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+    FinArgs f;
+    memset(&f, 0, sizeof(f));
+    f.lists = (const u64 *)workspace;
+    f.idx = idx;
+    f.dist = val;
+    f.nq = m;
+    f.nq_pad = m;
+    f.k = k;
+    f.kcap = kcap;
+    f.S = S;
+    f.mode = FIN_SELECT;
+    e = launch_finalize(f, stream);
+    if (e != hipSuccess) { set_error("finalize_rows(select)", e); return KNN_EDEVICE; }
+    return KNN_OK;
 }
 
 size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,

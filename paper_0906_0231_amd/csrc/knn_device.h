@@ -57,7 +57,7 @@ struct PairArgs {
     int32_t round;     // 0 .. NBp-2, or -1
 };
 
-enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3 };
+enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3, FIN_SELECT = 4, FIN_RESCORE_HEL = 5 };
 
 struct FinArgs {
     const u64 *lists;
@@ -70,6 +70,16 @@ struct FinArgs {
     int32_t d, k, kcap, S, mode, vec4;
 };
 
+// batched partial sort of a materialised matrix
+struct SelectArgs {
+    const float *A;    // [m, lda]
+    u64 *lists;        // [S, m, kcap]
+    int64_t m, n, lda;
+    int64_t seg;       // columns per segment (multiple of 1024)
+    int32_t k, kcap, S, vec4;
+};
+
+hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query

@@ -82,9 +82,12 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
     }
     for (int64_t row = wave; row < a.n; row += nwaves) {
         const float *x = a.X + row * (int64_t)a.d;
+        // Hellinger (metric 2): everything below sees y = sqrt(x); sum (sqrt u - sqrt v)^2 is
+        // the squared Euclidean distance of the square-rooted rows
+        const bool root = a.metric == 2;
         float s = 0.f;
         for (int c = lane; c < a.d; c += 64) {
-            float v = x[c];
+            float v = root ? sqrtf(x[c]) : x[c];
             s = fmaf(v, v, s);
         }
         s = wave_sum(s);
@@ -101,11 +104,11 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
         }
         if (a.q_out) {
             float *o = a.q_out + row * (int64_t)a.dpad;
-            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? qscale * x[c] : 0.f;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? qscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
         }
         if (a.r_out) {
             float *o = a.r_out + row * (int64_t)a.dpad;
-            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? rscale * x[c] : 0.f;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? rscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
         }
         if (lane == 0) {
             if (a.c_out) a.c_out[row] = cval;
@@ -1201,6 +1204,100 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// select_rows: batched partial sort of a materialised matrix -- the paper's Phase 2 as it
+// states it (Sect. 6): for every row of A[m, n], the k smallest entries.  Bound by HBM
+// (4 bytes per element, read once); nothing else is moved.
+//
+// One wave per (row, column segment).  The paper gives a thread block a row, lets the
+// threads stride it for coalescing, compares each element with the heap's top and
+// buffers the few survivors per thread before a serialised push.  Here a lane reads 16
+// consecutive-by-4 floats per iteration (four 1 KB wave loads in flight), keeps their
+// minimum, and the whole wave takes one branch on "any lane below the threshold"; the
+// survivors are compacted into a wave queue in LDS with ballot/popcount and rank-merged
+// into the row's sorted list (also in LDS) by the same code as the fused kernels.
+// ---------------------------------------------------------------------------
+constexpr int SEL_LOADS = 4;                      // float4 loads in flight per lane
+constexpr int SEL_CHUNK = 64 * 4 * SEL_LOADS;     // columns per wave iteration
+
+__global__ __launch_bounds__(256) void select_rows(SelectArgs a)
+{
+    __shared__ u64 sList[4][KNN_MAX_KCAP];
+    __shared__ u64 sQueue[4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t gw = (int64_t)blockIdx.x * 4 + w;
+    if (gw >= a.m * a.S) return;                  // whole wave; no barriers in this kernel
+    const int64_t row = gw / a.S;
+    const int seg = (int)(gw - row * a.S);
+    const int64_t c0 = (int64_t)seg * a.seg;
+    const int64_t c1 = min(c0 + a.seg, a.n);
+    const float *Arow = a.A + row * a.lda;
+    u64 *L = &sList[w][0];
+    u64 *Q = &sQueue[w][0];
+    for (int i = lane; i < a.kcap; i += 64) L[i] = KEY_INF;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+
+    u64 tau_key = KEY_INF;
+    float tau_p = __builtin_inff();
+    int count = 0;                                // queued candidates (wave-uniform)
+    const float INF = __builtin_inff();
+
+    auto flush = [&]() __attribute__((always_inline)) {
+        if (count == 0) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        u64 nt = merge_one(L, a.kcap, a.k, Q, count, lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        tau_key = nt;
+        tau_p = nt == KEY_INF ? INF : ord2f((uint32_t)(nt >> 32));
+        count = 0;
+    };
+
+    for (int64_t base = c0; base < c1; base += SEL_CHUNK) {
+        f32x4 v[SEL_LOADS];
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) {
+            const int64_t col = base + j * 256 + lane * 4;
+            if (a.vec4 && col + 3 < c1) {
+                v[j] = *(const f32x4 *)(Arow + col);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[j][e] = col + e < c1 ? Arow[col + e] : INF;
+            }
+        }
+        float m = INF;
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) m = fminf(m, fminf(fminf(v[j][0], v[j][1]), fminf(v[j][2], v[j][3])));
+        if (__ballot(m <= tau_p) == 0) continue;
+        // rare path: element by element, survivors compacted into the wave queue
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p = v[j][e];
+                const bool c = p <= tau_p;
+                if (__ballot(c)) {
+                    const int64_t col = base + j * 256 + lane * 4 + e;
+                    const u64 key = make_key(p, (int32_t)col);
+                    const bool pass = c && key < tau_key && col < c1;
+                    u64 bal = __ballot(pass);
+                    int np = __popcll(bal);
+                    if (np) {
+                        if (count + np > 64) flush();     // thresholds move; entries already chosen stay valid candidates
+                        int pos = count + __popcll(bal & ((1ull << lane) - 1ull));
+                        if (pass) Q[pos] = key;
+                        count += np;
+                    }
+                }
+            }
+        }
+        if (count >= 32 || tau_key == KEY_INF) flush();
+    }
+    flush();
+    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
+    for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
+}
+
+// ---------------------------------------------------------------------------
 // finalize_rows: one wave per query.
 // ---------------------------------------------------------------------------
 constexpr int FIN_MAX = KNN_FIN_MAX;   // most keys one query can bring (S * kcap)
@@ -1250,13 +1347,14 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     for (int i = lane; i < kpow; i += 64) outk[i] = KEY_INF;
     __syncthreads();
 
-    if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS) {
+    if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS || a.mode == FIN_RESCORE_HEL) {
         // The k winners are priced again from the original rows, accumulating in
         // double: a direct sum of squared differences (or 1 - cos from the three
         // sums), so the reported value carries neither the cancellation of
         // |u|^2+|v|^2-2u.v nor that of 1-cos in fp32.  n*k*d work, HBM bound.
         const float *x = a.Q + q * (int64_t)a.d;
         const bool cosine = a.mode == FIN_RESCORE_COS;
+        const bool root = a.mode == FIN_RESCORE_HEL;
         for (int r = 0; r < a.k; ++r) {
             int32_t j = (int32_t)(uint32_t)keys[r];
             const float *y = a.R + (int64_t)j * a.d;
@@ -1272,7 +1370,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                             uu = fma(ud, ud, uu);
                             vv = fma(vd, vd, vv);
                         } else {
-                            double t = ud - vd;
+                            double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
                             s = fma(t, t, s);
                         }
                     }
@@ -1285,7 +1383,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                         uu = fma(ud, ud, uu);
                         vv = fma(vd, vd, vv);
                     } else {
-                        double t = ud - vd;
+                        double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
                         s = fma(t, t, s);
                     }
                 }
@@ -1299,6 +1397,8 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
             }
             if (lane == 0) outk[r] = make_key((float)s, j);
         }
+    } else if (a.mode == FIN_SELECT) {
+        for (int r = lane; r < a.k; r += 64) outk[r] = keys[r];   // keys are (value, column) already
     } else {
         const float add = a.mode == FIN_ADD_SQ ? a.sq[q] : 1.0f;
         for (int r = lane; r < a.k; r += 64) {
@@ -1416,6 +1516,13 @@ hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
     case 256: hipLaunchKernelGGL(knn_pairs_qreg<256>, grid, block, 0, stream, a); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
+{
+    int64_t blocks = (a.m * a.S + 3) / 4;
+    hipLaunchKernelGGL(select_rows, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -106,6 +106,12 @@ def unit_rows(n: int, d: int, seed: int, chunk: int = 1 << 16) -> torch.Tensor:
     return x
 
 
+def uniform_rows(n: int, d: int, seed: int) -> torch.Tensor:
+    """i.i.d. U[0,1) entries: non-negative "randomly generated" data, the only thing the
+    paper says about its experiment's input (Sect. 7); Hellinger distance needs >= 0."""
+    return torch.rand(n, d, generator=_gen(seed), dtype=torch.float32)
+
+
 def config(which: int, n: Optional[int] = None, nq: Optional[int] = None) -> Workload:
     """The five benchmark/parity configurations; `n` (and `nq` for config 5)
     shrink them for tests while keeping distribution, d, k and metric."""
@@ -131,4 +137,10 @@ def config(which: int, n: Optional[int] = None, nq: Optional[int] = None) -> Wor
         nq = nq or max(1, n // 8)
         return Workload("c5_mix256_nq%d_nr%d_d128_k16" % (nq, n), mixture(n, 128, 256, seed),
                         nq, 0, 16, "sqeuclidean", False)
-    raise ValueError("config must be 1..5")
+    if which == 6:
+        # the shape of the paper's own experiment (Sect. 7, Table 1): d = 256, k = 100,
+        # Hellinger distance, n = 10 000 .. 80 000
+        n = n or 80000
+        return Workload("paper_table1_n%d_d256_k100_hellinger" % n, uniform_rows(n, 256, seed), n, 0,
+                        100, "hellinger", True)
+    raise ValueError("config must be 1..6")

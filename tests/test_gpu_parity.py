@@ -175,6 +175,38 @@ def test_symmetric_exact_ties():
     _check_rows(D.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
 
 
+# ---------------------------------------------------------------------------
+# Hellinger distance, the distance of the paper's experiment (Sect. 7)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,k,sym", [(1200, 64, 10, 2), (900, 50, 100, 2), (1500, 256, 20, 1)])
+def test_hellinger(n, d, k, sym):
+    X = workloads.uniform_rows(n, d, seed=60 + n)
+    res = knn_build(X.cuda(), k, "hellinger", symmetric=sym)
+    torch.cuda.synchronize()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "hellinger", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+def test_hellinger_perfect_squares_exact():
+    """Inputs a^2 with small integer a: every distance is an integer, ties go to the lower index."""
+    rng = np.random.default_rng(12)
+    A = rng.integers(0, 12, size=(700, 6)).astype(np.float32)
+    X = torch.from_numpy(A * A)
+    res = knn_build(X.cuda(), 9, "hellinger")
+    torch.cuda.synchronize()
+    _check_rows(X.numpy(), np.arange(700), 0, 9, "hellinger", res.idx.cpu().numpy(),
+                res.dist.cpu().numpy(), strict=True)
+
+
+def test_paper_experiment_shape():
+    """n = 10 000, d = 256, k = 100, Hellinger: the smallest column of the paper's Table 1."""
+    w = workloads.config(6, n=10000)
+    res = knn_build(w.R.cuda(), w.k, w.metric, profile=True)
+    torch.cuda.synchronize()
+    _say(f"    gpu: {res.profile.ms_total:.1f} ms total")
+    rows = _sample_rows(w.n, 512, seed=6)
+    _check_rows(w.R.numpy(), rows, 0, w.k, w.metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
 def test_search_equals_build():
     """knn_build(X) == knn_search(X, X, self_offset=0), bit for bit."""
     X = workloads.gaussian(900, 40, seed=3).cuda()

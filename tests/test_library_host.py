@@ -40,6 +40,7 @@ def test_workspace_bytes(lib):
     assert f(4, 4, 8, 4, 0, 1) == 0            # k > n - 1 for a self search
     assert f(4, 4, 8, 4, 0, 0) > 0             # fine when queries are not references
     assert f(10, 10, 8, 3, 7, 0) == 0          # unknown metric
+    assert f(10, 10, 8, 3, 2, 0) > 0           # Hellinger
     assert f(10, 1000, 8, api.KNN_MAX_K + 1, 0, 0) == 0
     n, d, k = 1 << 20, 256, 10
     b = f(n, n, d, k, 0, 1)
