@@ -280,6 +280,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.dist = dist;
     f.nq = nq;
     f.nq_pad = p.nq_pad;
+    f.nr = nr;
     f.d = d;
     f.k = k;
     f.kcap = p.kcap;

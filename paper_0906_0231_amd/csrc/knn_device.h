@@ -67,6 +67,7 @@ struct FinArgs {
     int32_t *idx;      // [nq, k]
     float *dist;       // [nq, k]
     int64_t nq, nq_pad;
+    int64_t nr;        // number of reference rows (indices outside [0, nr) are never dereferenced)
     int32_t d, k, kcap, S, mode, vec4;
 };
 

@@ -1357,6 +1357,10 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
         const bool root = a.mode == FIN_RESCORE_HEL;
         for (int r = 0; r < a.k; ++r) {
             int32_t j = (int32_t)(uint32_t)keys[r];
+            if (j < 0 || j >= a.nr) {             // an unfilled slot (cannot happen for k <= nr - self)
+                if (lane == 0) outk[r] = KEY_INF;
+                continue;
+            }
             const float *y = a.R + (int64_t)j * a.d;
             double s = 0.0, uu = 0.0, vv = 0.0;
             if (a.vec4) {
