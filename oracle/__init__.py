@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "knn_oracle.c")
 _LIB = os.path.join(_HERE, "libknn_oracle.so")
 
-METRICS = {"sqeuclidean": 0, "cosine": 1, "hellinger": 2}
+METRICS = {"sqeuclidean": 0, "cosine": 1, "hellinger": 2, "l1": 3, "linf": 4, "kl": 5}
 
 _lib = None
 

@@ -37,6 +37,16 @@
  *   2  squared Hellinger   sum_c (sqrt(u_c) - sqrt(v_c))^2   (Sect. 7, Eq. 1;
  *      the printed formula lacks the square, without which it would not be
  *      symmetric as Sect. 3 requires).  Inputs must be >= 0.
+ * Further cumulatively computable distances in the sense of Sect. 3 (the paper
+ * asks only that delta be such a fold; it names Kullback-Leibler as the distance
+ * of the work it compares with, Sect. 2, and notes in Sect. 3 that a distance
+ * that is not symmetric needs both orders of every pair):
+ *   3  Manhattan (L1)      dbar(u, v, a) = a + |u - v|
+ *   4  Chebyshev (L-inf)   dbar(u, v, a) = max(a, |u - v|)
+ *   5  Kullback-Leibler    dbar(u, v, a) = a + u ln(u / v), a term with u = 0
+ *      counting 0; delta(q, r) takes the QUERY as the first argument, so it is
+ *      not symmetric.  Inputs must be >= 0 and references > 0 wherever the
+ *      query is > 0 (no normalisation is applied or required).
  */
 #include <math.h>
 #include <stdint.h>
@@ -84,12 +94,33 @@ static double delta(const float *u, const float *v, int32_t d, int metric)
         if (uu == 0.0 || vv == 0.0) return 1.0;
         return 1.0 - uv / (sqrt(uu) * sqrt(vv));
     }
-    /* metric == 2 */
-    {
+    if (metric == 2) {
         double a = 0.0;
         for (int32_t c = 0; c < d; ++c) {
             double t = sqrt((double)u[c]) - sqrt((double)v[c]);
             a = a + t * t;
+        }
+        return a;
+    }
+    if (metric == 3) {
+        double a = 0.0;
+        for (int32_t c = 0; c < d; ++c) a = a + fabs((double)u[c] - (double)v[c]);
+        return a;
+    }
+    if (metric == 4) {
+        double a = 0.0;
+        for (int32_t c = 0; c < d; ++c) {
+            double t = fabs((double)u[c] - (double)v[c]);
+            if (t > a) a = t;
+        }
+        return a;
+    }
+    /* metric == 5 */
+    {
+        double a = 0.0;
+        for (int32_t c = 0; c < d; ++c) {
+            double x = (double)u[c], y = (double)v[c];
+            if (x > 0.0) a = a + x * log(x / y);
         }
         return a;
     }
@@ -112,7 +143,7 @@ int32_t knn_oracle_pair_dists(const float *Q, int64_t nq, const float *R, int64_
 {
     if (!Q || !R || !idx || !out) return 1;
     if (nq < 1 || nr < 1 || d < 1 || k < 1) return 1;
-    if (metric < 0 || metric > 2) return 1;
+    if (metric < 0 || metric > 5) return 1;
     for (int64_t i = 0; i < nq; ++i) {
         for (int32_t r = 0; r < k; ++r) {
             int64_t j = idx[(size_t)i * (size_t)k + (size_t)r];
@@ -188,7 +219,7 @@ int32_t knn_oracle_search(const float *Q, int64_t nq, const float *R, int64_t nr
 {
     if (!Q || !R || !idx || !dist) return 1;
     if (nq < 1 || nr < 1 || d < 1 || k < 1) return 1;
-    if (metric < 0 || metric > 2) return 1;
+    if (metric < 0 || metric > 5) return 1;
     if (nr > (int64_t)INT32_MAX) return 1;
     int32_t failed = 0;
 

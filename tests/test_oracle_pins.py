@@ -38,7 +38,8 @@ def _read_golden(name):
     return out
 
 
-@pytest.mark.parametrize("name", ["hand_sqeuclidean.txt", "hand_cosine.txt"])
+@pytest.mark.parametrize("name", ["hand_sqeuclidean.txt", "hand_cosine.txt", "hand_l1.txt",
+                                  "hand_linf.txt", "hand_kl.txt"])
 def test_hand_examples(name):
     """Hand-computed tables: distance formula, order, lower-index ties, self-exclusion."""
     g = _read_golden(name)
@@ -69,10 +70,23 @@ def _naive_knn(Q, R, k, metric, self_idx):
                     uu += float(Q[i][c]) ** 2
                     vv += float(R[j][c]) ** 2
                 acc = 1.0 if uu == 0 or vv == 0 else 1.0 - uv / (math.sqrt(uu) * math.sqrt(vv))
-            else:
+            elif metric == "hellinger":
                 acc = 0.0
                 for c in range(len(Q[i])):
                     acc += (math.sqrt(float(Q[i][c])) - math.sqrt(float(R[j][c]))) ** 2
+            elif metric == "l1":
+                acc = 0.0
+                for c in range(len(Q[i])):
+                    acc += abs(float(Q[i][c]) - float(R[j][c]))
+            elif metric == "linf":
+                acc = 0.0
+                for c in range(len(Q[i])):
+                    acc = max(acc, abs(float(Q[i][c]) - float(R[j][c])))
+            else:
+                acc = 0.0
+                for c in range(len(Q[i])):
+                    if float(Q[i][c]) > 0:
+                        acc += float(Q[i][c]) * math.log(float(Q[i][c]) / float(R[j][c]))
             row.append(acc)
         taken, ri, rd = set(), [], []
         for _ in range(k):
@@ -90,13 +104,15 @@ def _naive_knn(Q, R, k, metric, self_idx):
     return out_i, out_d
 
 
-@pytest.mark.parametrize("metric", ["sqeuclidean", "cosine", "hellinger"])
+@pytest.mark.parametrize("metric", ["sqeuclidean", "cosine", "hellinger", "l1", "linf", "kl"])
 @pytest.mark.parametrize("n,d,k", [(17, 3, 4), (64, 9, 7), (40, 1, 39)])
 def test_against_naive_triple_loop(metric, n, d, k):
     rng = np.random.default_rng(n * 100 + d)
     X = rng.standard_normal((n, d)).astype(np.float32)
     if metric == "hellinger":
         X = np.abs(X)
+    if metric == "kl":
+        X = np.abs(X) + np.float32(0.5)          # rounding below must not produce a zero reference
     # duplicate a row and quantise a few so that exact ties occur
     X[5] = X[2]
     X[7:12] = np.round(X[7:12])
@@ -247,6 +263,85 @@ def test_against_library_routines(metric):
     td, ti = torch.topk(D, k, dim=1, largest=False)
     assert np.array_equal(idx, ti.numpy())
     np.testing.assert_allclose(dist, td.numpy(), rtol=1e-12)
+
+
+@pytest.mark.parametrize("metric", ["l1", "linf", "kl"])
+def test_fold_distances_against_library_routines(metric):
+    """scipy's cityblock / chebyshev distance matrices and its elementwise x ln(x/y)
+    (rel_entr), summed: independent routes to the same numbers; then a stable argsort."""
+    from scipy.spatial.distance import cdist
+    from scipy.special import rel_entr
+    rng = np.random.default_rng(33)
+    nq, nr, d, k = 60, 500, 24, 9
+    R = rng.random((nr, d)).astype(np.float32) + np.float32(0.05)
+    Q = rng.random((nq, d)).astype(np.float32)
+    Q[3, :5] = 0                                  # zero query coordinates contribute nothing to KL
+    if metric == "kl":
+        D = rel_entr(Q.astype(np.float64)[:, None, :], R.astype(np.float64)[None, :, :]).sum(axis=2)
+    else:
+        D = cdist(Q.astype(np.float64), R.astype(np.float64),
+                  "cityblock" if metric == "l1" else "chebyshev")
+    order = np.argsort(D, axis=1, kind="stable")[:, :k]
+    idx, dist, nxt = oracle.search(Q, R, k, metric)
+    assert np.array_equal(idx, order)
+    np.testing.assert_allclose(dist, np.take_along_axis(D, order, 1), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(nxt, np.sort(D, axis=1)[:, k], rtol=1e-12, atol=1e-13)
+
+
+def test_fold_distances_closed_forms_and_invariants():
+    """What the mathematics fixes: on 0/1 vectors L1 = squared Euclidean = Hamming and L-inf is
+    0 or 1; L-inf <= L1 <= d L-inf; symmetry and the triangle inequality (both are metrics);
+    KL against the uniform distribution is ln d minus the entropy, KL of a distribution with
+    itself is 0, Gibbs' inequality, asymmetry, and scaling the query by s adds s ln s sum(q)."""
+    from scipy.stats import entropy
+    rng = np.random.default_rng(5)
+    B = (rng.random((30, 12)) < 0.4).astype(np.float32)
+    for i in range(0, 30, 3):
+        for j in range(1, 30, 4):
+            ham = float(np.sum(B[i] != B[j]))
+            assert oracle.delta(B[i], B[j], "l1") == ham == oracle.delta(B[i], B[j], "sqeuclidean")
+            assert oracle.delta(B[i], B[j], "linf") == (1.0 if ham > 0 else 0.0)
+    X = rng.standard_normal((25, 7)).astype(np.float32)
+    for m in ("l1", "linf"):
+        for i in range(25):
+            assert oracle.delta(X[i], X[i], m) == 0.0
+            for j in range(i):
+                dij = oracle.delta(X[i], X[j], m)
+                assert dij == oracle.delta(X[j], X[i], m) and dij > 0
+                for l in range(0, 25, 6):
+                    assert dij <= oracle.delta(X[i], X[l], m) + oracle.delta(X[l], X[j], m) + 1e-12
+    for i in range(25):
+        for j in range(i):
+            l1, li = oracle.delta(X[i], X[j], "l1"), oracle.delta(X[i], X[j], "linf")
+            assert li <= l1 <= 7 * li
+    assert oracle.delta(np.array([3, -4, 0.5]), np.array([1, 1, 1]), "l1") == 2 + 5 + 0.5
+    assert oracle.delta(np.array([3, -4, 0.5]), np.array([1, 1, 1]), "linf") == 5
+    d = 16
+    P = rng.random((10, d)).astype(np.float32)
+    P /= P.sum(axis=1, keepdims=True)
+    P = P.astype(np.float32)
+    U = np.full(d, 1.0 / d, dtype=np.float32)       # 1/16 is exact in fp32
+    for i in range(10):
+        p64 = P[i].astype(np.float64)
+        s = p64.sum()
+        # sum p ln(p d) = s ln d - H for the unnormalised entropy H = -sum p ln p
+        want = s * math.log(d) + float(np.sum(p64 * np.log(p64)))
+        assert abs(oracle.delta(P[i], U, "kl") - want) < 1e-14
+        assert abs(oracle.delta(P[i], P[i], "kl")) == 0.0
+        pn = p64 / s
+        for j in range(10):
+            qn = P[j].astype(np.float64) / P[j].astype(np.float64).sum()
+            got = oracle.delta(pn.astype(np.float32), qn.astype(np.float32), "kl")
+            if i != j:
+                assert got > -1e-6                   # Gibbs (inputs are normalised only to fp32 accuracy)
+            ref = entropy(pn.astype(np.float32).astype(np.float64), qn.astype(np.float32).astype(np.float64))
+            # scipy normalises its arguments; ours are normalised to 1e-7, so agree to that order
+            assert abs(got - ref) < 1e-5
+    a, b = P[0], P[1]
+    assert oracle.delta(a, b, "kl") != oracle.delta(b, a, "kl")
+    two = oracle.delta((2 * a).astype(np.float32), b, "kl")
+    assert abs(two - (2 * oracle.delta(a, b, "kl") + 2 * math.log(2) * float(a.astype(np.float64).sum()))) < 1e-14
+    assert oracle.delta(np.array([0, 2.0]), np.array([5, 1.0]), "kl") == 2 * math.log(2)   # 0 ln 0 = 0
 
 
 def test_comparator_accepts_oracle_and_catches_mistakes():
