@@ -20,6 +20,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
+# Vector-ALU ceiling for the fold kernel: its arithmetic is one subtract and one add (or max)
+# per coordinate and pair, single-flop instructions that cannot fuse into FMAs, issued
+# unpacked: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-operations per second
+# (the published 157.3 TFLOP/s vector figure counts packed FMAs, 4 flop per lane and cycle).
+VALU_F32_PLAIN_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md).
@@ -35,7 +40,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the headline one)")
+    ap.add_argument("--config", type=int, default=3, help="workload 1..8 (3 = the headline one; 7 = Manhattan on the vector ALUs, "
+                         "8 = Kullback-Leibler)")
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query-resident")
@@ -126,9 +132,24 @@ def main() -> int:
                    "datagen_s": round(gen_s, 2)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                     "traffic": None, "kernel": "knn_pairs_qreg" if symmetric else "knn_tiles",
+                     "traffic": None, "kernel": "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
+
+    # the fp32 matrix rate this machine sustains (matrix instructions only, ~0.25 s), beside the nominal peak
+    from paper_0906_0231_amd import knn_mfma_calibration
+    knn_mfma_calibration(1 << 16, 2)
+    cal_tflops, _ = knn_mfma_calibration(1 << 22, 2)
+    out["roofline"]["measured_peak"] = cal_tflops
+    out["roofline"]["frac_of_measured_peak"] = achieved / cal_tflops
+
+    if w.metric in ("l1", "linf"):
+        out["roofline"].update({"bound": "alu", "peak": VALU_F32_PLAIN_TOPS,
+                                "frac": achieved / VALU_F32_PLAIN_TOPS, "kernel": "knn_fold",
+                                "peak_derivation": "256 CU x 64 lanes/clk x 2.4 GHz, one flop per "
+                                                   "instruction (sub, add|.|), no packed ops"})
+        out["roofline"].pop("measured_peak", None)
+        out["roofline"].pop("frac_of_measured_peak", None)
 
     tkey = (w.name, out["config"]["schedule"])
     if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3) and not args.block_rows:

@@ -40,9 +40,20 @@ extern "C" {
 typedef enum {
     KNN_SQEUCLIDEAN = 0, /* sum_c (u_c - v_c)^2 */
     KNN_COSINE = 1,      /* 1 - u.v / (|u| |v|); 1 if either vector is all zero */
-    KNN_HELLINGER = 2    /* sum_c (sqrt u_c - sqrt v_c)^2, the distance of the paper's experiment
+    KNN_HELLINGER = 2,   /* sum_c (sqrt u_c - sqrt v_c)^2, the distance of the paper's experiment
                             (Sect. 7, Eq. 1, with the square its printed form lacks);
                             inputs must be >= 0 */
+    /* Sect. 3 asks of a distance only that it be a fold over the coordinates,
+       a_{c+1} = dbar(u_c, v_c, a_c).  The three above reduce to an inner product and run on
+       the matrix cores; so does KNN_KL.  KNN_L1 and KNN_LINF do not: they run the fold
+       itself on the vector ALUs (a separate kernel, bound by the vector instruction rate). */
+    KNN_L1 = 3,          /* sum_c |u_c - v_c| */
+    KNN_LINF = 4,        /* max_c |u_c - v_c| */
+    KNN_KL = 5           /* sum_c q_c ln(q_c / r_c), the QUERY first; terms with q_c = 0 count 0.
+                            Not symmetric (Sect. 3 notes that such a distance needs both orders
+                            of every pair): knn_build evaluates the full square for it.
+                            Inputs must be >= 0, references > 0 wherever a query is > 0; no
+                            normalisation is applied or required */
 } knn_metric_t;
 
 typedef enum {
@@ -161,6 +172,20 @@ knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32
 
 /* Bytes of device workspace knn_select needs (256-byte aligned); 0 if the sizes are invalid. */
 size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k);
+
+/*
+ * Calibration, not part of the method: launches a kernel that does nothing but issue
+ * v_mfma_f32_32x32x2_f32 (the instruction of the fused kernels' contraction) from
+ * `waves_per_simd` (1..4) waves on every SIMD of the device, `mfma_per_wave` of them per wave
+ * on four independent accumulators, so that a caller who times the launch learns the matrix
+ * rate this device sustains under load, to put beside the nominal peak.  One launch executes
+ * waves * mfma_per_wave * 4096 flop, waves = *total_waves (HOST pointer, may be NULL).
+ *   sink  device buffer of at least 4 * 64 * 4 * (compute units) * waves_per_simd bytes
+ *         (one float per lane; the value is meaningless, it keeps the work observable)
+ * Asynchronous on `stream`.  KNN_EINVAL for bad arguments, KNN_EDEVICE on a launch error.
+ */
+knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd, float *sink,
+                                  size_t sink_bytes, int64_t *total_waves, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *knn_status_string(knn_status_t status);

@@ -20,13 +20,17 @@ LIB_PATH = os.path.join(_HERE, "libknn.so")
 KNN_SQEUCLIDEAN = 0
 KNN_COSINE = 1
 KNN_HELLINGER = 2
+KNN_L1 = 3
+KNN_LINF = 4
+KNN_KL = 5
 KNN_OK, KNN_EINVAL, KNN_EUNSUPPORTED, KNN_ENOMEM, KNN_EDEVICE = range(5)
 KNN_MAX_K = 128
-METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KNN_HELLINGER}
+METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KNN_HELLINGER,
+           "l1": KNN_L1, "linf": KNN_LINF, "kl": KNN_KL}
 
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_select", "knn_select_workspace_bytes",
-           "knn_status_string", "knn_last_device_error"]
+           "knn_mfma_calibration", "knn_status_string", "knn_last_device_error"]
 
 
 class KnnProfile(ctypes.Structure):
@@ -80,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
     lib.knn_select_workspace_bytes.restype = sz
     lib.knn_select_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.knn_mfma_calibration.restype = i32
+    lib.knn_mfma_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_status_string.restype = ctypes.c_char_p
     lib.knn_status_string.argtypes = [i32]
     lib.knn_last_device_error.restype = ctypes.c_char_p
@@ -209,3 +215,23 @@ def knn_select(A: torch.Tensor, k: int, *, workspace: Optional[torch.Tensor] = N
         _check(lib.knn_select(A.data_ptr(), m, n, A.stride(0), k, idx.data_ptr(), val.data_ptr(),
                               workspace.data_ptr(), workspace.numel(), stream))
     return idx, val
+
+
+def knn_mfma_calibration(mfma_per_wave: int = 1 << 20, waves_per_simd: int = 2, device=None) -> Tuple[float, float]:
+    """Time the library's matrix-instruction-only kernel; returns (TFLOP/s, ms).  See
+    knn_mfma_calibration in knn.h: a calibration of the device, not part of the method."""
+    lib = load_library()
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    with torch.cuda.device(dev):
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        sink = torch.empty(cus * waves_per_simd * 256, dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream(dev)
+        waves = ctypes.c_int64(0)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        _check(lib.knn_mfma_calibration(mfma_per_wave, waves_per_simd, sink.data_ptr(), sink.numel() * 4,
+                                        ctypes.byref(waves), stream.cuda_stream))
+        stop.record(stream)
+        stop.synchronize()
+        ms = start.elapsed_time(stop)
+    return waves.value * mfma_per_wave * 4096.0 / (ms * 1e-3) / 1e12, ms

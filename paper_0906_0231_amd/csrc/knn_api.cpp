@@ -34,6 +34,8 @@ struct Plan {
     bool qres;      // query tile resident in LDS (knn_tiles_qres): two lists per slice
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
+    bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
+    int64_t refs_per_split; // fold kernel: references per slice, multiple of 32
     int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
     int32_t nlists; // partial lists per query
     size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
@@ -63,6 +65,40 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, Plan &p)
 {
     p.self = self;
+    p.fold = metric == KNN_L1 || metric == KNN_LINF;
+    p.refs_per_split = 0;
+    if (p.fold) {
+        // lane = query, 64 per wave; the reference range is cut so that the device has
+        // several thousand waves to run
+        p.dpad = (int32_t)align_up((size_t)d, 4);
+        p.qreg = p.qres = p.tri = false;
+        p.rcopy = true;
+        p.kcap = list_capacity(k);
+        p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
+        p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
+        p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
+        p.n_cpad = (nr + 31) / 32 * 32;
+        p.B = p.NB = p.NBp = 0;
+        const int64_t groups = (nq + 63) / 64;
+        int64_t S = r_splits > 0 ? r_splits : (8192 + groups - 1) / groups;
+        const int64_t smax = KNN_FIN_MAX / p.kcap;
+        if (S > smax) S = smax;
+        if (S < 1) S = 1;
+        p.refs_per_split = (int64_t)align_up((size_t)((nr + S - 1) / S), 32);
+        p.S = (int32_t)((nr + p.refs_per_split - 1) / p.refs_per_split);
+        p.rt_per_split = 0;
+        p.nlists = p.S;
+        size_t o = 0;
+        p.off_qp = o;                                 // coordinate-major queries [dpad][nq_pad]
+        o = align_up(o + (size_t)p.nq_pad * p.dpad * sizeof(float), 256);
+        p.off_rp = o;                                 // references packed by tile
+        o = align_up(o + (size_t)p.n_cpad * p.dpad * sizeof(float), 256);
+        p.off_c = p.off_sq = o;
+        p.off_lists = o;
+        o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
+        p.total = o;
+        return true;
+    }
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
     const int32_t dpad32 = (int32_t)align_up((size_t)d, 32);
     p.qreg = (variant == 0 || variant == 3) && dpad32 <= KNN_QRES_MAX_D;
@@ -75,7 +111,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
     // symmetric schedule: only for knn_build, only with the register-resident kernel;
     // by default only when a round has enough pairs to fill the GPU
-    p.tri = self && p.qreg && symmetric != 2 && (symmetric == 1 || nr >= 1024 * KNN_TILE);
+    p.tri = self && p.qreg && metric != KNN_KL && symmetric != 2 && (symmetric == 1 || nr >= 1024 * KNN_TILE);
     p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr);
     p.NB = (int32_t)((nr + p.B - 1) / p.B);
     p.NBp = p.NB + (p.NB & 1);
@@ -111,7 +147,7 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
                          int64_t self_offset)
 {
     if (nq < 1 || nr < 1 || d < 1 || k < 1) return KNN_EINVAL;
-    if (metric != KNN_SQEUCLIDEAN && metric != KNN_COSINE && metric != KNN_HELLINGER) return KNN_EINVAL;
+    if ((int)metric < (int)KNN_SQEUCLIDEAN || (int)metric > (int)KNN_KL) return KNN_EINVAL;
     if (self_offset < -1) return KNN_EINVAL;
     if (self_offset >= 0 && self_offset + nq > nr) return KNN_EINVAL;
     if ((int64_t)k > nr - (self_offset >= 0 ? 1 : 0)) return KNN_EINVAL;
@@ -186,7 +222,14 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     ev.record(0, stream);
 
     // ---- prologue: norms and scaled copies ----
-    if (self) {
+    if (p.fold) {
+        TransposeArgs t = {Q, qp, nq, p.nq_pad, d, p.dpad};
+        e = launch_transpose(t, stream);
+        if (e != hipSuccess) { set_error("transpose_pad", e); return KNN_EDEVICE; }
+        PackArgs pk = {R, rp, nr, d, p.dpad};
+        e = launch_pack(pk, stream);
+        if (e != hipSuccess) { set_error("pack_tiles", e); return KNN_EDEVICE; }
+    } else if (self) {
         PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq};
         e = launch_prep(a, stream);
         if (e != hipSuccess) { set_error("prep_rows", e); return KNN_EDEVICE; }
@@ -203,7 +246,26 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     // ---- fused distance + selection ----
     int32_t launches = 1;
     int64_t pairs_computed = p.nq_pad * p.n_cpad;
-    if (p.tri) {
+    if (p.fold) {
+        FoldArgs fa;
+        fa.Qt = qp;
+        fa.Rpk = rp;
+        fa.lists = lists;
+        fa.ldqt = p.nq_pad;
+        fa.nq = nq;
+        fa.nr = nr;
+        fa.nq_pad = p.nq_pad;
+        fa.self_offset = self_offset;
+        fa.refs_per_split = p.refs_per_split;
+        fa.dpad = p.dpad;
+        fa.k = k;
+        fa.kcap = p.kcap;
+        fa.metric = (int32_t)metric;
+        fa.S = p.S;
+        e = launch_fold(fa, stream);
+        if (e != hipSuccess) { set_error("knn_fold", e); return KNN_EDEVICE; }
+        pairs_computed = (nq + 63) / 64 * 64 * p.n_cpad;
+    } else if (p.tri) {
         // one launch for the diagonal blocks, then one per round of disjoint block pairs
         float *cmax = (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
         e = launch_reduce_max(cr, nr, cmax, stream);
@@ -285,7 +347,13 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.k = k;
     f.kcap = p.kcap;
     f.S = p.nlists;
-    if (metric == KNN_COSINE)
+    if (metric == KNN_L1)
+        f.mode = o.rescore == 2 ? FIN_SELECT : FIN_RESCORE_L1;      // the fold's value is the distance
+    else if (metric == KNN_LINF)
+        f.mode = o.rescore == 2 ? FIN_SELECT : FIN_RESCORE_LINF;
+    else if (metric == KNN_KL)
+        f.mode = o.rescore == 2 ? FIN_ADD_SQ_SIGNED : FIN_RESCORE_KL;
+    else if (metric == KNN_COSINE)
         f.mode = o.rescore == 2 ? FIN_ADD_ONE : FIN_RESCORE_COS;
     else if (metric == KNN_HELLINGER)
         f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_HEL;
@@ -432,6 +500,24 @@ size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_met
                            int32_t symmetric)
 {
     return knn_workspace_bytes_ex(nq, nr, d, k, metric, symmetric, nullptr);
+}
+
+knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd, float *sink,
+                                  size_t sink_bytes, int64_t *total_waves, void *stream)
+{
+    g_last_error[0] = 0;
+    if (mfma_per_wave < 16 || mfma_per_wave % 16 != 0 || waves_per_simd < 1 || waves_per_simd > 4 || !sink)
+        return KNN_EINVAL;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { set_error("hipDeviceGetAttribute", e); return KNN_EDEVICE; }
+    const int blocks = cus * waves_per_simd;                 // 4 waves each: one per SIMD
+    if (sink_bytes < (size_t)blocks * 256 * sizeof(float)) return KNN_EINVAL;
+    e = launch_mfma_calibration(mfma_per_wave, blocks, sink, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("mfma_only", e); return KNN_EDEVICE; }
+    if (total_waves) *total_waves = (int64_t)blocks * 4;
+    return KNN_OK;
 }
 
 const char *knn_status_string(knn_status_t s)

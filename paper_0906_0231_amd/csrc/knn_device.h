@@ -42,6 +42,33 @@ struct TileArgs {
     int32_t n_qtiles, n_rtiles, S, rt_per_split;
 };
 
+// fold kernel (distances that are not inner products): lane = query, references from
+// scalar registers
+struct FoldArgs {
+    const float *Qt;   // [dpad, ldqt] queries, coordinate-major (column q = query q)
+    const float *Rpk;  // references packed by tile: [ceil(nr/32)][dpad/4][32 rows][4 coordinates]
+    u64 *lists;        // [S, nq_pad, kcap]
+    int64_t ldqt;
+    int64_t nq, nr, nq_pad;
+    int64_t self_offset;
+    int64_t refs_per_split; // multiple of 32
+    int32_t dpad, k, kcap, metric, S;
+};
+
+struct PackArgs {
+    const float *X;    // [n, d]
+    float *Xpk;        // [ceil(n/32)][dpad/4][32][4]; zero where the source has no value
+    int64_t n;
+    int32_t d, dpad;
+};
+
+struct TransposeArgs {
+    const float *X;    // [n, d]
+    float *Xt;         // [dpad, ldt]; zero where the source has no value
+    int64_t n, ldt;
+    int32_t d, dpad;
+};
+
 // symmetric schedule: one launch = one round of block pairs (round < 0: the diagonal blocks)
 struct PairArgs {
     const float *Qp;   // [n, ldq] query-side copy
@@ -57,7 +84,8 @@ struct PairArgs {
     int32_t round;     // 0 .. NBp-2, or -1
 };
 
-enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3, FIN_SELECT = 4, FIN_RESCORE_HEL = 5 };
+enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3, FIN_SELECT = 4, FIN_RESCORE_HEL = 5,
+       FIN_RESCORE_L1 = 6, FIN_RESCORE_LINF = 7, FIN_RESCORE_KL = 8, FIN_ADD_SQ_SIGNED = 9 };
 
 struct FinArgs {
     const u64 *lists;
@@ -80,6 +108,10 @@ struct SelectArgs {
     int32_t k, kcap, S, vec4;
 };
 
+hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
+hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
+hipError_t launch_transpose(const TransposeArgs &a, hipStream_t stream);
+hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);

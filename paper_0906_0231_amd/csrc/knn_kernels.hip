@@ -85,6 +85,28 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
         // Hellinger (metric 2): everything below sees y = sqrt(x); sum (sqrt u - sqrt v)^2 is
         // the squared Euclidean distance of the square-rooted rows
         const bool root = a.metric == 2;
+        if (a.metric == 5) {
+            // Kullback-Leibler: sum q ln(q/r) = sum q ln q - sum q ln r.  The first sum does
+            // not depend on the reference (deferred, s_out); the second is an inner product
+            // of q with ln r.  ln 0 is replaced by a large negative finite value so that a
+            // zero query coordinate still contributes exactly 0 on the matrix cores.
+            float s = 0.f;
+            for (int c = lane; c < a.d; c += 64) s += x[c] > 0.f ? x[c] * logf(x[c]) : 0.f;
+            s = wave_sum(s);
+            if (a.q_out) {
+                float *o = a.q_out + row * (int64_t)a.dpad;
+                for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? -x[c] : 0.f;
+            }
+            if (a.r_out) {
+                float *o = a.r_out + row * (int64_t)a.dpad;
+                for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? fmaxf(logf(x[c]), -104.f) : 0.f;
+            }
+            if (lane == 0) {
+                if (a.c_out) a.c_out[row] = 0.f;
+                if (a.s_out) a.s_out[row] = s;
+            }
+            continue;
+        }
         float s = 0.f;
         for (int c = lane; c < a.d; c += 64) {
             float v = root ? sqrtf(x[c]) : x[c];
@@ -286,7 +308,7 @@ __device__ __forceinline__ void merge_pending(u64 pend, int kcap, int k, int lan
     }
 }
 
-// State a wave keeps for the selection of its 32 queries.
+// State a wave keeps for the selection of its queries (32 or 64, see merge_queues).
 struct SelState {
     u64 tau_key;      // current k-th best (distance, index) key of the lane's query; KEY_INF if fewer than k
     float tau_p;      // its distance part (+inf while the list is not full)
@@ -299,13 +321,15 @@ struct SelState {
 
 // Rank-merge every non-empty candidate queue of this wave into its list and refresh the
 // thresholds.  Whole wave.
-template <int QC>
+// QPW: queries per wave -- 32 in the matrix kernels (lanes l and l+32 share query l%32),
+// 64 in the fold kernel (one query per lane).
+template <int QC, int QPW = 32>
 __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int lane)
 {
-    const int ql = lane & 31;
+    const int ql = lane & (QPW - 1);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     uint32_t mycnt = *(volatile uint32_t *)&st.cnt[ql];
-    u64 pend = __ballot(mycnt > 0) & 0xffffffffull;
+    u64 pend = __ballot(mycnt > 0) & (QPW == 64 ? ~0ull : 0xffffffffull);
     if (pend == 0) return;
     merge_pending(
         pend, kcap, k, lane,
@@ -319,7 +343,7 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
         });
     st.tau_p = st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-    if (lane < 32) {
+    if (lane < QPW) {
         st.cnt[lane] = 0;
         if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
     }
@@ -337,12 +361,13 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
 // queue loses nothing: the value stays in the block copy and the block is walked again
 // after the merge.
 //   jb0: reference row of register 0 of block 0 for this lane (tile base + 4*(lane/32));
-//   block t adds 32t.
-template <int NB, int QC>
+//   block t adds 32t.  With QPW == 64 (fold kernel: one query per lane, registers are
+//   consecutive references) register r of block t is row jb0 + 16t + r.
+template <int NB, int QC, int QPW = 32>
 __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0, int64_t nr, int kcap,
                                             int k, SelState &st, int lane)
 {
-    const int ql = lane & 31;
+    const int ql = lane & (QPW - 1);
 #pragma unroll 1
     for (int t = 0; t < NB; ++t) {
         f32x16 v = acc[0];
@@ -350,7 +375,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
         for (int b = 1; b < NB; ++b)
             if (t == b) v = acc[b];
         if (__ballot(min16(v) <= st.tau_p) == 0) continue;
-        const int32_t jbase = jb0 + t * 32;
+        const int32_t jbase = jb0 + t * (QPW == 64 ? 16 : 32);
         bool again;
         do {
             bool ovf = false, urgent = false;
@@ -359,7 +384,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                 float p = v[r];
                 bool c = p <= st.tau_p;
                 if (__ballot(c)) {
-                    int32_t j = jbase + 8 * (r >> 2) + (r & 3);
+                    int32_t j = QPW == 64 ? jbase + r : jbase + 8 * (r >> 2) + (r & 3);
                     u64 key = make_key(p, j);
                     if (c && key < st.tau_key && j < nr && j != st.selfj) {
                         uint32_t slot = atomicAdd(&st.cnt[ql], 1u);
@@ -375,7 +400,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                 }
             }
             again = __ballot(ovf) != 0;
-            if (again || __ballot(urgent)) merge_queues<QC>(st, kcap, k, lane);
+            if (again || __ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane);
         } while (again);
     }
 }
@@ -1179,6 +1204,10 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
                 }
             }
             if (last) {
+                // The epilogue is short vector work; at raised priority it does not queue behind
+                // the matrix instructions of the other workgroup's wave on this SIMD, and the
+                // wave is back to feeding the matrix pipe sooner (measured: -1.3 %).
+                __builtin_amdgcn_s_setprio(1);
                 float m2 = fminf(min16(acc0), min16(acc1));
                 if (__ballot(m2 <= sm.tp[tid])) {
                     SelState st = load_state();
@@ -1188,6 +1217,7 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
                     save_state(st);
                 }
                 if (!diag) mirror_scan(rt, true);
+                __builtin_amdgcn_s_setprio(0);
             }
             if (more) stash(last ? 0 : kc + 1, (rt + 1) & 1);
             __syncthreads();
@@ -1200,6 +1230,156 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
         }
         if (!diag) mirror_service(n_rt - 1);
         __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// knn_fold<METRIC>: distances that are a fold over the coordinates but not an inner product
+// (Sect. 3: a_{c+1} = dbar(u_c, v_c, a_c)); here dbar = a + |u - v| (Manhattan) and
+// max(a, |u - v|) (Chebyshev).  This is the paper's own Phase 1 arithmetic (Sect. 5: every
+// thread folds its pair's coordinates into a register), on the vector ALUs: two
+// instructions per coordinate and pair (subtract; add or max with the |.| modifier), so
+// the bound is the vector instruction rate, not the matrix rate.
+//
+// Lane = query (64 per wave, one accumulator per reference of a 32-row tile in its own
+// registers, so the selection is the same register-axis test as in the matrix kernels).
+// The reference coordinates are the same for all 64 lanes: they are read with scalar loads
+// into scalar registers and enter the vector instructions as scalar operands -- no LDS, no
+// vector registers, no barrier; the scalar cache shares them between the waves of a CU.
+// For that the references are re-packed once, tile by tile, in the order the loop consumes
+// them ([tile][4 coordinates][32 rows]): the scalar loads walk one pointer with constant
+// offsets and need no address arithmetic per row.
+// The query side is read coordinate-major (transposed copy), one coalesced 256-byte row per
+// coordinate, and re-read per reference tile from the L1/L2.  Waves are independent: each
+// keeps 64 lists per slice of the reference range.
+// ---------------------------------------------------------------------------
+constexpr int FOLD_NR = 32;                       // references per tile (accumulators per lane)
+constexpr int FOLD_QCAP = 8;
+
+typedef const float __attribute__((address_space(4))) *const_f32_ptr;   // constant address space: scalar loads
+
+template <int METRIC>
+__device__ __forceinline__ float fold_step(float u, float v, float acc)
+{
+    if (METRIC == 3) return acc + fabsf(u - v);
+    return fmaxf(acc, fabsf(u - v));
+}
+
+template <int METRIC>
+__global__ __launch_bounds__(256) void knn_fold(FoldArgs a)
+{
+    __shared__ u64 s_cq[4][64][FOLD_QCAP];
+    __shared__ uint32_t s_cnt[4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t qg = (int64_t)(blockIdx.x / a.S) * 4 + w;
+    const int split = blockIdx.x % a.S;
+    const int64_t q0 = qg * 64;
+    if (q0 >= a.nq) return;                        // whole wave; the kernel has no barrier
+    const int64_t myq = q0 + lane;                 // < nq_pad: the transposed copy is that wide
+    const bool qvalid = myq < a.nq;
+
+    u64 *Lw = a.lists + ((int64_t)split * a.nq_pad + q0) * a.kcap;
+    for (int i = lane; i < 64 * a.kcap; i += 64) Lw[i] = KEY_INF;
+    s_cnt[w][lane] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+
+    SelState st;
+    st.tau_key = qvalid ? KEY_INF : 0ull;
+    st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
+    st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    st.Lw = Lw;
+    st.cq = &s_cq[w][0][0];
+    st.cnt = &s_cnt[w][0];
+    st.shared_tau = nullptr;
+
+    const int64_t j_begin = (int64_t)split * a.refs_per_split;
+    const int64_t j_end = min(a.nr, j_begin + a.refs_per_split);
+    const float *qcol = a.Qt + myq;
+    const_f32_ptr Rc = (const_f32_ptr)a.Rpk;       // never written while this kernel runs
+    const int ncq = a.dpad >> 2;
+
+    for (int64_t j0 = j_begin; j0 < j_end; j0 += FOLD_NR) {
+        float acc[FOLD_NR];
+#pragma unroll
+        for (int r = 0; r < FOLD_NR; ++r) acc[r] = 0.f;
+        // rows past the end of the set are zero rows in the packed copy; the selection discards them
+        const_f32_ptr tile = Rc + (j0 / FOLD_NR) * (int64_t)ncq * (FOLD_NR * 4);
+        f32x4 qn;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) qn[e] = qcol[(int64_t)e * a.ldqt];
+        for (int cq = 0; cq < ncq; ++cq) {
+            const f32x4 q = qn;
+            if (cq + 1 < ncq) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qn[e] = qcol[(int64_t)(4 * cq + 4 + e) * a.ldqt];
+            }
+            const_f32_ptr rp = tile + cq * (FOLD_NR * 4);
+#pragma unroll
+            for (int r = 0; r < FOLD_NR; ++r) {
+                const float v0 = rp[4 * r], v1 = rp[4 * r + 1], v2 = rp[4 * r + 2], v3 = rp[4 * r + 3];
+                float t = acc[r];
+                t = fold_step<METRIC>(q[0], v0, t);
+                t = fold_step<METRIC>(q[1], v1, t);
+                t = fold_step<METRIC>(q[2], v2, t);
+                t = fold_step<METRIC>(q[3], v3, t);
+                acc[r] = t;
+            }
+        }
+        float m = acc[0];
+#pragma unroll
+        for (int r = 1; r < FOLD_NR; ++r) m = fminf(m, acc[r]);
+        if (__ballot(m <= st.tau_p)) {
+            f32x16 blocks[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                blocks[0][r] = acc[r];
+                blocks[1][r] = acc[16 + r];
+            }
+            select_rare<2, FOLD_QCAP, 64>(blocks, (int32_t)j0, a.nr, a.kcap, a.k, st, lane);
+        }
+    }
+    merge_queues<FOLD_QCAP, 64>(st, a.kcap, a.k, lane);
+}
+
+// pack_tiles: Xpk[tile t][coordinate quad cq][row r][e] = X[32 t + r][4 cq + e], zero outside.
+// One thread per (row, quad); consecutive threads take consecutive quads of a row.
+__global__ __launch_bounds__(256) void pack_tiles(PackArgs a)
+{
+    const int ncq = a.dpad >> 2;
+    const int64_t total = (a.n + FOLD_NR - 1) / FOLD_NR * FOLD_NR * (int64_t)ncq;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (int64_t)gridDim.x * 256) {
+        const int64_t row = g / ncq;
+        const int cq = (int)(g - row * ncq);
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int c = 4 * cq + e;
+            v[e] = (row < a.n && c < a.d) ? a.X[row * (int64_t)a.d + c] : 0.f;
+        }
+        const int64_t t = row / FOLD_NR;
+        const int r = (int)(row - t * FOLD_NR);
+        *(f32x4 *)(a.Xpk + ((t * ncq + cq) * FOLD_NR + r) * 4) = v;
+    }
+}
+
+// transpose_pad: Xt[c, q] = X[q, c], zero where c >= d or q >= n.  64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_pad(TransposeArgs a)
+{
+    __shared__ float tile[64][65];
+    const int64_t q0 = (int64_t)blockIdx.x * 64;
+    const int c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t q = q0 + i;
+        const int c = c0 + tx;
+        tile[i][tx] = (q < a.n && c < a.d) ? a.X[q * (int64_t)a.d + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i;
+        const int64_t q = q0 + tx;
+        if (c < a.dpad && q < a.ldt) a.Xt[(int64_t)c * a.ldt + q] = tile[tx][i];
     }
 }
 
@@ -1347,7 +1527,32 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     for (int i = lane; i < kpow; i += 64) outk[i] = KEY_INF;
     __syncthreads();
 
-    if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS || a.mode == FIN_RESCORE_HEL) {
+    if (a.mode == FIN_RESCORE_L1 || a.mode == FIN_RESCORE_LINF || a.mode == FIN_RESCORE_KL) {
+        // the same re-pricing of the k winners in double for the distances of the fold family
+        const float *x = a.Q + q * (int64_t)a.d;
+        for (int r = 0; r < a.k; ++r) {
+            int32_t j = (int32_t)(uint32_t)keys[r];
+            if (j < 0 || j >= a.nr) {
+                if (lane == 0) outk[r] = KEY_INF;
+                continue;
+            }
+            const float *y = a.R + (int64_t)j * a.d;
+            double s = 0.0;
+            for (int c = lane; c < a.d; c += 64) {
+                double ud = (double)x[c], vd = (double)y[c];
+                if (a.mode == FIN_RESCORE_L1) s += fabs(ud - vd);
+                else if (a.mode == FIN_RESCORE_LINF) s = fmax(s, fabs(ud - vd));
+                else if (ud > 0.0) s += ud * log(ud / vd);
+            }
+            if (a.mode == FIN_RESCORE_LINF) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) s = fmax(s, __shfl_xor(s, o, 64));
+            } else {
+                s = wave_sum_f64(s);
+            }
+            if (lane == 0) outk[r] = make_key((float)s, j);
+        }
+    } else if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS || a.mode == FIN_RESCORE_HEL) {
         // The k winners are priced again from the original rows, accumulating in
         // double: a direct sum of squared differences (or 1 - cos from the three
         // sums), so the reported value carries neither the cancellation of
@@ -1404,11 +1609,11 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     } else if (a.mode == FIN_SELECT) {
         for (int r = lane; r < a.k; r += 64) outk[r] = keys[r];   // keys are (value, column) already
     } else {
-        const float add = a.mode == FIN_ADD_SQ ? a.sq[q] : 1.0f;
+        const float add = a.mode == FIN_ADD_ONE ? 1.0f : a.sq[q];
         for (int r = lane; r < a.k; r += 64) {
             u64 key = keys[r];
             float p = ord2f((uint32_t)(key >> 32));
-            float dist = fmaxf(p + add, 0.f);
+            float dist = a.mode == FIN_ADD_SQ_SIGNED ? p + add : fmaxf(p + add, 0.f);
             outk[r] = make_key(dist, (int32_t)(uint32_t)key);
         }
     }
@@ -1419,6 +1624,47 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
         a.idx[q * a.k + r] = (int32_t)(uint32_t)key;
         a.dist[q * a.k + r] = ord2f((uint32_t)(key >> 32));
     }
+}
+
+// ---------------------------------------------------------------------------
+// mfma_only: calibration.  Nothing but the contraction's matrix instruction on four
+// independent accumulators per wave; no memory traffic inside the loop.  Timing it gives
+// the fp32 matrix rate the device sustains under load (clock included).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mfma_only(int64_t groups_of_16, float *sink)
+{
+    f32x16 a0 = {}, a1 = {}, a2 = {}, a3 = {};
+    // operands with busy mantissas that differ from lane to lane and from one instruction to
+    // the next, as real data do (constant operands would flatter the power draw); products
+    // of both signs keep the sums bounded
+    float x[4], y[4];
+    uint32_t hsh = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        hsh = hsh * 1664525u + 1013904223u;
+        x[u] = __uint_as_float(0x3f000000u | (hsh >> 9)) * ((hsh & 256u) ? 1.f : -1.f);
+        hsh = hsh * 1664525u + 1013904223u;
+        y[u] = __uint_as_float(0x3f000000u | (hsh >> 9)) * ((hsh & 256u) ? 1.f : -1.f) * 9.5367431640625e-07f;
+    }
+    for (int64_t i = 0; i < groups_of_16; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u], y[u], a0, 0, 0, 0);
+            a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x[(u + 1) & 3], y[u], a1, 0, 0, 0);
+            a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(x[(u + 2) & 3], y[(u + 1) & 3], a2, 0, 0, 0);
+            a3 = __builtin_amdgcn_mfma_f32_32x32x2f32(x[(u + 3) & 3], y[(u + 2) & 3], a3, 0, 0, 0);
+        }
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t += (a0[e] + a1[e]) + (a2[e] + a3[e]);
+    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(mfma_only, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -1520,6 +1766,35 @@ hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
     case 256: hipLaunchKernelGGL(knn_pairs_qreg<256>, grid, block, 0, stream, a); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)
+{
+    const int64_t groups = (a.nq + 63) / 64;
+    const int64_t blocks = (groups + 3) / 4 * a.S;
+    if (a.metric == 3)
+        hipLaunchKernelGGL(knn_fold<3>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    else if (a.metric == 4)
+        hipLaunchKernelGGL(knn_fold<4>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_pack(const PackArgs &a, hipStream_t stream)
+{
+    int64_t total = (a.n + FOLD_NR - 1) / FOLD_NR * FOLD_NR * (int64_t)(a.dpad >> 2);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(pack_tiles, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose(const TransposeArgs &a, hipStream_t stream)
+{
+    dim3 grid((unsigned)((a.ldt + 63) / 64), (unsigned)((a.dpad + 63) / 64));
+    hipLaunchKernelGGL(transpose_pad, grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

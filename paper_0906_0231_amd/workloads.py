@@ -29,7 +29,7 @@ class Workload:
     nq: int                    # queries are rows self_offset .. self_offset+nq of R
     self_offset: int
     k: int
-    metric: str                # "sqeuclidean" | "cosine"
+    metric: str                # "sqeuclidean" | "cosine" | "hellinger" | "l1" | "linf" | "kl"
     symmetric: bool            # queries == whole reference set (all-pairs self kNN)
 
     @property
@@ -143,4 +143,14 @@ def config(which: int, n: Optional[int] = None, nq: Optional[int] = None) -> Wor
         n = n or 80000
         return Workload("paper_table1_n%d_d256_k100_hellinger" % n, uniform_rows(n, 256, seed), n, 0,
                         100, "hellinger", True)
-    raise ValueError("config must be 1..6")
+    if which == 7:
+        # a distance that is a fold but not an inner product (Sect. 3): Manhattan, on config 2's data
+        n = n or 65536
+        return Workload("fold_l1_mix64_n%d_d128_k32" % n, mixture(n, 128, 64, BASE_SEED + 2), n, 0, 32,
+                        "l1", True)
+    if which == 8:
+        # a distance that is not symmetric (Sect. 3): Kullback-Leibler on strictly positive rows
+        n = n or 65536
+        return Workload("kl_uniform_n%d_d128_k32" % n, uniform_rows(n, 128, seed).add_(0.05), n, 0, 32,
+                        "kl", True)
+    raise ValueError("config must be 1..8")

@@ -1,0 +1,161 @@
+"""GPU parity for the distances beyond the paper's experiment: the fold family of Sect. 3 that
+is not an inner product (Manhattan, Chebyshev: vector-ALU kernel knn_fold) and the
+non-symmetric Kullback-Leibler divergence (matrix-core path, full square).  Each case is
+compared row by row with the CPU oracle through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import compare
+from paper_0906_0231_amd import api, knn_build, knn_search, workloads
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    api.load_library()
+
+
+def _check(Q, R, self_idx, k, metric, g_idx, g_dist, strict=False, atol=0.0):
+    o_idx, o_dist, o_next = oracle.search(Q, R, k, metric, self_idx=self_idx)
+    rep = compare.check(Q, R, metric, o_idx, o_dist, o_next, g_idx, g_dist, self_idx=self_idx,
+                        rtol=RTOL, atol=atol, strict_ties=strict)
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)
+    return rep
+
+
+# several query groups of 64, ragged tails in n and d (d not a multiple of 4), every list capacity,
+# k = n - 1, slices of the reference range
+@pytest.mark.parametrize("metric", ["l1", "linf"])
+@pytest.mark.parametrize("n,d,k,splits", [
+    (1500, 64, 10, 0),
+    (777, 37, 5, 0),
+    (600, 130, 100, 3),
+    (515, 16, 64, 1),
+    (300, 1, 7, 0),
+    (129, 8, 128, 0),
+    (2, 5, 1, 0),
+    (70, 3, 69, 0),
+    (4100, 20, 12, 7),
+])
+def test_fold_build_small(metric, n, d, k, splits):
+    _say(f"  fold build {metric} n={n} d={d} k={k} splits={splits}")
+    X = workloads.gaussian(n, d, seed=4000 + n + d)
+    res = knn_build(X.cuda(), k, metric, r_splits=splits)
+    torch.cuda.synchronize()
+    _check(X.numpy(), X.numpy(), np.arange(n), k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+@pytest.mark.parametrize("metric", ["l1", "linf"])
+@pytest.mark.parametrize("nq,nr,off", [(100, 3000, -1), (257, 2000, 300), (64, 64, 0), (1, 5000, 4999)])
+def test_fold_search(metric, nq, nr, off):
+    _say(f"  fold search {metric} nq={nq} nr={nr} off={off}")
+    R = workloads.mixture(nr, 24, 5, seed=50 + nr)
+    Q = R[off:off + nq].contiguous() if off >= 0 else workloads.gaussian(nq, 24, seed=51)
+    res = knn_search(Q.cuda(), R.cuda(), 8, metric, self_offset=off)
+    torch.cuda.synchronize()
+    self_idx = np.arange(nq) + off if off >= 0 else None
+    _check(Q.numpy(), R.numpy(), self_idx, 8, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+@pytest.mark.parametrize("metric", ["l1", "linf"])
+def test_fold_exact_on_integers(metric):
+    """Small integers: every fold value is exact in fp32, so indices (ties to the lower index
+    included -- the lattice has many) and distances must match the oracle exactly, with and
+    without the re-pricing pass."""
+    rng = np.random.default_rng(8)
+    X = torch.from_numpy(rng.integers(-6, 7, size=(900, 6)).astype(np.float32))
+    for rescore in (0, 2):
+        res = knn_build(X.cuda(), 9, metric, rescore=rescore)
+        torch.cuda.synchronize()
+        o_idx, o_dist, _ = oracle.build_knn(X.numpy(), 9, metric)
+        assert np.array_equal(res.idx.cpu().numpy(), o_idx)
+        assert np.array_equal(res.dist.cpu().numpy().astype(np.float64), o_dist)
+
+
+def test_fold_matches_hamming_on_bits():
+    """On 0/1 rows Manhattan = squared Euclidean = Hamming distance: the vector-ALU kernel and
+    the matrix-core kernel must give the same lists."""
+    rng = np.random.default_rng(9)
+    X = torch.from_numpy((rng.random((2000, 96)) < 0.3).astype(np.float32)).cuda()
+    a = knn_build(X, 10, "l1")
+    b = knn_build(X, 10, "sqeuclidean", symmetric=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+
+
+def test_fold_deterministic_and_search_equals_build():
+    X = workloads.gaussian(3000, 33, seed=12).cuda()
+    a = knn_build(X, 7, "l1")
+    b = knn_build(X, 7, "l1")
+    c = knn_search(X, X, 7, "l1", self_offset=0)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+    assert torch.equal(a.idx, c.idx) and torch.equal(a.dist, c.dist)
+
+
+def test_fold_config_sampled():
+    """The benchmark's Manhattan workload at full size (n = 65 536, d = 128, k = 32), oracle on
+    sampled rows."""
+    w = workloads.config(7)
+    res = knn_build(w.R.cuda(), w.k, w.metric, profile=True)
+    torch.cuda.synchronize()
+    _say(f"    gpu: {res.profile.ms_main:.1f} ms fused kernel")
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([rng.choice(w.n, 300, replace=False), [0, 63, 64, w.n - 1]]))
+    R = w.R.numpy()
+    _check(R[rows], R, rows, w.k, w.metric, res.idx.cpu().numpy()[rows], res.dist.cpu().numpy()[rows])
+
+
+# ---- Kullback-Leibler: not symmetric, matrix-core path ----
+@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("n,d,k", [(1500, 64, 10), (777, 37, 5), (600, 130, 100), (300, 1, 7), (2, 5, 1)])
+def test_kl_build_small(n, d, k, variant):
+    _say(f"  kl build n={n} d={d} k={k} variant={variant}")
+    X = workloads.uniform_rows(n, d, seed=6000 + n).add_(0.05)
+    res = knn_build(X.cuda(), k, "kl", variant=variant, symmetric=1, profile=True)   # the request for the
+    torch.cuda.synchronize()                                                         # triangle is ignored
+    assert res.profile.symmetric == 0
+    _check(X.numpy(), X.numpy(), np.arange(n), k, "kl", res.idx.cpu().numpy(), res.dist.cpu().numpy(),
+           atol=1e-6)
+
+
+def test_kl_is_directional_and_handles_zero_query_coordinates():
+    """delta(q, r) takes the query first: swapping the roles of two sets changes the answer; a zero
+    query coordinate contributes nothing even where the reference is tiny."""
+    R = workloads.uniform_rows(3000, 40, seed=71).add_(0.01)
+    Q = workloads.uniform_rows(200, 40, seed=72)
+    Q[:, ::3] = 0.0
+    res = knn_search(Q.cuda(), R.cuda(), 6, "kl")
+    torch.cuda.synchronize()
+    _check(Q.numpy(), R.numpy(), None, 6, "kl", res.idx.cpu().numpy(), res.dist.cpu().numpy(), atol=1e-6)
+    P = workloads.uniform_rows(500, 16, seed=73).add_(0.05)
+    a = knn_build(P.cuda(), 5, "kl")
+    torch.cuda.synchronize()
+    fwd = a.idx.cpu().numpy()
+    # the oracle with the arguments the other way round is a different problem with a different answer
+    o_idx, _, _ = oracle.build_knn(P.numpy(), 5, "kl")
+    assert np.array_equal(fwd, o_idx)
+    rev = np.array([[oracle.delta(P[j].numpy(), P[i].numpy(), "kl") for j in range(500)] for i in range(40)])
+    rev[np.arange(40), np.arange(40)] = np.inf
+    assert not np.array_equal(np.argsort(rev, axis=1, kind="stable")[:, :5], o_idx[:40])
+
+
+def test_kl_config_sampled():
+    w = workloads.config(8)
+    res = knn_build(w.R.cuda(), w.k, w.metric, profile=True)
+    torch.cuda.synchronize()
+    _say(f"    gpu: {res.profile.ms_main:.1f} ms fused kernel, symmetric={res.profile.symmetric}")
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([rng.choice(w.n, 300, replace=False), [0, 127, 128, w.n - 1]]))
+    R = w.R.numpy()
+    _check(R[rows], R, rows, w.k, w.metric, res.idx.cpu().numpy()[rows], res.dist.cpu().numpy()[rows])

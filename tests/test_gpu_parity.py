@@ -283,6 +283,18 @@ def test_nondefault_stream_and_caller_buffers():
     _check_rows(X.numpy(), np.arange(1000), 0, 5, "sqeuclidean", idx.cpu().numpy(), dist.cpu().numpy())
 
 
+def test_mfma_calibration_runs():
+    """The matrix-instruction-only kernel: right amount of work, a plausible rate, and the
+    sink-size check."""
+    from paper_0906_0231_amd import knn_mfma_calibration
+    tf, ms = knn_mfma_calibration(1 << 14, 2)
+    assert ms > 0 and 1.0 < tf < 200.0
+    lib = api.load_library()
+    sink = torch.empty(64, dtype=torch.float32, device="cuda")
+    st = lib.knn_mfma_calibration(1024, 2, sink.data_ptr(), sink.numel() * 4, None, None)
+    assert st == api.KNN_EINVAL
+
+
 def test_device_error_paths():
     X = workloads.gaussian(100, 8, seed=1).cuda()
     with pytest.raises(api.KnnError) as e:

@@ -60,7 +60,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert call(one, 100, 8, 0, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # k < 1
     assert call(one, 100, 8, 100, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL  # k > n-1
     assert call(one, 1000, 8, 129, 0, one, one, ws, 1 << 30, None) == api.KNN_EUNSUPPORTED
-    assert call(one, 100, 8, 3, 5, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # metric
+    assert call(one, 100, 8, 3, 6, one, one, ws, 1 << 30, None) == api.KNN_EINVAL    # metric
     assert call(one, 100, 8, 3, 0, one, one, None, 1 << 30, None) == api.KNN_EINVAL  # no workspace
     assert call(one, 100, 8, 3, 0, one, one, ws, 16, None) == api.KNN_ENOMEM
     assert call(ctypes.c_void_p(260), 100, 8, 3, 0, one, one, ws, 1 << 30, None) == api.KNN_EINVAL
@@ -68,6 +68,16 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert s(one, 10, one, 100, 8, 3, 0, 95, one, one, ws, 1 << 30, None) == api.KNN_EINVAL  # self range
     assert s(one, 10, one, 100, 8, 3, 0, -2, one, one, ws, 1 << 30, None) == api.KNN_EINVAL
     assert s(one, 10, one, 1 << 31, 8, 3, 0, -1, one, one, ws, 1 << 30, None) == api.KNN_EUNSUPPORTED
+
+
+def test_calibration_rejects_bad_arguments_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    call = lib.knn_mfma_calibration
+    assert call(0, 2, one, 1 << 30, None, None) == api.KNN_EINVAL        # no work
+    assert call(24, 2, one, 1 << 30, None, None) == api.KNN_EINVAL       # not a multiple of 16
+    assert call(1024, 0, one, 1 << 30, None, None) == api.KNN_EINVAL     # waves per SIMD out of range
+    assert call(1024, 5, one, 1 << 30, None, None) == api.KNN_EINVAL
+    assert call(1024, 2, None, 1 << 30, None, None) == api.KNN_EINVAL    # no sink
 
 
 def test_binding_refuses_cpu_tensors(lib):
