@@ -187,6 +187,18 @@ size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k);
 knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd, float *sink,
                                   size_t sink_bytes, int64_t *total_waves, void *stream);
 
+/*
+ * The same for the vector ALUs: every wave issues `pairs_per_wave` times the fold kernel's
+ * instruction pair (v_sub_f32 with a scalar operand, v_add_f32 with the |.| modifier) on 32
+ * independent accumulators.  One launch executes waves * pairs_per_wave * 2 * 64 lane
+ * operations.  pairs_per_wave must be a positive multiple of 128, waves_per_simd 1..8, and
+ * the sink 64 bytes larger than knn_mfma_calibration asks for (the kernel's 16 operand values
+ * are copied there from the host, asynchronously, before the launch).  Errors as for
+ * knn_mfma_calibration.
+ */
+knn_status_t knn_valu_calibration(int64_t pairs_per_wave, int32_t waves_per_simd, float *sink,
+                                  size_t sink_bytes, int64_t *total_waves, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *knn_status_string(knn_status_t status);
 

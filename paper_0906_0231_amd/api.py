@@ -30,7 +30,7 @@ METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KN
 
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_select", "knn_select_workspace_bytes",
-           "knn_mfma_calibration", "knn_status_string", "knn_last_device_error"]
+           "knn_mfma_calibration", "knn_valu_calibration", "knn_status_string", "knn_last_device_error"]
 
 
 class KnnProfile(ctypes.Structure):
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_select_workspace_bytes.argtypes = [i64, i64, i32]
     lib.knn_mfma_calibration.restype = i32
     lib.knn_mfma_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
+    lib.knn_valu_calibration.restype = i32
+    lib.knn_valu_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_status_string.restype = ctypes.c_char_p
     lib.knn_status_string.argtypes = [i32]
     lib.knn_last_device_error.restype = ctypes.c_char_p
@@ -235,3 +237,23 @@ def knn_mfma_calibration(mfma_per_wave: int = 1 << 20, waves_per_simd: int = 2, 
         stop.synchronize()
         ms = start.elapsed_time(stop)
     return waves.value * mfma_per_wave * 4096.0 / (ms * 1e-3) / 1e12, ms
+
+
+def knn_valu_calibration(pairs_per_wave: int = 1 << 22, waves_per_simd: int = 4, device=None) -> Tuple[float, float]:
+    """Time the library's vector-instruction-only kernel; returns (1e12 lane operations per second,
+    ms).  See knn_valu_calibration in knn.h."""
+    lib = load_library()
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    with torch.cuda.device(dev):
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        sink = torch.empty(cus * waves_per_simd * 256 + 16, dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream(dev)
+        waves = ctypes.c_int64(0)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        _check(lib.knn_valu_calibration(pairs_per_wave, waves_per_simd, sink.data_ptr(), sink.numel() * 4,
+                                        ctypes.byref(waves), stream.cuda_stream))
+        stop.record(stream)
+        stop.synchronize()
+        ms = start.elapsed_time(stop)
+    return waves.value * pairs_per_wave * 128.0 / (ms * 1e-3) / 1e12, ms

@@ -35,7 +35,7 @@ struct Plan {
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
-    int64_t refs_per_split; // fold kernel: references per slice, multiple of 32
+    int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
     int32_t nlists; // partial lists per query
     size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
@@ -77,23 +77,25 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
         p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
         p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
-        p.n_cpad = (nr + 31) / 32 * 32;
+        p.n_cpad = (nr + KNN_FOLD_NR - 1) / KNN_FOLD_NR * KNN_FOLD_NR;
         p.B = p.NB = p.NBp = 0;
         const int64_t groups = (nq + 63) / 64;
         int64_t S = r_splits > 0 ? r_splits : (8192 + groups - 1) / groups;
         const int64_t smax = KNN_FIN_MAX / p.kcap;
         if (S > smax) S = smax;
         if (S < 1) S = 1;
-        p.refs_per_split = (int64_t)align_up((size_t)((nr + S - 1) / S), 32);
+        p.refs_per_split = (int64_t)align_up((size_t)((nr + S - 1) / S), KNN_FOLD_NR);
         p.S = (int32_t)((nr + p.refs_per_split - 1) / p.refs_per_split);
         p.rt_per_split = 0;
         p.nlists = p.S;
         size_t o = 0;
-        p.off_qp = o;                                 // coordinate-major queries [dpad][nq_pad]
+        p.off_qp = o;                                 // queries packed by tile of 64 rows
         o = align_up(o + (size_t)p.nq_pad * p.dpad * sizeof(float), 256);
         p.off_rp = o;                                 // references packed by tile
-        o = align_up(o + (size_t)p.n_cpad * p.dpad * sizeof(float), 256);
-        p.off_c = p.off_sq = o;
+        o = align_up(o + (size_t)p.n_cpad * p.dpad * sizeof(float), 256) + 256;   // + one batch of read-ahead
+        p.off_c = o;                                  // here: one bound word per query
+        o = align_up(o + (size_t)p.nq_pad * sizeof(uint32_t), 256);
+        p.off_sq = o;
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
         p.total = o;
@@ -223,12 +225,12 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
 
     // ---- prologue: norms and scaled copies ----
     if (p.fold) {
-        TransposeArgs t = {Q, qp, nq, p.nq_pad, d, p.dpad};
-        e = launch_transpose(t, stream);
-        if (e != hipSuccess) { set_error("transpose_pad", e); return KNN_EDEVICE; }
-        PackArgs pk = {R, rp, nr, d, p.dpad};
+        PackArgs pq = {Q, qp, nq, d, p.dpad, 64, (uint32_t *)cr};
+        e = launch_pack(pq, stream);
+        if (e != hipSuccess) { set_error("pack_tiles(Q)", e); return KNN_EDEVICE; }
+        PackArgs pk = {R, rp, nr, d, p.dpad, KNN_FOLD_NR, nullptr};
         e = launch_pack(pk, stream);
-        if (e != hipSuccess) { set_error("pack_tiles", e); return KNN_EDEVICE; }
+        if (e != hipSuccess) { set_error("pack_tiles(R)", e); return KNN_EDEVICE; }
     } else if (self) {
         PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq};
         e = launch_prep(a, stream);
@@ -248,10 +250,10 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     int64_t pairs_computed = p.nq_pad * p.n_cpad;
     if (p.fold) {
         FoldArgs fa;
-        fa.Qt = qp;
+        fa.Qpk = qp;
         fa.Rpk = rp;
         fa.lists = lists;
-        fa.ldqt = p.nq_pad;
+        fa.bound = (uint32_t *)cr;
         fa.nq = nq;
         fa.nr = nr;
         fa.nq_pad = p.nq_pad;
@@ -516,6 +518,30 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
     if (sink_bytes < (size_t)blocks * 256 * sizeof(float)) return KNN_EINVAL;
     e = launch_mfma_calibration(mfma_per_wave, blocks, sink, (hipStream_t)stream);
     if (e != hipSuccess) { set_error("mfma_only", e); return KNN_EDEVICE; }
+    if (total_waves) *total_waves = (int64_t)blocks * 4;
+    return KNN_OK;
+}
+
+knn_status_t knn_valu_calibration(int64_t pairs_per_wave, int32_t waves_per_simd, float *sink,
+                                  size_t sink_bytes, int64_t *total_waves, void *stream)
+{
+    g_last_error[0] = 0;
+    if (pairs_per_wave < 128 || pairs_per_wave % 128 != 0 || waves_per_simd < 1 || waves_per_simd > 8 || !sink)
+        return KNN_EINVAL;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { set_error("hipDeviceGetAttribute", e); return KNN_EDEVICE; }
+    const int blocks = cus * waves_per_simd;
+    // the kernel reads 16 operand values stored behind the part of the sink it writes
+    if (sink_bytes < ((size_t)blocks * 256 + 16) * sizeof(float)) return KNN_EINVAL;
+    static const float operands[16] = {0.013f, 0.171f, 0.029f, 0.257f, 0.043f, 0.311f, 0.059f, 0.127f,
+                                       0.067f, 0.219f, 0.083f, 0.149f, 0.097f, 0.283f, 0.101f, 0.193f};
+    e = hipMemcpyAsync(sink + (size_t)blocks * 256, operands, sizeof(operands), hipMemcpyHostToDevice,
+                       (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("hipMemcpyAsync", e); return KNN_EDEVICE; }
+    e = launch_valu_calibration(pairs_per_wave, blocks, waves_per_simd, sink, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("valu_only", e); return KNN_EDEVICE; }
     if (total_waves) *total_waves = (int64_t)blocks * 4;
     return KNN_OK;
 }

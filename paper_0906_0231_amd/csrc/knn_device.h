@@ -13,6 +13,9 @@
 #define KNN_FIN_MAX 2048   // most keys per query finalize_rows can merge (S * kcap)
 #define KNN_QRES_MAX_D 256 // largest padded d whose query tile is kept resident in LDS
 #define KNN_TILE 128       // queries per workgroup tile == references per tile
+#ifndef KNN_FOLD_NR
+#define KNN_FOLD_NR 64      // fold kernel: references per tile (accumulators per lane), multiple of 16
+#endif
 
 namespace knn {
 
@@ -45,28 +48,22 @@ struct TileArgs {
 // fold kernel (distances that are not inner products): lane = query, references from
 // scalar registers
 struct FoldArgs {
-    const float *Qt;   // [dpad, ldqt] queries, coordinate-major (column q = query q)
-    const float *Rpk;  // references packed by tile: [ceil(nr/32)][dpad/4][32 rows][4 coordinates]
+    const float *Qpk;  // queries packed by tile of 64 rows: [ceil(nq/64)][dpad/4][64 rows][4 coordinates]
+    const float *Rpk;  // references packed by tile: [ceil(nr/NR)][dpad/4][NR rows][4 coordinates], NR = KNN_FOLD_NR
     u64 *lists;        // [S, nq_pad, kcap]
-    int64_t ldqt;
+    uint32_t *bound;   // [nq_pad] smallest k-th-best distance any slice has reached, order-preserving bits
     int64_t nq, nr, nq_pad;
     int64_t self_offset;
-    int64_t refs_per_split; // multiple of 32
+    int64_t refs_per_split; // multiple of KNN_FOLD_NR
     int32_t dpad, k, kcap, metric, S;
 };
 
 struct PackArgs {
     const float *X;    // [n, d]
-    float *Xpk;        // [ceil(n/32)][dpad/4][32][4]; zero where the source has no value
+    float *Xpk;        // [ceil(n/NR)][dpad/4][NR][4]; zero where the source has no value
     int64_t n;
-    int32_t d, dpad;
-};
-
-struct TransposeArgs {
-    const float *X;    // [n, d]
-    float *Xt;         // [dpad, ldt]; zero where the source has no value
-    int64_t n, ldt;
-    int32_t d, dpad;
+    int32_t d, dpad, rows_per_tile;
+    uint32_t *bound;   // optional [n]: set to "no bound yet" (all ones) on the way
 };
 
 // symmetric schedule: one launch = one round of block pairs (round < 0: the diagonal blocks)
@@ -108,9 +105,9 @@ struct SelectArgs {
     int32_t k, kcap, S, vec4;
 };
 
+hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, int waves_per_simd, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
-hipError_t launch_transpose(const TransposeArgs &a, hipStream_t stream);
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);

@@ -377,6 +377,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
         if (__ballot(min16(v) <= st.tau_p) == 0) continue;
         const int32_t jbase = jb0 + t * (QPW == 64 ? 16 : 32);
         bool again;
+        int rounds = 0;                            // 16 entries, QC per round: a few rounds at most
         do {
             bool ovf = false, urgent = false;
 #pragma unroll 1
@@ -390,7 +391,11 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                         uint32_t slot = atomicAdd(&st.cnt[ql], 1u);
                         if (slot < (uint32_t)QC) {
                             st.cq[ql * QC + slot] = key;
-                            p = __builtin_inff();          // taken: a re-walk must not see it again
+                            // taken: a re-walk must not see it again.  NaN, not +inf: while a list
+                            // is short of k entries its threshold is +inf, and an entry that came
+                            // round again as (+inf, j) would enter the list a second time; the rank
+                            // merge assumes distinct keys
+                            p = __builtin_nanf("");
                             urgent |= slot + 1 >= (uint32_t)(QC / 2) || st.tau_key == KEY_INF;
                         } else {
                             ovf = true;
@@ -399,7 +404,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                     v[r] = p;
                 }
             }
-            again = __ballot(ovf) != 0;
+            again = __ballot(ovf) != 0 && ++rounds < 16;
             if (again || __ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane);
         } while (again);
     }
@@ -1249,14 +1254,27 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
 // For that the references are re-packed once, tile by tile, in the order the loop consumes
 // them ([tile][4 coordinates][32 rows]): the scalar loads walk one pointer with constant
 // offsets and need no address arithmetic per row.
-// The query side is read coordinate-major (transposed copy), one coalesced 256-byte row per
-// coordinate, and re-read per reference tile from the L1/L2.  Waves are independent: each
-// keeps 64 lists per slice of the reference range.
+// The query side uses the same packing with 64 rows per tile: a lane reads its query's four
+// coordinates with one 16-byte load, the wave 1 KB contiguous, the slice of a wave is one
+// contiguous block that is re-read per reference tile from the L2.  Waves are independent:
+// each keeps 64 lists for its slice of the reference range.
+//
+// The slices of one query run at the same time and each starts with an empty list, i.e. no
+// threshold.  A slice's k-th best distance is an upper bound of the final k-th best, so the
+// slices publish theirs (atomic minimum on one word per query in global memory) and test
+// against the smallest one published so far: a value above it cannot be among the final k.
+// A stale read is merely a looser bound.  This keeps the number of queue insertions near
+// that of an unsliced run instead of multiplying it by the number of slices.
 // ---------------------------------------------------------------------------
-constexpr int FOLD_NR = 32;                       // references per tile (accumulators per lane)
+constexpr int FOLD_NR = KNN_FOLD_NR;               // references per tile (accumulators per lane)
 constexpr int FOLD_QCAP = 8;
+#ifndef KNN_FOLD_WAVES
+#define KNN_FOLD_WAVES 4
+#endif
+constexpr int FOLD_WAVES = KNN_FOLD_WAVES;          // waves (query groups) per workgroup
 
 typedef const float __attribute__((address_space(4))) *const_f32_ptr;   // constant address space: scalar loads
+typedef const f32x16 __attribute__((address_space(4))) *const_f32x16_ptr;
 
 template <int METRIC>
 __device__ __forceinline__ float fold_step(float u, float v, float acc)
@@ -1266,14 +1284,23 @@ __device__ __forceinline__ float fold_step(float u, float v, float acc)
 }
 
 template <int METRIC>
-__global__ __launch_bounds__(256) void knn_fold(FoldArgs a)
+__global__ __launch_bounds__(64 * FOLD_WAVES) void knn_fold(FoldArgs a)
 {
-    __shared__ u64 s_cq[4][64][FOLD_QCAP];
-    __shared__ uint32_t s_cnt[4][64];
+    __shared__ u64 s_cq[FOLD_WAVES][64][FOLD_QCAP];
+    __shared__ uint32_t s_cnt[FOLD_WAVES][64];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
-    const int64_t qg = (int64_t)(blockIdx.x / a.S) * 4 + w;
-    const int split = blockIdx.x % a.S;
+    // The waves of a workgroup take consecutive query groups and the same slice of the
+    // reference range: they read the same reference tiles at about the same time, so the
+    // scalar cache fetches each 64-byte line once for all of them (its path to the L2 is narrow).
+    // Workgroups are dealt to the 8 XCDs round-robin by number.  Renumber them so that an XCD
+    // runs a contiguous range of (query block, slice) pairs: the slices of one query block then
+    // run side by side on one XCD and its query values stay in that XCD's L2 between re-reads.
+    // (The grid is a multiple of 8; numbers past the last pair fall out at the test below.)
+    const uint32_t per_xcd = gridDim.x >> 3;
+    const uint32_t vb = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const int64_t qg = (int64_t)(vb / a.S) * FOLD_WAVES + w;
+    const int split = vb % a.S;
     const int64_t q0 = qg * 64;
     if (q0 >= a.nq) return;                        // whole wave; the kernel has no barrier
     const int64_t myq = q0 + lane;                 // < nq_pad: the transposed copy is that wide
@@ -1295,58 +1322,74 @@ __global__ __launch_bounds__(256) void knn_fold(FoldArgs a)
 
     const int64_t j_begin = (int64_t)split * a.refs_per_split;
     const int64_t j_end = min(a.nr, j_begin + a.refs_per_split);
-    const float *qcol = a.Qt + myq;
+    const f32x4 *qp = (const f32x4 *)(a.Qpk + qg * (int64_t)(a.dpad >> 2) * 256) + lane;
+    uint32_t *mybound = a.bound + myq;
+    uint32_t published = 0xffffffffu;
     const_f32_ptr Rc = (const_f32_ptr)a.Rpk;       // never written while this kernel runs
     const int ncq = a.dpad >> 2;
 
     for (int64_t j0 = j_begin; j0 < j_end; j0 += FOLD_NR) {
-        float acc[FOLD_NR];
+        f32x16 acc[FOLD_NR / 16];                  // register 16 t + r: reference j0 + 16 t + r
+        // what the other slices have reached; read now, used after the tile
+        const uint32_t seen = __hip_atomic_load(mybound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int r = 0; r < FOLD_NR; ++r) acc[r] = 0.f;
+        for (int t = 0; t < FOLD_NR / 16; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
         // rows past the end of the set are zero rows in the packed copy; the selection discards them
-        const_f32_ptr tile = Rc + (j0 / FOLD_NR) * (int64_t)ncq * (FOLD_NR * 4);
-        f32x4 qn;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) qn[e] = qcol[(int64_t)e * a.ldqt];
+        const_f32x16_ptr tile = (const_f32x16_ptr)(Rc + (j0 / FOLD_NR) * (int64_t)ncq * (FOLD_NR * 4));
+        f32x4 qn = qp[0];
+        // The scalar loads run one batch (8 rows x 4 coordinates = 128 bytes) ahead of the vector
+        // instructions that consume them; the batch after a tile's last one belongs to the next
+        // tile (or to the padding behind the last tile) and is simply dropped.
+        f32x16 cur0 = tile[0], cur1 = tile[1];
         for (int cq = 0; cq < ncq; ++cq) {
             const f32x4 q = qn;
-            if (cq + 1 < ncq) {
+            if (cq + 1 < ncq) qn = qp[(cq + 1) * 64];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) qn[e] = qcol[(int64_t)(4 * cq + 4 + e) * a.ldqt];
-            }
-            const_f32_ptr rp = tile + cq * (FOLD_NR * 4);
+            for (int b = 0; b < FOLD_NR / 8; ++b) {
+                const f32x16 nxt0 = tile[(cq * (FOLD_NR / 8) + b + 1) * 2];
+                const f32x16 nxt1 = tile[(cq * (FOLD_NR / 8) + b + 1) * 2 + 1];
+                __builtin_amdgcn_sched_barrier(0);
+                // coordinate outermost: consecutive instructions update different accumulators
 #pragma unroll
-            for (int r = 0; r < FOLD_NR; ++r) {
-                const float v0 = rp[4 * r], v1 = rp[4 * r + 1], v2 = rp[4 * r + 2], v3 = rp[4 * r + 3];
-                float t = acc[r];
-                t = fold_step<METRIC>(q[0], v0, t);
-                t = fold_step<METRIC>(q[1], v1, t);
-                t = fold_step<METRIC>(q[2], v2, t);
-                t = fold_step<METRIC>(q[3], v3, t);
-                acc[r] = t;
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[b >> 1][8 * (b & 1) + i] =
+                            fold_step<METRIC>(q[e], cur0[4 * i + e], acc[b >> 1][8 * (b & 1) + i]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[b >> 1][8 * (b & 1) + 4 + i] =
+                            fold_step<METRIC>(q[e], cur1[4 * i + e], acc[b >> 1][8 * (b & 1) + 4 + i]);
+                }
+                cur0 = nxt0;
+                cur1 = nxt1;
             }
         }
-        float m = acc[0];
+        float m = min16(acc[0]);
 #pragma unroll
-        for (int r = 1; r < FOLD_NR; ++r) m = fminf(m, acc[r]);
+        for (int t = 1; t < FOLD_NR / 16; ++t) m = fminf(m, min16(acc[t]));
+        if (seen != 0xffffffffu) st.tau_p = fminf(st.tau_p, ord2f(seen));
         if (__ballot(m <= st.tau_p)) {
-            f32x16 blocks[2];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                blocks[0][r] = acc[r];
-                blocks[1][r] = acc[16 + r];
+            select_rare<FOLD_NR / 16, FOLD_QCAP, 64>(acc, (int32_t)j0, a.nr, a.kcap, a.k, st, lane);
+            const uint32_t mine = (uint32_t)(st.tau_key >> 32);
+            if (qvalid && st.tau_key != KEY_INF && mine < published) {
+                atomicMin(mybound, mine);
+                published = mine;
             }
-            select_rare<2, FOLD_QCAP, 64>(blocks, (int32_t)j0, a.nr, a.kcap, a.k, st, lane);
         }
     }
     merge_queues<FOLD_QCAP, 64>(st, a.kcap, a.k, lane);
 }
 
-// pack_tiles: Xpk[tile t][coordinate quad cq][row r][e] = X[32 t + r][4 cq + e], zero outside.
+// pack_tiles: Xpk[tile t][coordinate quad cq][row r][e] = X[T t + r][4 cq + e], zero outside
+// (T = rows_per_tile).
 // One thread per (row, quad); consecutive threads take consecutive quads of a row.
 __global__ __launch_bounds__(256) void pack_tiles(PackArgs a)
 {
     const int ncq = a.dpad >> 2;
+    const int FOLD_NR = a.rows_per_tile;
     const int64_t total = (a.n + FOLD_NR - 1) / FOLD_NR * FOLD_NR * (int64_t)ncq;
     for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (int64_t)gridDim.x * 256) {
         const int64_t row = g / ncq;
@@ -1360,26 +1403,7 @@ __global__ __launch_bounds__(256) void pack_tiles(PackArgs a)
         const int64_t t = row / FOLD_NR;
         const int r = (int)(row - t * FOLD_NR);
         *(f32x4 *)(a.Xpk + ((t * ncq + cq) * FOLD_NR + r) * 4) = v;
-    }
-}
-
-// transpose_pad: Xt[c, q] = X[q, c], zero where c >= d or q >= n.  64 x 64 tiles through LDS.
-__global__ __launch_bounds__(256) void transpose_pad(TransposeArgs a)
-{
-    __shared__ float tile[64][65];
-    const int64_t q0 = (int64_t)blockIdx.x * 64;
-    const int c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        const int64_t q = q0 + i;
-        const int c = c0 + tx;
-        tile[i][tx] = (q < a.n && c < a.d) ? a.X[q * (int64_t)a.d + c] : 0.f;
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i;
-        const int64_t q = q0 + tx;
-        if (c < a.dpad && q < a.ldt) a.Xt[(int64_t)c * a.ldt + q] = tile[tx][i];
+        if (a.bound != nullptr && cq == 0 && row < a.n) a.bound[row] = 0xffffffffu;
     }
 }
 
@@ -1661,6 +1685,45 @@ __global__ __launch_bounds__(256) void mfma_only(int64_t groups_of_16, float *si
     sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = t;
 }
 
+// valu_only: the fold kernel's instruction pair and nothing else: 32 independent chains, the
+// subtrahend a scalar register, 128 distinct (query value, scalar) combinations per pass.
+__global__ __launch_bounds__(256) void valu_only(int64_t groups_of_128, const float *seed, float *sink)
+{
+    float acc[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc[r] = 0.f;
+    float q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = (float)((threadIdx.x & 63) + 64 * i) * 0.001f;
+    float sv[16];                                  // wave-uniform, from memory: scalar registers
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sv[i] = seed[i];
+    for (int64_t it = 0; it < groups_of_128; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(q[i]));   // opaque: nothing is hoisted or merged
+        // consecutive instructions belong to different chains, as in knn_fold
+#pragma unroll
+        for (int g = 0; g < 8; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[4 * g + i] += fabsf(q[g] - sv[i * 4 + e]);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) t += acc[r];
+    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, int waves_per_simd, float *sink, hipStream_t stream)
+{
+    // the seed values live at the end of the sink, past the part the kernel writes
+    const float *seed = sink + (int64_t)blocks * 256;
+    hipLaunchKernelGGL(valu_only, dim3((unsigned)blocks), dim3(256), 0, stream, pairs_per_wave / 128, seed, sink);
+    (void)waves_per_simd;
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream)
 {
     hipLaunchKernelGGL(mfma_only, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);
@@ -1772,11 +1835,11 @@ hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)
 {
     const int64_t groups = (a.nq + 63) / 64;
-    const int64_t blocks = (groups + 3) / 4 * a.S;
+    const int64_t blocks = ((groups + FOLD_WAVES - 1) / FOLD_WAVES * a.S + 7) / 8 * 8;
     if (a.metric == 3)
-        hipLaunchKernelGGL(knn_fold<3>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(knn_fold<3>, dim3((unsigned)blocks), dim3(64 * FOLD_WAVES), 0, stream, a);
     else if (a.metric == 4)
-        hipLaunchKernelGGL(knn_fold<4>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(knn_fold<4>, dim3((unsigned)blocks), dim3(64 * FOLD_WAVES), 0, stream, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -1784,17 +1847,10 @@ hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)
 
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream)
 {
-    int64_t total = (a.n + FOLD_NR - 1) / FOLD_NR * FOLD_NR * (int64_t)(a.dpad >> 2);
+    int64_t total = (a.n + a.rows_per_tile - 1) / a.rows_per_tile * a.rows_per_tile * (int64_t)(a.dpad >> 2);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(pack_tiles, dim3((unsigned)blocks), dim3(256), 0, stream, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_transpose(const TransposeArgs &a, hipStream_t stream)
-{
-    dim3 grid((unsigned)((a.ldt + 63) / 64), (unsigned)((a.dpad + 63) / 64));
-    hipLaunchKernelGGL(transpose_pad, grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
