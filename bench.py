@@ -21,10 +21,11 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
 # Vector-ALU ceiling for the fold kernel: its arithmetic is one subtract and one add (or max)
-# per coordinate and pair, single-flop instructions that cannot fuse into FMAs, issued
-# unpacked: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-operations per second
-# (the published 157.3 TFLOP/s vector figure counts packed FMAs, 4 flop per lane and cycle).
-VALU_F32_PLAIN_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# per coordinate and pair -- single-flop instructions that cannot fuse into FMAs.  The published
+# 157.3 TFLOP/s fp32 vector figure is 256 CUs x 4 SIMDs x 32 lanes per clock x 2 flop (FMA) x
+# 2.4 GHz; one flop per instruction gives half of it.  (A lone wave issues every 4th cycle, 16
+# lanes per clock; two or more waves of a SIMD reach the 32, measured by knn_valu_calibration.)
+VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 # HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md).
@@ -144,12 +145,15 @@ def main() -> int:
     out["roofline"]["frac_of_measured_peak"] = achieved / cal_tflops
 
     if w.metric in ("l1", "linf"):
+        from paper_0906_0231_amd import knn_valu_calibration
+        knn_valu_calibration(1 << 16, 4)
+        valu_tops, _ = knn_valu_calibration(1 << 21, 4)
         out["roofline"].update({"bound": "alu", "peak": VALU_F32_PLAIN_TOPS,
                                 "frac": achieved / VALU_F32_PLAIN_TOPS, "kernel": "knn_fold",
-                                "peak_derivation": "256 CU x 64 lanes/clk x 2.4 GHz, one flop per "
-                                                   "instruction (sub, add|.|), no packed ops"})
-        out["roofline"].pop("measured_peak", None)
-        out["roofline"].pop("frac_of_measured_peak", None)
+                                "peak_derivation": "256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz, one flop per "
+                                                   "instruction (sub, add|.|): half the published FMA rate",
+                                "measured_peak": valu_tops,
+                                "frac_of_measured_peak": achieved / valu_tops})
 
     tkey = (w.name, out["config"]["schedule"])
     if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3) and not args.block_rows:

@@ -317,20 +317,31 @@ struct SelState {
     u64 *cq;          // the wave's candidate queues in LDS: [32][QCAP]
     uint32_t *cnt;    // their fill counts: [32]
     u64 *shared_tau;  // LDS [32]: bound shared with the other waves serving the same queries, or null
+    uint32_t mine;    // QPW == 64 only: fill count of the lane's own queue (no other lane appends to it)
 };
 
-// Rank-merge every non-empty candidate queue of this wave into its list and refresh the
-// thresholds.  Whole wave.
+// Rank-merge candidate queues of this wave into their lists and refresh the thresholds.
+// Whole wave.  Only queues holding at least min_fill candidates are merged, and those whose
+// list is still short of k entries (no threshold yet): a merge costs about the same for one
+// candidate as for QC, so the others wait -- their thresholds are merely stale, i.e. looser,
+// until they fill up or the caller flushes with min_fill = 1.
 // QPW: queries per wave -- 32 in the matrix kernels (lanes l and l+32 share query l%32),
 // 64 in the fold kernel (one query per lane).
 template <int QC, int QPW = 32>
-__device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int lane)
+__device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int lane, uint32_t min_fill = 1)
 {
     const int ql = lane & (QPW - 1);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-    uint32_t mycnt = *(volatile uint32_t *)&st.cnt[ql];
-    u64 pend = __ballot(mycnt > 0) & (QPW == 64 ? ~0ull : 0xffffffffull);
+    uint32_t mycnt;
+    if (QPW == 64) {                               // one lane per queue: the count lives in a register
+        mycnt = st.mine;
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        mycnt = *(volatile uint32_t *)&st.cnt[ql];
+    }
+    const bool due = mycnt >= min_fill || (mycnt > 0 && st.tau_key == KEY_INF);
+    const u64 pend = __ballot(due) & (QPW == 64 ? ~0ull : 0xffffffffull);
     if (pend == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // the queue entries written by other lanes
     merge_pending(
         pend, kcap, k, lane,
         [&](int qi, u64 *&L, const u64 *&cq, int &nc) {
@@ -343,8 +354,10 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
         });
     st.tau_p = st.tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(st.tau_key >> 32));
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-    if (lane < QPW) {
-        st.cnt[lane] = 0;
+    if (QPW == 64) {
+        if (due) st.mine = 0;
+    } else if (lane < 32) {
+        if ((pend >> lane) & 1ull) st.cnt[lane] = 0;
         if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
@@ -355,7 +368,7 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
 // index (small code, no extra register pressure in the hot loop).  A survivor is tested
 // exactly on the packed (distance, index) key, with the query itself and padding rows
 // excluded, and appended to the query's queue in LDS.  Queues are merged into the lists
-// lazily: when one is half full, when a list is still short of k entries (no threshold
+// lazily: when one is three quarters full, when a list is still short of k entries (no threshold
 // yet), or when the caller flushes at the end of its sweep; until then the threshold is
 // merely stale, i.e. looser, which only lets more candidates into the queue.  A full
 // queue loses nothing: the value stays in the block copy and the block is walked again
@@ -388,7 +401,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                     int32_t j = QPW == 64 ? jbase + r : jbase + 8 * (r >> 2) + (r & 3);
                     u64 key = make_key(p, j);
                     if (c && key < st.tau_key && j < nr && j != st.selfj) {
-                        uint32_t slot = atomicAdd(&st.cnt[ql], 1u);
+                        uint32_t slot = QPW == 64 ? st.mine++ : atomicAdd(&st.cnt[ql], 1u);
                         if (slot < (uint32_t)QC) {
                             st.cq[ql * QC + slot] = key;
                             // taken: a re-walk must not see it again.  NaN, not +inf: while a list
@@ -396,7 +409,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                             // round again as (+inf, j) would enter the list a second time; the rank
                             // merge assumes distinct keys
                             p = __builtin_nanf("");
-                            urgent |= slot + 1 >= (uint32_t)(QC / 2) || st.tau_key == KEY_INF;
+                            urgent |= slot + 1 >= (uint32_t)(QC * 3 / 4) || st.tau_key == KEY_INF;
                         } else {
                             ovf = true;
                         }
@@ -405,7 +418,7 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
                 }
             }
             again = __ballot(ovf) != 0 && ++rounds < 16;
-            if (again || __ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane);
+            if (again || __ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane, QC * 3 / 4);
         } while (again);
     }
 }
@@ -441,6 +454,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
     st.cq = &sm.cq[w][0][0];
     st.cnt = &sm.cnt[w][0];
     st.shared_tau = nullptr;
+    st.mine = 0;
 
     // staging: thread -> (row, 16-byte column) of the DC-wide chunk
     const int lcol = (tid % LD_PER_ROW) * 4;
@@ -627,6 +641,7 @@ __global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
     st.cq = sCq + w * 32 * QR_QCAP;
     st.cnt = sCnt + w * 32;
     st.shared_tau = sTau + qi * 32;
+    st.mine = 0;
 
     // query tile -> LDS, once
     {
@@ -815,6 +830,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     st.cq = &sm.cq[w][0][0];
     st.cnt = &sm.cnt[w][0];
     st.shared_tau = nullptr;
+    st.mine = 0;
 
     // the wave's query operands, once
     f32x4 qreg[NS];
@@ -1056,6 +1072,7 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
             st.cq = &sm.cq[w][0][0];
             st.cnt = &sm.cnt[w][0];
             st.shared_tau = nullptr;
+            st.mine = 0;
             return st;
         };
         auto save_state = [&](const SelState &st) __attribute__((always_inline)) {
@@ -1267,7 +1284,7 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
 // that of an unsliced run instead of multiplying it by the number of slices.
 // ---------------------------------------------------------------------------
 constexpr int FOLD_NR = KNN_FOLD_NR;               // references per tile (accumulators per lane)
-constexpr int FOLD_QCAP = 8;
+constexpr int FOLD_QCAP = 16;
 #ifndef KNN_FOLD_WAVES
 #define KNN_FOLD_WAVES 4
 #endif
@@ -1319,6 +1336,7 @@ __global__ __launch_bounds__(64 * FOLD_WAVES) void knn_fold(FoldArgs a)
     st.cq = &s_cq[w][0][0];
     st.cnt = &s_cnt[w][0];
     st.shared_tau = nullptr;
+    st.mine = 0;
 
     const int64_t j_begin = (int64_t)split * a.refs_per_split;
     const int64_t j_end = min(a.nr, j_begin + a.refs_per_split);

@@ -80,6 +80,16 @@ def test_calibration_rejects_bad_arguments_on_the_host(lib):
     assert call(1024, 2, None, 1 << 30, None, None) == api.KNN_EINVAL    # no sink
 
 
+def test_valu_calibration_rejects_bad_arguments_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    call = lib.knn_valu_calibration
+    assert call(0, 2, one, 1 << 30, None, None) == api.KNN_EINVAL
+    assert call(100, 2, one, 1 << 30, None, None) == api.KNN_EINVAL      # not a multiple of 128
+    assert call(1024, 0, one, 1 << 30, None, None) == api.KNN_EINVAL
+    assert call(1024, 9, one, 1 << 30, None, None) == api.KNN_EINVAL
+    assert call(1024, 2, None, 1 << 30, None, None) == api.KNN_EINVAL
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(ValueError):
