@@ -383,10 +383,16 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
     const int ql = lane & (QPW - 1);
 #pragma unroll 1
     for (int t = 0; t < NB; ++t) {
-        f32x16 v = acc[0];
+        // element by element with constant indices: the blocks stay in registers (a run-time
+        // index into `acc` would give the whole array a home in scratch memory)
+        f32x16 v;
 #pragma unroll
-        for (int b = 1; b < NB; ++b)
-            if (t == b) v = acc[b];
+        for (int e = 0; e < 16; ++e) {
+            float x = acc[0][e];
+#pragma unroll
+            for (int b = 1; b < NB; ++b) x = t == b ? acc[b][e] : x;
+            v[e] = x;
+        }
         if (__ballot(min16(v) <= st.tau_p) == 0) continue;
         const int32_t jbase = jb0 + t * (QPW == 64 ? 16 : 32);
         bool again;
