@@ -423,7 +423,7 @@ knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, 
 static void select_plan(int64_t m, int64_t n, int32_t k, int32_t &kcap, int32_t &S, int64_t &seg)
 {
     kcap = list_capacity(k);
-    int64_t want = (8192 + m - 1) / m;
+    int64_t want = (4096 + m - 1) / m;       // waves wanted in all; measured: more (shorter) segments only add lists
     int64_t most = n / 16384 > 0 ? n / 16384 : 1;
     if (want > most) want = most;
     if (want > KNN_FIN_MAX / kcap) want = KNN_FIN_MAX / kcap;

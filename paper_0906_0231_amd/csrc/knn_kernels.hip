@@ -1453,13 +1453,13 @@ __global__ __launch_bounds__(256) void pack_tiles(PackArgs a)
 //
 // One wave per (row, column segment).  The paper gives a thread block a row, lets the
 // threads stride it for coalescing, compares each element with the heap's top and
-// buffers the few survivors per thread before a serialised push.  Here a lane reads 16
-// consecutive-by-4 floats per iteration (four 1 KB wave loads in flight), keeps their
+// buffers the few survivors per thread before a serialised push.  Here a lane reads 32
+// consecutive-by-4 floats per iteration (eight 1 KB wave loads in flight), keeps their
 // minimum, and the whole wave takes one branch on "any lane below the threshold"; the
 // survivors are compacted into a wave queue in LDS with ballot/popcount and rank-merged
 // into the row's sorted list (also in LDS) by the same code as the fused kernels.
 // ---------------------------------------------------------------------------
-constexpr int SEL_LOADS = 4;                      // float4 loads in flight per lane
+constexpr int SEL_LOADS = 8;                      // float4 loads in flight per lane
 constexpr int SEL_CHUNK = 64 * 4 * SEL_LOADS;     // columns per wave iteration
 
 __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
