@@ -116,6 +116,21 @@ def test_fold_config_sampled():
     _check(R[rows], R, rows, w.k, w.metric, res.idx.cpu().numpy()[rows], res.dist.cpu().numpy()[rows])
 
 
+@pytest.mark.parametrize("metric,k", [("l1", 10), ("linf", 10), ("l1", 100)])
+def test_fold_lists_short_of_k_for_long(metric, k):
+    """n = 65 536 in 8 slices that share their bound: most slices hold fewer than k entries for the
+    whole run, the state in which an entry already queued must not come round again on a re-walk
+    (it did once, as a (+inf, index) key, and the duplicate keys stalled the rank merge)."""
+    _say(f"  fold short lists {metric} k={k}")
+    w = workloads.config(7)
+    res = knn_build(w.R.cuda(), k, metric)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(70 + k)
+    rows = np.unique(np.concatenate([rng.choice(w.n, 150, replace=False), [0, 63, 64, w.n - 1]]))
+    R = w.R.numpy()
+    _check(R[rows], R, rows, k, metric, res.idx.cpu().numpy()[rows], res.dist.cpu().numpy()[rows])
+
+
 # ---- Kullback-Leibler: not symmetric, matrix-core path ----
 @pytest.mark.parametrize("variant", [1, 3])
 @pytest.mark.parametrize("n,d,k", [(1500, 64, 10), (777, 37, 5), (600, 130, 100), (300, 1, 7), (2, 5, 1)])
