@@ -1,0 +1,345 @@
+// Per-row kernels bound by HBM: prep_rows (norms and scaled copies), select_rows (batched partial
+// sort of a materialised matrix, paper Sect. 6), finalize_rows (merge of partial lists, re-score,
+// final order), reduce_max.  Included by knn_kernels.hip only.
+#ifndef KNN_ROWS_KERNELS_H_
+#define KNN_ROWS_KERNELS_H_
+
+namespace knn {
+
+// ---------------------------------------------------------------------------
+// prep_rows: one wave per row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+
+    // rows past the end of the reference set never win: c = +inf
+    if (a.c_out) {
+        int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (g < a.n_cpad - a.n) a.c_out[a.n + g] = __builtin_inff();
+    }
+    for (int64_t row = wave; row < a.n; row += nwaves) {
+        const float *x = a.X + row * (int64_t)a.d;
+        // Hellinger (metric 2): everything below sees y = sqrt(x); sum (sqrt u - sqrt v)^2 is
+        // the squared Euclidean distance of the square-rooted rows
+        const bool root = a.metric == 2;
+        if (a.metric == 5) {
+            // Kullback-Leibler: sum q ln(q/r) = sum q ln q - sum q ln r.  The first sum does
+            // not depend on the reference (deferred, s_out); the second is an inner product
+            // of q with ln r.  ln 0 is replaced by a large negative finite value so that a
+            // zero query coordinate still contributes exactly 0 on the matrix cores.
+            float s = 0.f;
+            for (int c = lane; c < a.d; c += 64) s += x[c] > 0.f ? x[c] * logf(x[c]) : 0.f;
+            s = wave_sum(s);
+            if (a.q_out) {
+                float *o = a.q_out + row * (int64_t)a.dpad;
+                for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? -x[c] : 0.f;
+            }
+            if (a.r_out) {
+                float *o = a.r_out + row * (int64_t)a.dpad;
+                for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? fmaxf(logf(x[c]), -104.f) : 0.f;
+            }
+            if (lane == 0) {
+                if (a.c_out) a.c_out[row] = 0.f;
+                if (a.s_out) a.s_out[row] = s;
+            }
+            continue;
+        }
+        float s = 0.f;
+        for (int c = lane; c < a.d; c += 64) {
+            float v = root ? sqrtf(x[c]) : x[c];
+            s = fmaf(v, v, s);
+        }
+        s = wave_sum(s);
+        float qscale, rscale, cval;
+        if (a.metric == 1) {
+            float inv = s > 0.f ? 1.0f / sqrtf(s) : 0.f;
+            qscale = -inv;
+            rscale = inv;
+            cval = 0.f;
+        } else {
+            qscale = -2.f;
+            rscale = 1.f;
+            cval = s;
+        }
+        if (a.q_out) {
+            float *o = a.q_out + row * (int64_t)a.dpad;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? qscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
+        }
+        if (a.r_out) {
+            float *o = a.r_out + row * (int64_t)a.dpad;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? rscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
+        }
+        if (lane == 0) {
+            if (a.c_out) a.c_out[row] = cval;
+            if (a.s_out) a.s_out[row] = s;
+        }
+    }
+}
+
+
+// ---------------------------------------------------------------------------
+// select_rows: batched partial sort of a materialised matrix -- the paper's Phase 2 as it
+// states it (Sect. 6): for every row of A[m, n], the k smallest entries.  Bound by HBM
+// (4 bytes per element, read once); nothing else is moved.
+//
+// One wave per (row, column segment).  The paper gives a thread block a row, lets the
+// threads stride it for coalescing, compares each element with the heap's top and
+// buffers the few survivors per thread before a serialised push.  Here a lane reads 32
+// consecutive-by-4 floats per iteration (eight 1 KB wave loads in flight), keeps their
+// minimum, and the whole wave takes one branch on "any lane below the threshold"; the
+// survivors are compacted into a wave queue in LDS with ballot/popcount and rank-merged
+// into the row's sorted list (also in LDS) by the same code as the fused kernels.
+// ---------------------------------------------------------------------------
+constexpr int SEL_LOADS = 8;                      // float4 loads in flight per lane
+constexpr int SEL_CHUNK = 64 * 4 * SEL_LOADS;     // columns per wave iteration
+
+__global__ __launch_bounds__(256) void select_rows(SelectArgs a)
+{
+    __shared__ u64 sList[4][KNN_MAX_KCAP];
+    __shared__ u64 sQueue[4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t gw = (int64_t)blockIdx.x * 4 + w;
+    if (gw >= a.m * a.S) return;                  // whole wave; no barriers in this kernel
+    const int64_t row = gw / a.S;
+    const int seg = (int)(gw - row * a.S);
+    const int64_t c0 = (int64_t)seg * a.seg;
+    const int64_t c1 = min(c0 + a.seg, a.n);
+    const float *Arow = a.A + row * a.lda;
+    u64 *L = &sList[w][0];
+    u64 *Q = &sQueue[w][0];
+    for (int i = lane; i < a.kcap; i += 64) L[i] = KEY_INF;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+
+    u64 tau_key = KEY_INF;
+    float tau_p = __builtin_inff();
+    int count = 0;                                // queued candidates (wave-uniform)
+    const float INF = __builtin_inff();
+
+    auto flush = [&]() __attribute__((always_inline)) {
+        if (count == 0) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        u64 nt = merge_one(L, a.kcap, a.k, Q, count, lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        tau_key = nt;
+        tau_p = nt == KEY_INF ? INF : ord2f((uint32_t)(nt >> 32));
+        count = 0;
+    };
+
+    for (int64_t base = c0; base < c1; base += SEL_CHUNK) {
+        f32x4 v[SEL_LOADS];
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) {
+            const int64_t col = base + j * 256 + lane * 4;
+            if (a.vec4 && col + 3 < c1) {
+                v[j] = *(const f32x4 *)(Arow + col);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[j][e] = col + e < c1 ? Arow[col + e] : INF;
+            }
+        }
+        float m = INF;
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) m = fminf(m, fminf(fminf(v[j][0], v[j][1]), fminf(v[j][2], v[j][3])));
+        if (__ballot(m <= tau_p) == 0) continue;
+        // rare path: element by element, survivors compacted into the wave queue
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p = v[j][e];
+                const bool c = p <= tau_p;
+                if (__ballot(c)) {
+                    const int64_t col = base + j * 256 + lane * 4 + e;
+                    const u64 key = make_key(p, (int32_t)col);
+                    const bool pass = c && key < tau_key && col < c1;
+                    u64 bal = __ballot(pass);
+                    int np = __popcll(bal);
+                    if (np) {
+                        if (count + np > 64) flush();     // thresholds move; entries already chosen stay valid candidates
+                        int pos = count + __popcll(bal & ((1ull << lane) - 1ull));
+                        if (pass) Q[pos] = key;
+                        count += np;
+                    }
+                }
+            }
+        }
+        if (count >= 32 || tau_key == KEY_INF) flush();
+    }
+    flush();
+    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
+    for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
+}
+
+// ---------------------------------------------------------------------------
+// finalize_rows: one wave per query.
+// ---------------------------------------------------------------------------
+constexpr int FIN_MAX = KNN_FIN_MAX;   // most keys one query can bring (S * kcap)
+
+__device__ __forceinline__ void bitonic_sort_lds(u64 *keys, int n, int lane)
+{
+    for (int size = 2; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = lane; i < (n >> 1); i += 64) {
+                int lo = 2 * i - (i & (stride - 1));
+                int hi = lo + stride;
+                bool up = (lo & size) == 0;
+                u64 x = keys[lo], y = keys[hi];
+                if ((x > y) == up) {
+                    keys[lo] = y;
+                    keys[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
+{
+    __shared__ u64 keys[FIN_MAX];
+    __shared__ u64 outk[KNN_MAX_KCAP];
+    const int lane = threadIdx.x;
+    const int64_t q = blockIdx.x;
+
+    const int nin = a.S * a.kcap;
+    int npow = 1;
+    while (npow < nin) npow <<= 1;
+    for (int i = lane; i < npow; i += 64) {
+        u64 v = KEY_INF;
+        if (i < nin) {
+            int s = i / a.kcap, e = i - s * a.kcap;
+            v = a.lists[((int64_t)s * a.nq_pad + q) * a.kcap + e];
+        }
+        keys[i] = v;
+    }
+    __syncthreads();
+    if (a.S > 1) bitonic_sort_lds(keys, npow, lane);
+
+    int kpow = 1;
+    while (kpow < a.k) kpow <<= 1;
+    for (int i = lane; i < kpow; i += 64) outk[i] = KEY_INF;
+    __syncthreads();
+
+    if (a.mode == FIN_RESCORE_L1 || a.mode == FIN_RESCORE_LINF || a.mode == FIN_RESCORE_KL) {
+        // the same re-pricing of the k winners in double for the distances of the fold family
+        const float *x = a.Q + q * (int64_t)a.d;
+        for (int r = 0; r < a.k; ++r) {
+            int32_t j = (int32_t)(uint32_t)keys[r];
+            if (j < 0 || j >= a.nr) {
+                if (lane == 0) outk[r] = KEY_INF;
+                continue;
+            }
+            const float *y = a.R + (int64_t)j * a.d;
+            double s = 0.0;
+            for (int c = lane; c < a.d; c += 64) {
+                double ud = (double)x[c], vd = (double)y[c];
+                if (a.mode == FIN_RESCORE_L1) s += fabs(ud - vd);
+                else if (a.mode == FIN_RESCORE_LINF) s = fmax(s, fabs(ud - vd));
+                else if (ud > 0.0) s += ud * log(ud / vd);
+            }
+            if (a.mode == FIN_RESCORE_LINF) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) s = fmax(s, __shfl_xor(s, o, 64));
+            } else {
+                s = wave_sum_f64(s);
+            }
+            if (lane == 0) outk[r] = make_key((float)s, j);
+        }
+    } else if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS || a.mode == FIN_RESCORE_HEL) {
+        // The k winners are priced again from the original rows, accumulating in
+        // double: a direct sum of squared differences (or 1 - cos from the three
+        // sums), so the reported value carries neither the cancellation of
+        // |u|^2+|v|^2-2u.v nor that of 1-cos in fp32.  n*k*d work, HBM bound.
+        const float *x = a.Q + q * (int64_t)a.d;
+        const bool cosine = a.mode == FIN_RESCORE_COS;
+        const bool root = a.mode == FIN_RESCORE_HEL;
+        for (int r = 0; r < a.k; ++r) {
+            int32_t j = (int32_t)(uint32_t)keys[r];
+            if (j < 0 || j >= a.nr) {             // an unfilled slot (cannot happen for k <= nr - self)
+                if (lane == 0) outk[r] = KEY_INF;
+                continue;
+            }
+            const float *y = a.R + (int64_t)j * a.d;
+            double s = 0.0, uu = 0.0, vv = 0.0;
+            if (a.vec4) {
+                for (int c = lane * 4; c < a.d; c += 256) {
+                    f32x4 u = *(const f32x4 *)(x + c), v = *(const f32x4 *)(y + c);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        double ud = (double)u[e], vd = (double)v[e];
+                        if (cosine) {
+                            s = fma(ud, vd, s);
+                            uu = fma(ud, ud, uu);
+                            vv = fma(vd, vd, vv);
+                        } else {
+                            double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
+                            s = fma(t, t, s);
+                        }
+                    }
+                }
+            } else {
+                for (int c = lane; c < a.d; c += 64) {
+                    double ud = (double)x[c], vd = (double)y[c];
+                    if (cosine) {
+                        s = fma(ud, vd, s);
+                        uu = fma(ud, ud, uu);
+                        vv = fma(vd, vd, vv);
+                    } else {
+                        double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
+                        s = fma(t, t, s);
+                    }
+                }
+            }
+            s = wave_sum_f64(s);
+            if (cosine) {
+                uu = wave_sum_f64(uu);
+                vv = wave_sum_f64(vv);
+                s = (uu == 0.0 || vv == 0.0) ? 1.0 : 1.0 - s / (sqrt(uu) * sqrt(vv));
+                if (s < 0.0) s = 0.0;
+            }
+            if (lane == 0) outk[r] = make_key((float)s, j);
+        }
+    } else if (a.mode == FIN_SELECT) {
+        for (int r = lane; r < a.k; r += 64) outk[r] = keys[r];   // keys are (value, column) already
+    } else {
+        const float add = a.mode == FIN_ADD_ONE ? 1.0f : a.sq[q];
+        for (int r = lane; r < a.k; r += 64) {
+            u64 key = keys[r];
+            float p = ord2f((uint32_t)(key >> 32));
+            float dist = a.mode == FIN_ADD_SQ_SIGNED ? p + add : fmaxf(p + add, 0.f);
+            outk[r] = make_key(dist, (int32_t)(uint32_t)key);
+        }
+    }
+    __syncthreads();
+    bitonic_sort_lds(outk, kpow, lane);
+    for (int r = lane; r < a.k; r += 64) {
+        u64 key = outk[r];
+        a.idx[q * a.k + r] = (int32_t)(uint32_t)key;
+        a.dist[q * a.k + r] = ord2f((uint32_t)(key >> 32));
+    }
+}
+
+
+// largest c_j (squared norm) of the data set: scale of the mirror slack
+__global__ __launch_bounds__(1024) void reduce_max(const float *c, int64_t n, float *out)
+{
+    __shared__ float part[16];
+    float m = 0.f;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, c[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 16; ++i) m = fmaxf(m, part[i]);
+        *out = m;
+    }
+}
+
+}  // namespace knn
+
+#endif
