@@ -540,7 +540,7 @@ knn_status_t knn_valu_calibration(int64_t pairs_per_wave, int32_t waves_per_simd
     e = hipMemcpyAsync(sink + (size_t)blocks * 256, operands, sizeof(operands), hipMemcpyHostToDevice,
                        (hipStream_t)stream);
     if (e != hipSuccess) { set_error("hipMemcpyAsync", e); return KNN_EDEVICE; }
-    e = launch_valu_calibration(pairs_per_wave, blocks, waves_per_simd, sink, (hipStream_t)stream);
+    e = launch_valu_calibration(pairs_per_wave, blocks, sink, (hipStream_t)stream);
     if (e != hipSuccess) { set_error("valu_only", e); return KNN_EDEVICE; }
     if (total_waves) *total_waves = (int64_t)blocks * 4;
     return KNN_OK;

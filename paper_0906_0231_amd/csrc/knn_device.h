@@ -105,7 +105,7 @@ struct SelectArgs {
     int32_t k, kcap, S, vec4;
 };
 
-hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, int waves_per_simd, float *sink, hipStream_t stream);
+hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);

@@ -50,8 +50,9 @@ __device__ __forceinline__ float fold_step(float u, float v, float acc)
     return fmaxf(acc, fabsf(u - v));
 }
 
+// (four waves per SIMD: the register allocation is capped at 128 so that the rare path cannot cost one)
 template <int METRIC>
-__global__ __launch_bounds__(64 * FOLD_WAVES) void knn_fold(FoldArgs a)
+__global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOLD_WAVES) void knn_fold(FoldArgs a)
 {
     __shared__ u64 s_cq[FOLD_WAVES][64][FOLD_QCAP];
     __shared__ uint32_t s_cnt[FOLD_WAVES][64];

@@ -43,12 +43,11 @@ typedef __attribute__((address_space(3))) void *lds_ptr;
 
 namespace knn {
 
-hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, int waves_per_simd, float *sink, hipStream_t stream)
+hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream)
 {
     // the seed values live at the end of the sink, past the part the kernel writes
     const float *seed = sink + (int64_t)blocks * 256;
     hipLaunchKernelGGL(valu_only, dim3((unsigned)blocks), dim3(256), 0, stream, pairs_per_wave / 128, seed, sink);
-    (void)waves_per_simd;
     return hipGetLastError();
 }
 
@@ -132,14 +131,21 @@ hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
 {
     dim3 grid((unsigned)blocks), block(256);
     switch (a.dpad) {
-    case 32: hipLaunchKernelGGL(knn_pairs_qreg<32>, grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL(knn_pairs_qreg<64>, grid, block, 0, stream, a); break;
-    case 96: hipLaunchKernelGGL(knn_pairs_qreg<96>, grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL(knn_pairs_qreg<128>, grid, block, 0, stream, a); break;
-    case 160: hipLaunchKernelGGL(knn_pairs_qreg<160>, grid, block, 0, stream, a); break;
-    case 192: hipLaunchKernelGGL(knn_pairs_qreg<192>, grid, block, 0, stream, a); break;
-    case 224: hipLaunchKernelGGL(knn_pairs_qreg<224>, grid, block, 0, stream, a); break;
-    case 256: hipLaunchKernelGGL(knn_pairs_qreg<256>, grid, block, 0, stream, a); break;
+    case 32: hipLaunchKernelGGL((knn_pairs_qreg<32, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_pairs_qreg<64, true>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_pairs_qreg<96, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_pairs_qreg<128, true>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_pairs_qreg<160, true>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_pairs_qreg<192, true>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_pairs_qreg<224, true>), grid, block, 0, stream, a); break;
+    case 256:
+        // at the register limit: the mask scan costs the matrix loop spills that only pay
+        // while candidates are frequent, i.e. for the smaller problems
+        if (a.n < (1 << 19))
+            hipLaunchKernelGGL((knn_pairs_qreg<256, true>), grid, block, 0, stream, a);
+        else
+            hipLaunchKernelGGL((knn_pairs_qreg<256, false>), grid, block, 0, stream, a);
+        break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

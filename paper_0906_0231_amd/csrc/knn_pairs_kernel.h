@@ -46,7 +46,7 @@ struct __attribute__((aligned(16))) PairSmem {
     u64 tkey[256];                                // threshold key of the thread's query
     float tp[256];                                // its distance part
     float cqv[256];                               // c of the thread's query (+inf: no valid query)
-    uint32_t taken[256];                          // mirror entries of the current tile already queued
+    uint32_t taken[256];                          // mirror entries of the current tile: still without a slot (mask scan) / already queued (walk)
 };
 
 __device__ __forceinline__ float mirror_T(u64 tkey, float cj, float cmax, float abound)
@@ -58,7 +58,13 @@ __device__ __forceinline__ float mirror_T(u64 tkey, float cj, float cmax, float 
     return (t + cj) + slack + slack;
 }
 
-template <int DPAD>
+// MASKSCAN: how the mirror candidates of a tile are collected once the cheap test has fired --
+// per-lane bit masks and lowest-bit passes (true), or a walk over the 32 registers with one
+// ballot each (false).  The mask version is several times cheaper per call, which matters
+// while thresholds are loose (small n, early rounds), but at d = 256 its few extra live
+// registers push spills into the matrix loop (+4.7 % at n = 2^20, -5 % at n = 2^18): the host
+// picks the walk for d = 256 and large n.
+template <int DPAD, bool MASKSCAN>
 __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
 {
     constexpr int NK = DPAD / QG_DC;
@@ -178,8 +184,8 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
         __syncthreads();
 
         // Mirror candidates of one tile: cheap one-sided test per register, exact test for
-        // survivors, per-row queue (by tile parity).  Entries that found a slot are recorded
-        // in a per-lane bit mask so that a re-scan after an overflow skips them (the
+        // survivors, per-row queue (by tile parity).  Entries that found no slot are recorded
+        // in a per-lane bit mask, which is all a re-scan after an overflow looks at (the
         // accumulators themselves are only ever read here).
         auto mirror_scan = [&](int rt, bool fresh) __attribute__((always_inline)) {
             const int par = rt & 1;
@@ -199,36 +205,89 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
                 if (fresh) sm.taken[tid] = 0;
                 return;
             }
-            uint32_t taken = fresh ? 0u : sm.taken[tid];
-            bool ovf = false;
-#pragma unroll 1
-            for (int t = 0; t < 2; ++t) {
-                const f32x16 v = t == 0 ? acc0 : acc1;
-#pragma unroll 1
-                for (int r = 0; r < 16; ++r) {
-                    const int m = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    const uint32_t bit = 1u << (t * 16 + r);
-                    const float p = v[r];
-                    bool c = qvalid && !(taken & bit) && sm.T[par][m] - p >= cq;
-                    if (__ballot(c)) {
-                        if (c) {
-                            float p2 = (p - sm.c[par][m]) + cq;          // this pair seen from row m
+            if constexpr (MASKSCAN) {
+                // Which of the lane's 32 values may pass: a bit mask built with constant register
+                // indices (a re-scan after an overflow takes up the bits that found no slot).  Then
+                // passes in which every lane handles ITS lowest marked entry, different entries in
+                // different lanes at once: as many passes as the busiest lane has candidates.
+                uint32_t mask;
+                if (fresh) {
+                    mask = 0;
+    #pragma unroll
+                    for (int gg = 0; gg < 4; ++gg) {
+                        f32x4 t0 = *(const f32x4 *)&sm.T[par][gg * 8 + h * 4];
+                        f32x4 t1 = *(const f32x4 *)&sm.T[par][32 + gg * 8 + h * 4];
+    #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            mask |= t0[e] - acc0[4 * gg + e] >= cq ? 1u << (4 * gg + e) : 0u;
+                            mask |= t1[e] - acc1[4 * gg + e] >= cq ? 1u << (16 + 4 * gg + e) : 0u;
+                        }
+                    }
+                    if (!qvalid) mask = 0;
+                } else {
+                    mask = sm.taken[tid];
+                }
+                uint32_t deferred = 0;
+    #pragma unroll 1
+                for (int t = 0; t < 2; ++t) {
+                    const f32x16 v = t == 0 ? acc0 : acc1;
+                    uint32_t m16 = (mask >> (16 * t)) & 0xffffu;
+    #pragma unroll 1
+                    for (int pass = 0; pass < 16 && __ballot(m16 != 0); ++pass) {
+                        const int r = m16 ? __builtin_ctz(m16) : 0;
+                        float p = v[0];
+    #pragma unroll
+                        for (int e = 1; e < 16; ++e) p = r == e ? v[e] : p;
+                        const int m = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (m16 != 0 && sm.T[par][m] - p >= cq) {      // the threshold may have been refreshed
+                            float p2 = (p - sm.c[par][m]) + cq;        // this pair seen from row m
                             u64 key = make_key(p2, (int32_t)myq);
                             if (key < sm.mtau[par][m]) {
                                 uint32_t slot = atomicAdd(&sm.mcnt[par][m], 1u);
-                                if (slot < (uint32_t)MQCAP) {
+                                if (slot < (uint32_t)MQCAP)
                                     sm.mq[par][m][slot] = key;
-                                    taken |= bit;
-                                } else {
-                                    ovf = true;
+                                else
+                                    deferred |= 1u << (16 * t + r);    // no slot: again after the merge
+                            }
+                        }
+                        m16 &= m16 - 1;
+                    }
+                }
+                sm.taken[tid] = deferred;
+                if (deferred) atomicOr(&sm.movf[par], 1u);
+            } else {
+                // walk: sm.taken holds the entries already queued, which a re-scan skips
+                uint32_t taken = fresh ? 0u : sm.taken[tid];
+                bool ovf = false;
+#pragma unroll 1
+                for (int t = 0; t < 2; ++t) {
+                    const f32x16 v = t == 0 ? acc0 : acc1;
+#pragma unroll 1
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        const uint32_t bit = 1u << (t * 16 + r);
+                        const float p = v[r];
+                        bool c = qvalid && !(taken & bit) && sm.T[par][m] - p >= cq;
+                        if (__ballot(c)) {
+                            if (c) {
+                                float p2 = (p - sm.c[par][m]) + cq;      // this pair seen from row m
+                                u64 key = make_key(p2, (int32_t)myq);
+                                if (key < sm.mtau[par][m]) {
+                                    uint32_t slot = atomicAdd(&sm.mcnt[par][m], 1u);
+                                    if (slot < (uint32_t)MQCAP) {
+                                        sm.mq[par][m][slot] = key;
+                                        taken |= bit;
+                                    } else {
+                                        ovf = true;
+                                    }
                                 }
                             }
                         }
                     }
                 }
+                sm.taken[tid] = taken;
+                if (ovf) atomicOr(&sm.movf[par], 1u);
             }
-            sm.taken[tid] = taken;
-            if (ovf) atomicOr(&sm.movf[par], 1u);
         };
         // Wave w merges the queued mirror candidates of rows 16w..16w+15 of tile rt.
         auto mirror_merge = [&](int rt, bool refresh) __attribute__((always_inline)) {

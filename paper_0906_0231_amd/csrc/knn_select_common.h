@@ -233,15 +233,17 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
 }
 
 // The rare path of the selection: some accumulator of this wave is below its query's
-// threshold.  One 32x32 block at a time, its 16 registers are walked with a run-time
-// index (small code, no extra register pressure in the hot loop).  A survivor is tested
-// exactly on the packed (distance, index) key, with the query itself and padding rows
-// excluded, and appended to the query's queue in LDS.  Queues are merged into the lists
-// lazily: when one is three quarters full, when a list is still short of k entries (no threshold
-// yet), or when the caller flushes at the end of its sweep; until then the threshold is
-// merely stale, i.e. looser, which only lets more candidates into the queue.  A full
-// queue loses nothing: the value stays in the block copy and the block is walked again
-// after the merge.
+// threshold.  One block of 16 registers at a time.  Every lane first marks, in a bit mask, which
+// of its 16 values pass the threshold (constant register indices); then the wave loops while any
+// lane has a bit left, each lane taking ITS lowest marked register -- different registers in
+// different lanes in the same pass -- so the passes number as many as the busiest lane has
+// candidates (one or two), not 16.  A survivor is tested exactly on the packed
+// (distance, index) key, with the query itself and padding rows excluded, and appended to the
+// query's queue in LDS.  Queues are merged into the lists lazily: when one is three quarters
+// full, when a list is still short of k entries (no threshold yet), or when the caller flushes
+// at the end of its sweep; until then the threshold is merely stale, i.e. looser, which only
+// lets more candidates into the queue.  A full queue loses nothing: the lane keeps its bit,
+// the queues are merged, and the lane tries again in the next pass.
 //   jb0: reference row of register 0 of block 0 for this lane (tile base + 4*(lane/32));
 //   block t adds 32t.  With QPW == 64 (fold kernel: one query per lane, registers are
 //   consecutive references) register r of block t is row jb0 + 16t + r.
@@ -252,58 +254,52 @@ __device__ __forceinline__ void select_rare(const f32x16 (&acc)[NB], int32_t jb0
     const int ql = lane & (QPW - 1);
 #pragma unroll 1
     for (int t = 0; t < NB; ++t) {
+        // the block, picked element by element with constant indices so that everything stays in
+        // registers (a run-time index would give the array a home in scratch memory)
         f32x16 v;
-        if (QPW == 64) {
-            // The fold kernel passes its live accumulators: pick the block element by element
-            // with constant indices, so that they stay in registers (a run-time index would
-            // give the whole array a home in scratch memory, written every tile).
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float x = acc[0][e];
+        for (int e = 0; e < 16; ++e) {
+            float x = acc[0][e];
 #pragma unroll
-                for (int b = 1; b < NB; ++b) x = t == b ? acc[b][e] : x;
-                v[e] = x;
-            }
-        } else {
-            // The matrix kernels pass a copy made on this rare path only.
-            v = acc[0];
-#pragma unroll
-            for (int b = 1; b < NB; ++b)
-                if (t == b) v = acc[b];
+            for (int b = 1; b < NB; ++b) x = t == b ? acc[b][e] : x;
+            v[e] = x;
         }
-        if (__ballot(min16(v) <= st.tau_p) == 0) continue;
+        uint32_t mask = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mask |= v[e] <= st.tau_p ? 1u << e : 0u;
+        if (__ballot(mask != 0) == 0) continue;
         const int32_t jbase = jb0 + t * (QPW == 64 ? 16 : 32);
-        bool again;
-        int rounds = 0;                            // 16 entries, QC per round: a few rounds at most
-        do {
-            bool ovf = false, urgent = false;
+        bool urgent = false;
+        // every pass clears a bit in each busy lane, or merges the queue that was full: at most
+        // 16 + 16 passes; the bound is a guard, not a mechanism
 #pragma unroll 1
-            for (int r = 0; r < 16; ++r) {
-                float p = v[r];
-                bool c = p <= st.tau_p;
-                if (__ballot(c)) {
-                    int32_t j = QPW == 64 ? jbase + r : jbase + 8 * (r >> 2) + (r & 3);
-                    u64 key = make_key(p, j);
-                    if (c && key < st.tau_key && j < nr && j != st.selfj) {
-                        uint32_t slot = QPW == 64 ? st.mine++ : atomicAdd(&st.cnt[ql], 1u);
-                        if (slot < (uint32_t)QC) {
-                            st.cq[ql * QC + slot] = key;
-                            // taken: a re-walk must not see it again.  NaN, not +inf: while a list
-                            // is short of k entries its threshold is +inf, and an entry that came
-                            // round again as (+inf, j) would enter the list a second time; the rank
-                            // merge assumes distinct keys
-                            p = __builtin_nanf("");
-                            urgent |= slot + 1 >= (uint32_t)(QC * 3 / 4) || st.tau_key == KEY_INF;
-                        } else {
-                            ovf = true;
-                        }
-                    }
-                    v[r] = p;
+        for (int pass = 0; pass < 64 && __ballot(mask != 0); ++pass) {
+            const int r = mask ? __builtin_ctz(mask) : 0;
+            float p = v[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) p = r == e ? v[e] : p;
+            const int32_t j = QPW == 64 ? jbase + r : jbase + 8 * (r >> 2) + (r & 3);
+            const u64 key = make_key(p, j);
+            // the thresholds may have moved since the mask was made
+            const bool want = mask != 0 && p <= st.tau_p && key < st.tau_key && j < nr && j != st.selfj;
+            bool full = false;
+            if (want) {
+                uint32_t slot = QPW == 64 ? st.mine : atomicAdd(&st.cnt[ql], 1u);
+                if (slot < (uint32_t)QC) {
+                    st.cq[ql * QC + slot] = key;
+                    if (QPW == 64) st.mine = slot + 1;
+                    urgent |= slot + 1 >= (uint32_t)(QC * 3 / 4) || st.tau_key == KEY_INF;
+                } else {
+                    full = true;
                 }
             }
-            again = __ballot(ovf) != 0 && ++rounds < 16;
-            if (again || __ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane, QC * 3 / 4);
-        } while (again);
+            if (!full) mask &= mask - 1;           // done with this register (taken or rejected)
+            if (__ballot(full)) {
+                merge_queues<QC, QPW>(st, kcap, k, lane, QC * 3 / 4);
+                urgent = false;
+            }
+        }
+        if (__ballot(urgent)) merge_queues<QC, QPW>(st, kcap, k, lane, QC * 3 / 4);
     }
 }
 
