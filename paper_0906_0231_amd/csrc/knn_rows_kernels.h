@@ -198,6 +198,14 @@ __device__ __forceinline__ void bitonic_sort_lds(u64 *keys, int n, int lane)
     }
 }
 
+// sum over the 16 lanes of a lane's quarter of the wave
+__device__ __forceinline__ double group16_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
 __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
 {
     __shared__ u64 keys[FIN_MAX];
@@ -224,49 +232,48 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     for (int i = lane; i < kpow; i += 64) outk[i] = KEY_INF;
     __syncthreads();
 
+    // Re-pricing: the k winners are priced again from the original rows, accumulating in double
+    // (a direct sum of squared differences, 1 - cos from the three sums, ...), so the reported
+    // value carries neither the cancellation of |u|^2+|v|^2-2u.v nor that of 1-cos in fp32.
+    // n*k*d work, bound by the latency of the row gathers: the wave is cut into four groups of 16
+    // lanes that price four winners at a time.
+    const int g16 = lane >> 4, gl = lane & 15;
     if (a.mode == FIN_RESCORE_L1 || a.mode == FIN_RESCORE_LINF || a.mode == FIN_RESCORE_KL) {
-        // the same re-pricing of the k winners in double for the distances of the fold family
         const float *x = a.Q + q * (int64_t)a.d;
-        for (int r = 0; r < a.k; ++r) {
-            int32_t j = (int32_t)(uint32_t)keys[r];
-            if (j < 0 || j >= a.nr) {
-                if (lane == 0) outk[r] = KEY_INF;
-                continue;
-            }
-            const float *y = a.R + (int64_t)j * a.d;
+        for (int r0 = 0; r0 < a.k; r0 += 4) {
+            const int r = r0 + g16;
+            const int32_t j = r < a.k ? (int32_t)(uint32_t)keys[r] : -1;
+            const bool ok = j >= 0 && j < a.nr;    // else an unfilled slot (cannot happen for k <= nr - self)
+            const float *y = a.R + (int64_t)(ok ? j : 0) * a.d;
             double s = 0.0;
-            for (int c = lane; c < a.d; c += 64) {
-                double ud = (double)x[c], vd = (double)y[c];
-                if (a.mode == FIN_RESCORE_L1) s += fabs(ud - vd);
-                else if (a.mode == FIN_RESCORE_LINF) s = fmax(s, fabs(ud - vd));
-                else if (ud > 0.0) s += ud * log(ud / vd);
+            if (ok) {
+                for (int c = gl; c < a.d; c += 16) {
+                    double ud = (double)x[c], vd = (double)y[c];
+                    if (a.mode == FIN_RESCORE_L1) s += fabs(ud - vd);
+                    else if (a.mode == FIN_RESCORE_LINF) s = fmax(s, fabs(ud - vd));
+                    else if (ud > 0.0) s += ud * log(ud / vd);
+                }
             }
             if (a.mode == FIN_RESCORE_LINF) {
 #pragma unroll
-                for (int o = 32; o > 0; o >>= 1) s = fmax(s, __shfl_xor(s, o, 64));
+                for (int o = 8; o > 0; o >>= 1) s = fmax(s, __shfl_xor(s, o, 64));
             } else {
-                s = wave_sum_f64(s);
+                s = group16_sum_f64(s);
             }
-            if (lane == 0) outk[r] = make_key((float)s, j);
+            if (gl == 0 && r < a.k) outk[r] = ok ? make_key((float)s, j) : KEY_INF;
         }
     } else if (a.mode == FIN_RESCORE_SQ || a.mode == FIN_RESCORE_COS || a.mode == FIN_RESCORE_HEL) {
-        // The k winners are priced again from the original rows, accumulating in
-        // double: a direct sum of squared differences (or 1 - cos from the three
-        // sums), so the reported value carries neither the cancellation of
-        // |u|^2+|v|^2-2u.v nor that of 1-cos in fp32.  n*k*d work, HBM bound.
         const float *x = a.Q + q * (int64_t)a.d;
         const bool cosine = a.mode == FIN_RESCORE_COS;
         const bool root = a.mode == FIN_RESCORE_HEL;
-        for (int r = 0; r < a.k; ++r) {
-            int32_t j = (int32_t)(uint32_t)keys[r];
-            if (j < 0 || j >= a.nr) {             // an unfilled slot (cannot happen for k <= nr - self)
-                if (lane == 0) outk[r] = KEY_INF;
-                continue;
-            }
-            const float *y = a.R + (int64_t)j * a.d;
+        for (int r0 = 0; r0 < a.k; r0 += 4) {
+            const int r = r0 + g16;
+            const int32_t j = r < a.k ? (int32_t)(uint32_t)keys[r] : -1;
+            const bool ok = j >= 0 && j < a.nr;
+            const float *y = a.R + (int64_t)(ok ? j : 0) * a.d;
             double s = 0.0, uu = 0.0, vv = 0.0;
-            if (a.vec4) {
-                for (int c = lane * 4; c < a.d; c += 256) {
+            if (ok && a.vec4) {
+                for (int c = gl * 4; c < a.d; c += 64) {
                     f32x4 u = *(const f32x4 *)(x + c), v = *(const f32x4 *)(y + c);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -281,8 +288,8 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                         }
                     }
                 }
-            } else {
-                for (int c = lane; c < a.d; c += 64) {
+            } else if (ok) {
+                for (int c = gl; c < a.d; c += 16) {
                     double ud = (double)x[c], vd = (double)y[c];
                     if (cosine) {
                         s = fma(ud, vd, s);
@@ -294,14 +301,14 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                     }
                 }
             }
-            s = wave_sum_f64(s);
+            s = group16_sum_f64(s);
             if (cosine) {
-                uu = wave_sum_f64(uu);
-                vv = wave_sum_f64(vv);
+                uu = group16_sum_f64(uu);
+                vv = group16_sum_f64(vv);
                 s = (uu == 0.0 || vv == 0.0) ? 1.0 : 1.0 - s / (sqrt(uu) * sqrt(vv));
                 if (s < 0.0) s = 0.0;
             }
-            if (lane == 0) outk[r] = make_key((float)s, j);
+            if (gl == 0 && r < a.k) outk[r] = ok ? make_key((float)s, j) : KEY_INF;
         }
     } else if (a.mode == FIN_SELECT) {
         for (int r = lane; r < a.k; r += 64) outk[r] = keys[r];   // keys are (value, column) already
