@@ -294,6 +294,9 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
             const int par = rt & 1;
             uint32_t mc = lane < QG_TR ? *(volatile uint32_t *)&sm.mcnt[par][lane] : 0u;
             u64 pend = __ballot(mc > 0) & (0xffffull << (16 * w));
+            // Nothing queued for this wave's rows (nine tiles in ten at n = 2^20): leave before
+            // the fence below, which would wait for the staging loads the step has just issued.
+            if (pend == 0) return;
             merge_pending(
                 pend, a.kcap, a.k, lane,
                 [&](int m, u64 *&L, const u64 *&cq, int &nc) {
