@@ -31,8 +31,8 @@ VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md).
 # Keyed by (workload, schedule); reported per launch next to `achieved`.
 MEASURED_TRAFFIC_BYTES_PER_STEP = {
-    ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.65e12 + 1.64e10,
-    ("c3_lowrank32_n1048576_d256_k10", "full-square"): 6.78e12 + 8.57e9,
+    ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.83e12 + 3.01e10,
+    ("c3_lowrank32_n1048576_d256_k10", "full-square"): 5.85e12 + 1.59e9,
 }
 
 
