@@ -38,7 +38,7 @@ struct Plan {
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
     int32_t nlists; // partial lists per query
-    size_t off_qp, off_rp, off_c, off_sq, off_lists, total;
+    size_t off_qp, off_rp, off_c, off_sq, off_bound, off_lists, total;
 };
 
 int32_t list_capacity(int32_t k)
@@ -96,6 +96,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.off_c = o;                                  // here: one bound word per query
         o = align_up(o + (size_t)p.nq_pad * sizeof(uint32_t), 256);
         p.off_sq = o;
+        p.off_bound = o;
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
         p.total = o;
@@ -121,7 +122,30 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     int32_t smax = KNN_FIN_MAX / (p.kcap * per_slice);
     if (smax > p.n_rtiles) smax = p.n_rtiles;
     int32_t S = r_splits;
-    if (S <= 0) S = p.n_qtiles >= 512 ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
+    if (S <= 0) {
+        // The device holds 512 workgroups of the tile kernels at once (two per CU).  With fewer
+        // query tiles than that, take the smallest slice count that fills at least 90 % of the
+        // last round of workgroups (every slice costs each query a list of its own: k forced
+        // insertions and a merge at the end), else the one that fills it best.  With more tiles
+        // than that and long lists, one slice: measured faster even when the second round of
+        // workgroups is short (n = 80 000, k = 100), while with short lists balancing the second
+        // round still pays (n = 100 000, k = 10).
+        const int32_t cap = (p.n_qtiles >= 512 && p.kcap > 32) ? 1 : (2048 + p.n_qtiles - 1) / p.n_qtiles;
+        double best = -1.0;
+        S = 1;
+        for (int32_t s = 1; s <= cap && s <= smax; ++s) {
+            const int64_t wg = (int64_t)p.n_qtiles * s;
+            const double eff = (double)wg / (double)((wg + 511) / 512 * 512);
+            if (eff >= 0.9) {
+                S = s;
+                break;
+            }
+            if (eff > best + 1e-9) {
+                best = eff;
+                S = s;
+            }
+        }
+    }
     if (S > smax) S = smax;
     if (S < 1) S = 1;
     if (p.tri) S = 1;
@@ -139,6 +163,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     o = align_up(o + (size_t)p.n_cpad * sizeof(float), 256);
     p.off_sq = o;
     o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;   // + one scalar (max c_j)
+    p.off_bound = o;                                 // one word per query: bound shared by the slices
+    o = align_up(o + (size_t)nq * sizeof(uint32_t), 256);
     p.off_lists = o;
     o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
@@ -211,6 +237,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     float *cr = (float *)(ws + p.off_c);
     float *sq = (float *)(ws + p.off_sq);
     u64 *lists = (u64 *)(ws + p.off_lists);
+    uint32_t *bound = (!p.fold && p.qreg && !p.tri && p.S > 1) ? (uint32_t *)(ws + p.off_bound) : nullptr;
 
     Events ev;
     if (o.profile) {
@@ -232,14 +259,14 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         e = launch_pack(pk, stream);
         if (e != hipSuccess) { set_error("pack_tiles(R)", e); return KNN_EDEVICE; }
     } else if (self) {
-        PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq};
+        PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq, bound};
         e = launch_prep(a, stream);
         if (e != hipSuccess) { set_error("prep_rows", e); return KNN_EDEVICE; }
     } else {
-        PrepArgs aq = {Q, nq, d, p.dpad, (int32_t)metric, qp, nullptr, nullptr, nq, sq};
+        PrepArgs aq = {Q, nq, d, p.dpad, (int32_t)metric, qp, nullptr, nullptr, nq, sq, bound};
         e = launch_prep(aq, stream);
         if (e != hipSuccess) { set_error("prep_rows(Q)", e); return KNN_EDEVICE; }
-        PrepArgs ar = {R, nr, d, p.dpad, (int32_t)metric, nullptr, rp, cr, p.n_cpad, nullptr};
+        PrepArgs ar = {R, nr, d, p.dpad, (int32_t)metric, nullptr, rp, cr, p.n_cpad, nullptr, nullptr};
         e = launch_prep(ar, stream);
         if (e != hipSuccess) { set_error("prep_rows(R)", e); return KNN_EDEVICE; }
     }
@@ -313,6 +340,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         t.Rp = p.rcopy ? rp : R;
         t.cR = cr;
         t.lists = lists;
+        t.bound = bound;
         t.ldq = p.dpad;
         t.ldr = p.rcopy ? p.dpad : d;
         t.nq = nq;

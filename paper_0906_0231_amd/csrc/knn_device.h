@@ -31,6 +31,7 @@ struct PrepArgs {
     float *c_out;      // [n_cpad]  c_j, +inf beyond n, or null
     int64_t n_cpad;
     float *s_out;      // [n] squared norms, or null
+    uint32_t *b_out;   // [n] per-query bound shared by the slices of the reference range: set to "none yet", or null
 };
 
 struct TileArgs {
@@ -38,6 +39,7 @@ struct TileArgs {
     const float *Rp;   // [nr, ldr]
     const float *cR;   // [n_rtiles * 128]
     u64 *lists;        // [S, nq_pad, kcap]
+    uint32_t *bound;   // [nq] smallest k-th-best distance any slice has reached (order-preserving bits), or null (S == 1)
     int64_t ldq, ldr;
     int64_t nq, nr, nq_pad;
     int64_t self_offset;

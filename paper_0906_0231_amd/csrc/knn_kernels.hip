@@ -103,22 +103,29 @@ hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
+template <bool SHARE>
+static hipError_t launch_tiles_qreg_t(const TileArgs &a, hipStream_t stream)
 {
     int64_t blocks = (int64_t)a.n_qtiles * a.S;
     dim3 grid((unsigned)blocks), block(256);
     switch (a.dpad) {
-    case 32: hipLaunchKernelGGL(knn_tiles_qreg<32>, grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL(knn_tiles_qreg<64>, grid, block, 0, stream, a); break;
-    case 96: hipLaunchKernelGGL(knn_tiles_qreg<96>, grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL(knn_tiles_qreg<128>, grid, block, 0, stream, a); break;
-    case 160: hipLaunchKernelGGL(knn_tiles_qreg<160>, grid, block, 0, stream, a); break;
-    case 192: hipLaunchKernelGGL(knn_tiles_qreg<192>, grid, block, 0, stream, a); break;
-    case 224: hipLaunchKernelGGL(knn_tiles_qreg<224>, grid, block, 0, stream, a); break;
-    case 256: hipLaunchKernelGGL(knn_tiles_qreg<256>, grid, block, 0, stream, a); break;
+    case 32: hipLaunchKernelGGL((knn_tiles_qreg<32, SHARE>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_tiles_qreg<64, SHARE>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_tiles_qreg<96, SHARE>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_tiles_qreg<128, SHARE>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_tiles_qreg<160, SHARE>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_tiles_qreg<192, SHARE>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_tiles_qreg<224, SHARE>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((knn_tiles_qreg<256, SHARE>), grid, block, 0, stream, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
+{
+    // slices share their bound only when there is more than one of them
+    return a.bound != nullptr && a.S > 1 ? launch_tiles_qreg_t<true>(a, stream) : launch_tiles_qreg_t<false>(a, stream);
 }
 
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream)

@@ -44,6 +44,7 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
             if (lane == 0) {
                 if (a.c_out) a.c_out[row] = 0.f;
                 if (a.s_out) a.s_out[row] = s;
+                if (a.b_out) a.b_out[row] = 0xffffffffu;
             }
             continue;
         }
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
         if (lane == 0) {
             if (a.c_out) a.c_out[row] = cval;
             if (a.s_out) a.s_out[row] = s;
+            if (a.b_out) a.b_out[row] = 0xffffffffu;
         }
     }
 }

@@ -420,7 +420,12 @@ struct __attribute__((aligned(16))) QregSmem {
     uint32_t cnt[4][32];
 };
 
-template <int DPAD>
+// SHARE: the reference range is cut into slices that run side by side, each with its own list
+// per query starting empty.  A slice's k-th best is an upper bound of the final k-th best, so the
+// slices publish theirs (atomic minimum on one word per query) and test against the smallest
+// published so far; a stale read is merely looser.  Matters when n is small against k (the
+// shape of the paper's Table 1: without it 40 % of all pairs entered a queue at n = 10 000).
+template <int DPAD, bool SHARE>
 __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
 {
     constexpr int NK = DPAD / QG_DC;
@@ -454,6 +459,8 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     st.cnt = &sm.cnt[w][0];
     st.shared_tau = nullptr;
     st.mine = 0;
+    uint32_t *mybound = SHARE ? a.bound + min(myq, a.nq - 1) : nullptr;
+    uint32_t seen = 0xffffffffu;
 
     // the wave's query operands, once
     f32x4 qreg[NS];
@@ -504,6 +511,8 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
         // keep the loads up here: their latency must overlap this step's matrix work
         __builtin_amdgcn_sched_barrier(0);
         if (kc == 0) {
+            // what the other slices have reached: requested now, used after the tile
+            if (SHARE) seen = __hip_atomic_load(mybound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int gg = 0; gg < 4; ++gg) {
                 f32x4 c0 = *(const f32x4 *)&sm.c[buf][gg * 8 + h * 4];
@@ -533,9 +542,12 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
             // workgroup's matrix instructions on this SIMD (measured: -0.3 to -1.5 %)
             __builtin_amdgcn_s_setprio(1);
             float m2 = fminf(min16(acc0), min16(acc1));
+            if (SHARE && seen != 0xffffffffu) st.tau_p = fminf(st.tau_p, ord2f(seen));
             if (__ballot(m2 <= st.tau_p)) {
                 f32x16 blocks[2] = {acc0, acc1};
                 select_rare<2, QCAP>(blocks, rt * QG_TR + 4 * h, a.nr, a.kcap, a.k, st, lane);
+                if (SHARE && h == 0 && qvalid && st.tau_key != KEY_INF)
+                    atomicMin(mybound, (uint32_t)(st.tau_key >> 32));
             }
             __builtin_amdgcn_s_setprio(0);
         }
