@@ -82,7 +82,10 @@ typedef struct {
 typedef struct {
     int32_t symmetric;  /* knn_build only.  0 = auto, 1 = force the triangle schedule
                            (each unordered tile pair computed once, Sect. 3-4),
-                           2 = force the full square */
+                           2 = force the full square.  Auto takes the triangle when n >= 65536
+                           and a cost model of its rounds (fill of the device by the pairs of
+                           one round, fixed cost per pair, longer merges for k > 32) puts it
+                           below the full square */
     int32_t rescore;    /* 0 = auto (on), 1 = on, 2 = off.
                            On: the k reported distances of each query are recomputed
                            from the original rows with double accumulation (a direct
@@ -96,9 +99,10 @@ typedef struct {
                            1 = streaming: both operands through LDS chunk by chunk, any d.
                            2 = query tile resident in LDS, 3 = query tile resident in
                            registers; both need d <= 256 and fall back to 1 otherwise */
-    int32_t block_rows; /* symmetric schedule only.  0 = auto (n/1024 rounded down to a multiple
-                           of 128, at least 128).  Rows per block; rounded up to a multiple
-                           of 128.  A round launches floor(ceil(n/block_rows)/2) workgroups */
+    int32_t block_rows; /* symmetric schedule only.  Rows per block; rounded up to a multiple
+                           of 128.  A round launches ceil(ceil(n/block_rows)/2) workgroups.
+                           0 = auto: the multiple of 128 for which the rounds fill the device's
+                           512 workgroup slots best (n/1024 when n is a power of two >= 2^17) */
     int32_t reserved;   /* must be 0 */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
                            kernels with events, waits for them and fills this in */

@@ -50,15 +50,32 @@ int32_t list_capacity(int32_t k)
 
 // Sizes are assumed validated.  r_splits == 0 picks a split count that gives
 // the 256 compute units at least two workgroups each when query tiles are few.
-// Symmetric schedule: rows per block.  At least 512 disjoint pairs per round keep two
-// workgroups on every CU, so B = n/1024 rounded down to a multiple of the query tile;
-// never below one tile.
-int32_t pair_block_rows(int64_t n)
+// Symmetric schedule: rows per block, and what the schedule costs next to the full square.
+// A round is one launch of NBp/2 workgroups, one block pair each, on 512 workgroup slots
+// (two per CU), so a round lasts ceil(NBp/2 / 512) pair times whatever its fill; a pair
+// costs B*B distance evaluations times (a + c/B), the second term being the sweep's fixed
+// part (prologue, mirror hand-over).  a and c are fitted to measured run times at B = 128,
+// 256 and 1024 and are larger for long lists, whose mirror merges cost more.  The result is
+// the ratio to n*n evaluations spread over the same 512 slots by the full-square kernel; B is the multiple of the query
+// tile that minimises it.
+double pair_cost_ratio(int64_t n, int32_t B, int32_t kcap)
 {
-    int64_t b = n / 1024 / KNN_TILE * KNN_TILE;
-    if (b < KNN_TILE) b = KNN_TILE;
-    if (b > 8192) b = 8192;
-    return (int32_t)b;
+    const int64_t nb = (n + B - 1) / B, nbp = nb + (nb & 1);
+    const int64_t pairs = nbp / 2;
+    const double a = kcap > 32 ? 1.5 : 1.17, c = kcap > 32 ? 120.0 : 93.0;
+    const double rounds = (double)(nbp - 1) * (double)((pairs + 511) / 512) + (double)((nb + 511) / 512);  // + the diagonal blocks
+    return 512.0 * rounds * (double)B * (double)B * (a + c / (double)B) / ((double)n * (double)n);
+}
+
+int32_t pair_block_rows(int64_t n, int32_t kcap)
+{
+    int32_t best = KNN_TILE;
+    double best_ratio = pair_cost_ratio(n, best, kcap);
+    for (int32_t b = 2 * KNN_TILE; b <= 8192 && b < 2 * n; b += KNN_TILE) {
+        const double r = pair_cost_ratio(n, b, kcap);
+        if (r < best_ratio - 1e-12) { best_ratio = r; best = b; }
+    }
+    return best;
 }
 
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
@@ -114,8 +131,9 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
     // symmetric schedule: only for knn_build, only with the register-resident kernel;
     // by default only when a round has enough pairs to fill the GPU
-    p.tri = self && p.qreg && metric != KNN_KL && symmetric != 2 && (symmetric == 1 || nr >= 1024 * KNN_TILE);
-    p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr);
+    p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr, p.kcap);
+    p.tri = self && p.qreg && metric != KNN_KL && symmetric != 2 &&
+            (symmetric == 1 || (nr >= 512 * KNN_TILE && pair_cost_ratio(nr, p.B, p.kcap) < 0.97));
     p.NB = (int32_t)((nr + p.B - 1) / p.B);
     p.NBp = p.NB + (p.NB & 1);
     const int32_t per_slice = p.qres ? 2 : 1;

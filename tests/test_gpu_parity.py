@@ -153,6 +153,27 @@ def test_symmetric_equals_full_square():
     assert torch.equal(a.idx, c.idx) and torch.equal(a.dist, c.dist)     # and deterministic
 
 
+@pytest.mark.parametrize("n,k,sym,launches", [
+    (131072, 10, 1, 1024),     # blocks of 128 rows: 512 pairs per round, 1023 rounds + the diagonal
+    (150000, 10, 0, None),     # 586 blocks of 256 rows leave the rounds 57 % full: the square is cheaper
+    (262144, 10, 1, 1024),     # blocks of 256 rows
+    (262144, 100, 0, None),    # long lists: the mirror merges make the triangle no cheaper yet
+])
+def test_default_schedule_choice(n, k, sym, launches):
+    """With no option set the library takes the symmetric schedule where its rounds fill the
+    device and the square otherwise; a non-power-of-two n gets the block size whose rounds fit
+    best.  Sampled rows are checked against the oracle either way."""
+    _say(f"  default schedule n={n} k={k}")
+    X = workloads.mixture(n, 64, 32, seed=77)
+    res = knn_build(X.cuda(), k, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.symmetric == sym
+    if launches is not None:
+        assert res.profile.main_launches == launches
+    rows = _sample_rows(n, 64, seed=n % 97)
+    _check_rows(X.numpy(), rows, 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
 def test_symmetric_exact_ties():
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
