@@ -48,16 +48,14 @@ int32_t list_capacity(int32_t k)
     return c;
 }
 
-// Sizes are assumed validated.  r_splits == 0 picks a split count that gives
-// the 256 compute units at least two workgroups each when query tiles are few.
 // Symmetric schedule: rows per block, and what the schedule costs next to the full square.
 // A round is one launch of NBp/2 workgroups, one block pair each, on 512 workgroup slots
 // (two per CU), so a round lasts ceil(NBp/2 / 512) pair times whatever its fill; a pair
 // costs B*B distance evaluations times (a + c/B), the second term being the sweep's fixed
 // part (prologue, mirror hand-over).  a and c are fitted to measured run times at B = 128,
 // 256 and 1024 and are larger for long lists, whose mirror merges cost more.  The result is
-// the ratio to n*n evaluations spread over the same 512 slots by the full-square kernel; B is the multiple of the query
-// tile that minimises it.
+// the ratio to n*n evaluations spread over the same 512 slots by the full-square kernel;
+// B is the multiple of the query tile that minimises it.
 double pair_cost_ratio(int64_t n, int32_t B, int32_t kcap)
 {
     const int64_t nb = (n + B - 1) / B, nbp = nb + (nb & 1);
@@ -78,6 +76,8 @@ int32_t pair_block_rows(int64_t n, int32_t kcap)
     return best;
 }
 
+// Sizes are assumed validated.  r_splits == 0 picks the slice count of the reference range
+// (see below), block_rows == 0 and symmetric == 0 take the cost model above.
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
                int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, Plan &p)
 {
@@ -130,7 +130,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
     p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
     // symmetric schedule: only for knn_build, only with the register-resident kernel;
-    // by default only when a round has enough pairs to fill the GPU
+    // by default only where the cost model puts it below the full square
     p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr, p.kcap);
     p.tri = self && p.qreg && metric != KNN_KL && symmetric != 2 &&
             (symmetric == 1 || (nr >= 512 * KNN_TILE && pair_cost_ratio(nr, p.B, p.kcap) < 0.97));
