@@ -73,7 +73,8 @@ typedef struct {
     float ms_finalize;  /* merge of partial lists, re-score, final order            */
     float ms_total;
     int32_t main_launches; /* kernel launches counted in ms_main */
-    int32_t symmetric;     /* 1 if the triangle-of-tiles schedule was used */
+    int32_t symmetric;     /* 1 if each unordered pair of rows was evaluated once (triangle schedule,
+                              or the symmetric form of variant 4) */
     int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
                               padding of ragged tiles included */
 } knn_profile_t;
@@ -82,8 +83,8 @@ typedef struct {
 typedef struct {
     int32_t symmetric;  /* knn_build only.  0 = auto, 1 = force the triangle schedule
                            (each unordered tile pair computed once, Sect. 3-4),
-                           2 = force the full square.  Auto takes the triangle when n >= 65536
-                           and a cost model of its rounds (fill of the device by the pairs of
+                           2 = force the full square.  Auto (where variant 4 is not taken, see
+                           below) takes the triangle when n >= 65536 and a cost model of its rounds (fill of the device by the pairs of
                            one round, fixed cost per pair, longer merges for k > 32) puts it
                            below the full square */
     int32_t rescore;    /* 0 = auto (on), 1 = on, 2 = off.
@@ -98,7 +99,14 @@ typedef struct {
     int32_t variant;    /* fused-kernel variant.  0 = auto (3 if d <= 256, else 1).
                            1 = streaming: both operands through LDS chunk by chunk, any d.
                            2 = query tile resident in LDS, 3 = query tile resident in
-                           registers; both need d <= 256 and fall back to 1 otherwise */
+                           registers; both need d <= 256 and fall back to 1 otherwise.
+                           4 = not fused: the paper's two phases as such (Sect. 5-6), the matrix
+                           of distances written to the workspace ([nq, nr] floats, padded to
+                           multiples of 128) and the k smallest per row selected from it;
+                           knn_build computes each unordered pair once unless symmetric == 2.
+                           Needs d <= 256 (else as 0).  Auto takes it when that matrix is at
+                           most 72 GiB, symmetric != 1 and: k > 32; or knn_build (symmetric
+                           distance) with d > 96 or n <= 49152; or the matrix is at most 4 GiB */
     int32_t block_rows; /* symmetric schedule only.  Rows per block; rounded up to a multiple
                            of 128.  A round launches ceil(ceil(n/block_rows)/2) workgroups.
                            0 = auto: the multiple of 128 for which the rounds fill the device's

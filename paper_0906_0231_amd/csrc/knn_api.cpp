@@ -36,6 +36,13 @@ struct Plan {
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
+    bool matrix;    // two-phase organisation: distance matrix written out (knn_dist_qreg), then select_rows
+    bool msym;      // ... computing each unordered pair of rows once
+    int32_t n_rt64, chunk, n_chunks; // ... reference tiles of 64 rows, tiles per workgroup, workgroups per query tile
+    int64_t sel_seg;                 // ... columns per segment of select_rows
+    size_t off_D;                    // ... the matrix, [nq_pad, ldd]
+    int64_t ldd;                     // ... its row pitch in floats: n_cpad + 64, an odd multiple of 256 bytes, so that
+                                     //     a column of the matrix does not fall into one memory channel
     int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
     int32_t nlists; // partial lists per query
     size_t off_qp, off_rp, off_c, off_sq, off_bound, off_lists, total;
@@ -76,6 +83,21 @@ int32_t pair_block_rows(int64_t n, int32_t kcap)
     return best;
 }
 
+// knn_select: how the columns are cut.  Enough waves to fill the GPU when there are few rows,
+// segments no shorter than 16K columns, and no more partial lists than finalize can merge.
+void select_plan(int64_t m, int64_t n, int32_t k, int32_t &kcap, int32_t &S, int64_t &seg)
+{
+    kcap = list_capacity(k);
+    int64_t want = (4096 + m - 1) / m;       // waves wanted in all; measured: more (shorter) segments only add lists
+    int64_t most = n / 16384 > 0 ? n / 16384 : 1;
+    if (want > most) want = most;
+    if (want > KNN_FIN_MAX / kcap) want = KNN_FIN_MAX / kcap;
+    if (want < 1) want = 1;
+    seg = (n + want - 1) / want;
+    seg = (seg + 1023) / 1024 * 1024;
+    S = (int32_t)((n + seg - 1) / seg);
+}
+
 // Sizes are assumed validated.  r_splits == 0 picks the slice count of the reference range
 // (see below), block_rows == 0 and symmetric == 0 take the cost model above.
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
@@ -84,6 +106,11 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.self = self;
     p.fold = metric == KNN_L1 || metric == KNN_LINF;
     p.refs_per_split = 0;
+    p.matrix = p.msym = false;
+    p.n_rt64 = p.chunk = p.n_chunks = 0;
+    p.sel_seg = 0;
+    p.off_D = 0;
+    p.ldd = 0;
     if (p.fold) {
         // lane = query, 64 per wave; the reference range is cut so that the device has
         // several thousand waves to run
@@ -136,6 +163,56 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
             (symmetric == 1 || (nr >= 512 * KNN_TILE && pair_cost_ratio(nr, p.B, p.kcap) < 0.97));
     p.NB = (int32_t)((nr + p.B - 1) / p.B);
     p.NBp = p.NB + (p.NB & 1);
+    // Two-phase organisation (matrix written out, then selected from): on request, or by default
+    // where it was measured faster than the fused kernels and the matrix is at most 72 GiB:
+    // long lists (the fused kernels then spend more time merging candidates than multiplying:
+    // 2 to 3 times faster on the shapes of the paper's Table 1); knn_build with d >= 128, where
+    // computing each pair once saves more than the matrix costs to write and read back (below
+    // that the stores bound it: 4 n^2 bytes against n^2 d flop); and small problems, which its
+    // two-dimensional grid spreads over the device better than one sweep per query tile does.
+    // Needs the register-resident operand layout, i.e. d <= 256.
+    p.ldd = p.n_cpad + 64;
+    const double matrix_bytes = (double)p.nq_pad * (double)p.ldd * sizeof(float);
+    const bool matrix_ok = dpad32 <= KNN_QRES_MAX_D && p.n_cpad < ((int64_t)1 << 28);   // 32-bit element offsets within four rows
+    const bool msym = self && metric != KNN_KL && symmetric != 2;
+    p.matrix = false;
+    if (variant == 4)
+        p.matrix = matrix_ok;
+    else if (variant == 0 && symmetric != 1 && matrix_ok && matrix_bytes <= 72.0 * 1073741824.0)
+        p.matrix = p.kcap > 32 || (msym ? (dpad32 >= 128 || p.n_cpad <= 49152) : matrix_bytes <= 4.0 * 1073741824.0);
+    if (p.matrix) {
+        p.dpad = dpad32;
+        p.qreg = p.qres = p.tri = false;
+        p.msym = msym;
+        p.n_rt64 = (int32_t)((nr + 63) / 64);
+        const int64_t tiles = (int64_t)p.n_qtiles * p.n_rt64 / (p.msym ? 2 : 1);
+        int64_t chunk = (tiles + 1023) / 1024;
+        if (chunk < 4) chunk = 4;
+        if (chunk > 64) chunk = 64;
+        p.chunk = (int32_t)chunk;
+        p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
+        int32_t skcap;
+        select_plan(nq, nr, k, skcap, p.S, p.sel_seg);
+        p.nlists = p.S;
+        p.rt_per_split = 0;
+        p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
+        size_t o = 0;
+        p.off_qp = o;
+        o = align_up(o + (size_t)nq * p.dpad * sizeof(float), 256);
+        p.off_rp = o;
+        if (p.rcopy) o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
+        p.off_c = o;
+        o = align_up(o + (size_t)p.n_cpad * sizeof(float), 256);
+        p.off_sq = o;
+        o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;
+        p.off_bound = o;
+        p.off_D = o;
+        o = align_up(o + (size_t)p.nq_pad * p.ldd * sizeof(float), 256);
+        p.off_lists = o;
+        o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
+        p.total = o;
+        return true;
+    }
     const int32_t per_slice = p.qres ? 2 : 1;
     int32_t smax = KNN_FIN_MAX / (p.kcap * per_slice);
     if (smax > p.n_rtiles) smax = p.n_rtiles;
@@ -240,7 +317,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
     if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
-        o.variant < 0 || o.variant > 3 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
+        o.variant < 0 || o.variant > 4 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
         return KNN_EINVAL;
 
     Plan p;
@@ -312,6 +389,47 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         e = launch_fold(fa, stream);
         if (e != hipSuccess) { set_error("knn_fold", e); return KNN_EDEVICE; }
         pairs_computed = (nq + 63) / 64 * 64 * p.n_cpad;
+    } else if (p.matrix) {
+        DistArgs da;
+        da.Qp = qp;
+        da.Rp = p.rcopy ? rp : R;
+        da.cR = cr;
+        da.cQ = cr;                                // read in symmetric mode only: queries == references
+        da.D = (float *)(ws + p.off_D);
+        da.ldq = p.dpad;
+        da.ldr = p.rcopy ? p.dpad : d;
+        da.ldd = p.ldd;
+        da.nq = nq;
+        da.nr = nr;
+        da.self_offset = self_offset;
+        da.dpad = p.dpad;
+        da.n_rt = p.n_rt64;
+        da.chunk = p.chunk;
+        da.n_chunks = p.n_chunks;
+        da.n_qtiles = p.n_qtiles;
+        e = launch_dist_qreg(da, p.n_qtiles, p.msym, stream);
+        if (e != hipSuccess) { set_error("knn_dist_qreg", e); return KNN_EDEVICE; }
+        SelectArgs sa;
+        sa.A = da.D;
+        sa.lists = lists;
+        sa.m = nq;
+        sa.n = nr;
+        sa.lda = p.ldd;
+        sa.seg = p.sel_seg;
+        sa.k = k;
+        sa.kcap = p.kcap;
+        sa.S = p.S;
+        sa.vec4 = 1;                               // rows of the matrix start on 512-byte boundaries
+        e = launch_select(sa, stream);
+        if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+        launches = 2;
+        if (p.msym) {
+            pairs_computed = 0;
+            for (int32_t qt = 0; qt < p.n_qtiles; ++qt)
+                if (p.n_rt64 > 2 * qt) pairs_computed += (int64_t)(p.n_rt64 - 2 * qt) * KNN_TILE * 64;
+        } else {
+            pairs_computed = p.nq_pad * (int64_t)p.n_rt64 * 64;
+        }
     } else if (p.tri) {
         // one launch for the diagonal blocks, then one per round of disjoint block pairs
         float *cmax = (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
@@ -389,7 +507,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.idx = idx;
     f.dist = dist;
     f.nq = nq;
-    f.nq_pad = p.nq_pad;
+    f.nq_pad = p.matrix ? nq : p.nq_pad;           // select_rows packs its lists by row count
     f.nr = nr;
     f.d = d;
     f.k = k;
@@ -422,7 +540,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         (void)hipEventElapsedTime(&pr->ms_finalize, ev.e[2], ev.e[3]);
         (void)hipEventElapsedTime(&pr->ms_total, ev.e[0], ev.e[3]);
         pr->main_launches = launches;
-        pr->symmetric = p.tri ? 1 : 0;
+        pr->symmetric = (p.tri || p.msym) ? 1 : 0;
         pr->pairs_computed = pairs_computed;
     }
     return KNN_OK;
@@ -462,21 +580,6 @@ knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, 
 {
     return knn_search_ex(Q, nq, R, nr, d, k, metric, self_offset, idx, dist, workspace,
                          workspace_bytes, stream, nullptr);
-}
-
-// knn_select: how the columns are cut.  Enough waves to fill the GPU when there are few rows,
-// segments no shorter than 16K columns, and no more partial lists than finalize can merge.
-static void select_plan(int64_t m, int64_t n, int32_t k, int32_t &kcap, int32_t &S, int64_t &seg)
-{
-    kcap = list_capacity(k);
-    int64_t want = (4096 + m - 1) / m;       // waves wanted in all; measured: more (shorter) segments only add lists
-    int64_t most = n / 16384 > 0 ? n / 16384 : 1;
-    if (want > most) want = most;
-    if (want > KNN_FIN_MAX / kcap) want = KNN_FIN_MAX / kcap;
-    if (want < 1) want = 1;
-    seg = (n + want - 1) / want;
-    seg = (seg + 1023) / 1024 * 1024;
-    S = (int32_t)((n + seg - 1) / seg);
 }
 
 size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k)

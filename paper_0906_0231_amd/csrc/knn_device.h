@@ -68,6 +68,23 @@ struct PackArgs {
     uint32_t *bound;   // optional [n]: set to "no bound yet" (all ones) on the way
 };
 
+// Phase 1 of the two-phase organisation: the matrix of p(q, j), written out
+struct DistArgs {
+    const float *Qp;   // [nq, ldq]
+    const float *Rp;   // [nr, ldr]
+    const float *cR;   // [>= n_rt * 64], +inf past the end
+    const float *cQ;   // [nq] c of the queries (symmetric mode; the same array as cR)
+    float *D;          // [ceil(nq/128)*128, ldd]
+    int64_t ldq, ldr, ldd;
+    int64_t nq, nr;
+    int64_t self_offset;
+    int32_t dpad;
+    int32_t n_rt;      // reference tiles of 64 rows
+    int32_t chunk;     // reference tiles per workgroup
+    int32_t n_chunks;  // workgroups per query tile (those past the end of their sweep leave at once)
+    int32_t n_qtiles;  // query tiles of 128 rows
+};
+
 // symmetric schedule: one launch = one round of block pairs (round < 0: the diagonal blocks)
 struct PairArgs {
     const float *Qp;   // [n, ldq] query-side copy
@@ -116,6 +133,7 @@ hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
+hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, bool sym, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream);
 hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream);

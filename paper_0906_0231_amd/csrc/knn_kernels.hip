@@ -7,6 +7,8 @@
 //                        the distance matrix of the paper's Phase 1 (Sect. 5) is never written
 //                        out, its Phase 2 (Sect. 6) runs on the accumulators
 //   knn_pairs_kernel.h   the symmetric schedule (Sect. 3-4)
+//   knn_matrix_kernel.h  Phase 1 on its own: the distance matrix written out (Sect. 5), for the
+//                        problems where selecting from it afterwards (select_rows) is cheaper
 //   knn_fold_kernels.h   folds that are not inner products, on the vector ALUs; calibration
 //   this file            launchers called from the C ABI (knn_api.cpp)
 //
@@ -39,6 +41,7 @@ typedef __attribute__((address_space(3))) void *lds_ptr;
 #include "knn_rows_kernels.h"
 #include "knn_tiles_kernels.h"
 #include "knn_pairs_kernel.h"
+#include "knn_matrix_kernel.h"
 #include "knn_fold_kernels.h"
 
 namespace knn {
@@ -126,6 +129,29 @@ hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
 {
     // slices share their bound only when there is more than one of them
     return a.bound != nullptr && a.S > 1 ? launch_tiles_qreg_t<true>(a, stream) : launch_tiles_qreg_t<false>(a, stream);
+}
+
+template <bool SYM>
+static hipError_t launch_dist_qreg_t(const DistArgs &a, int n_qtiles, hipStream_t stream)
+{
+    dim3 grid((unsigned)((int64_t)n_qtiles * a.n_chunks)), block(256);
+    switch (a.dpad) {
+    case 32: hipLaunchKernelGGL((knn_dist_qreg<32, SYM>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_dist_qreg<64, SYM>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_dist_qreg<96, SYM>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_dist_qreg<128, SYM>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_dist_qreg<160, SYM>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_dist_qreg<192, SYM>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_dist_qreg<224, SYM>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((knn_dist_qreg<256, SYM>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, bool sym, hipStream_t stream)
+{
+    return sym ? launch_dist_qreg_t<true>(a, n_qtiles, stream) : launch_dist_qreg_t<false>(a, n_qtiles, stream);
 }
 
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream)

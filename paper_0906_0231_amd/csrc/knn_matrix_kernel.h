@@ -1,0 +1,183 @@
+// The two-phase organisation of the paper (Sect. 5: Phase 1 writes the distance matrix,
+// Sect. 6: Phase 2 selects per row) for problems where it is the cheaper one on this device:
+// few rows and long lists, where the fused kernels spend more time merging candidates than
+// multiplying, while an n x n matrix of a few GB costs HBM a millisecond or two to write and
+// read back.  Phase 2 is select_rows.  Included by knn_kernels.hip only.
+#ifndef KNN_MATRIX_KERNEL_H_
+#define KNN_MATRIX_KERNEL_H_
+
+namespace knn {
+
+// ---------------------------------------------------------------------------
+// knn_dist_qreg<DPAD, SYM>: Phase 1.  The matrix loop of knn_tiles_qreg (query operands in
+// registers, 64 reference rows x 32 coordinates per step through LDS); the epilogue stores
+// the tile instead of selecting from it:
+//   D[q][j] = p(q, j) = c_j + sum Q'[q] R'[j]        (the value the fused kernels select on;
+//                                                     finalize_rows adds the query's own term)
+// SYM (knn_build with a symmetric distance, Sect. 3): a workgroup starts its sweep at its own
+// diagonal block and every tile beyond it is stored twice, D[q][j] and, as row j sees the
+// same pair, D[j][q] = (p - c_j) + c_q -- half the matrix products, the zig-zag of Sect. 4
+// being unnecessary here because the sweeps are cut into chunks of equal length.  Stores to
+// distinct elements need no ownership, so one launch covers the triangle.
+// The entry of a row with itself is stored as +inf; columns past the end hold +inf (direct)
+// or are never read (mirror).
+// ---------------------------------------------------------------------------
+// a pointer every lane agrees on, told to the compiler as such
+typedef __attribute__((address_space(1))) float global_float;
+__device__ __forceinline__ global_float *scalar_ptr(float *p)
+{
+    const u64 v = (u64)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (global_float *)(((u64)hi << 32) | lo);
+}
+
+struct __attribute__((aligned(16))) DistSmem {
+    float r[2][QG_RBUF];
+    float c[2][QG_TR];                            // by tile parity: read again in the epilogue
+};
+
+template <int DPAD, bool SYM>
+__global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
+{
+    constexpr int NK = DPAD / QG_DC;
+    constexpr int NS = DPAD / 8;
+    __shared__ DistSmem sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int h = lane >> 5;
+    const int ql = lane & 31;
+
+    // chunk-major numbering: consecutive workgroups (which go to the 8 XCDs in turn) are
+    // consecutive query tiles of one chunk index.  In symmetric mode the chunks of high index
+    // exist for the first query tiles only; numbered tile-major with a chunk count that is a
+    // multiple of 8, every XCD would get its own chunk indices and the one with chunk 0 more
+    // than twice the work of the last (measured: n = 65536 took 1.6 times too long).
+    const int chunk = blockIdx.x / a.n_qtiles;
+    const int qt = blockIdx.x - chunk * a.n_qtiles;
+    // the diagonal block of query tile qt is reference tiles 2 qt and 2 qt + 1
+    const int first = SYM ? 2 * qt : 0;
+    const int rt0 = first + chunk * a.chunk;
+    const int rt1 = min(rt0 + a.chunk, a.n_rt);
+    if (rt0 >= rt1) return;                       // whole workgroup
+
+    const int64_t qbase = (int64_t)qt * TQ;
+    const int64_t myq = qbase + 32 * w + ql;      // < nq_pad: D has that many rows
+    const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
+    const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
+
+    f32x4 qreg[NS];
+    {
+        const float *qrow = a.Qp + min(myq, a.nq - 1) * a.ldq + h * 4;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) qreg[s] = *(const f32x4 *)(qrow + s * 8);
+    }
+
+    const int lrow = tid >> 3, lunit = tid & 7;
+    const int st_off = lrow * QG_DC + ((lunit ^ qg_swz(lrow)) << 2);
+    f32x4 g0, g1;
+    float gc = 0.f;
+    auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
+        int64_t r0 = min((int64_t)rt * QG_TR + lrow, a.nr - 1);
+        int64_t r1 = min((int64_t)rt * QG_TR + lrow + 32, a.nr - 1);
+        g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
+        g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
+        if (kc == 0 && tid < QG_TR) gc = a.cR[(int64_t)rt * QG_TR + tid];
+    };
+    auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
+        *(f32x4 *)&sm.r[buf][st_off] = g0;
+        *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
+        if (kc == 0 && tid < QG_TR) sm.c[tb][tid] = gc;
+    };
+    const int rbase0 = ql * QG_DC, rbase1 = (32 + ql) * QG_DC;
+    const int sw = qg_swz(ql);
+
+    f32x16 acc0, acc1;
+    issue(rt0, 0);
+    stash(0, 0, rt0 & 1);
+    __syncthreads();
+
+    int buf = 0;
+    auto step = [&](auto kc_tag, int rt) __attribute__((always_inline)) {
+        constexpr int kc = decltype(kc_tag)::value;
+        constexpr bool last = kc == NK - 1;
+        const bool more = !last || rt + 1 < rt1;
+        if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc == 0) {
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
+                f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc0[4 * gg + e] = c0[e];
+                    acc1[4 * gg + e] = c1[e];
+                }
+            }
+        }
+        const float *rb = &sm.r[buf][0];
+#pragma unroll
+        for (int s = 0; s < QG_NSLAB; ++s) {
+            const int u = ((2 * s + h) ^ sw) << 2;
+            f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+            f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+            const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+            }
+        }
+        if (last) {
+            // register 4 gg + e of block t is reference row j0 + 32 t + 8 gg + 4 h + e
+            const int64_t j0 = (int64_t)rt * QG_TR;
+            const float INF = __builtin_inff();
+            float *drow = a.D + myq * a.ldd + j0 + 4 * h;
+            // does the tile hold the entry of one of this wave's queries with itself?
+            const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
+                             j0 + QG_TR > a.self_offset + qbase + 32 * w;
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 v0 = {acc0[4 * gg], acc0[4 * gg + 1], acc0[4 * gg + 2], acc0[4 * gg + 3]};
+                f32x4 v1 = {acc1[4 * gg], acc1[4 * gg + 1], acc1[4 * gg + 2], acc1[4 * gg + 3]};
+                if (own) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (j0 + 8 * gg + 4 * h + e == selfj) v0[e] = INF;
+                        if (j0 + 32 + 8 * gg + 4 * h + e == selfj) v1[e] = INF;
+                    }
+                }
+                *(f32x4 *)(drow + 8 * gg) = v0;
+                *(f32x4 *)(drow + 32 + 8 * gg) = v1;
+            }
+            if (SYM && rt >= first + 2) {
+                // beyond the diagonal block: the same pairs as rows j see them; for a fixed
+                // register the 32 lanes of a half hold 32 consecutive queries, 128 bytes of row j
+                // a row address every lane agrees on plus a 32-bit lane offset: keeps the 32 store
+                // addresses from occupying two registers each across the matrix loop
+                global_float *tbase = scalar_ptr(a.D + j0 * a.ldd);
+                const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
+                    f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = (acc0[4 * gg + e] - c0[e]) + cq;
+                        (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = (acc1[4 * gg + e] - c1[e]) + cq;
+                    }
+                }
+            }
+        }
+        if (more) stash(buf ^ 1, last ? 0 : kc + 1, (rt + 1) & 1);
+        __syncthreads();
+        buf ^= 1;
+    };
+    for (int rt = rt0; rt < rt1; ++rt) for_each_step<NK>(step, rt);
+}
+
+}  // namespace knn
+
+#endif

@@ -132,7 +132,7 @@ def test_fold_lists_short_of_k_for_long(metric, k):
 
 
 # ---- Kullback-Leibler: not symmetric, matrix-core path ----
-@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 @pytest.mark.parametrize("n,d,k", [(1500, 64, 10), (777, 37, 5), (600, 130, 100), (300, 1, 7), (2, 5, 1)])
 def test_kl_build_small(n, d, k, variant):
     _say(f"  kl build n={n} d={d} k={k} variant={variant}")

@@ -65,7 +65,7 @@ def _sample_rows(n, count, seed):
     (2, 5, 1, "sqeuclidean"),
     (70, 3, 69, "cosine"),
 ])
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_build_small(n, d, k, metric, variant):
     _say(f"  build n={n} d={d} k={k} {metric} variant={variant}")
     X = workloads.gaussian(n, d, seed=1000 + n + d)
@@ -74,7 +74,7 @@ def test_build_small(n, d, k, metric, variant):
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 @pytest.mark.parametrize("splits", [1, 3, 16])
 @pytest.mark.parametrize("rescore", [1, 2])
 def test_split_reference_range_and_rescore(splits, rescore, variant):
@@ -96,7 +96,7 @@ def test_split_reference_range_and_rescore(splits, rescore, variant):
     (1, 513, 512, "cosine"),
     (640, 200, -1, "sqeuclidean"),
 ])
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_search_small(nq, nr, off, metric, variant):
     d, k = 24, 9
     _say(f"  search nq={nq} nr={nr} self_offset={off} {metric}")
@@ -153,23 +153,26 @@ def test_symmetric_equals_full_square():
     assert torch.equal(a.idx, c.idx) and torch.equal(a.dist, c.dist)     # and deterministic
 
 
-@pytest.mark.parametrize("n,k,sym,launches", [
-    (131072, 10, 1, 1024),     # blocks of 128 rows: 512 pairs per round, 1023 rounds + the diagonal
-    (150000, 10, 0, None),     # 586 blocks of 256 rows leave the rounds 57 % full: the square is cheaper
-    (262144, 10, 1, 1024),     # blocks of 256 rows
-    (262144, 100, 0, None),    # long lists: the mirror merges make the triangle no cheaper yet
+@pytest.mark.parametrize("n,d,k,sym,launches", [
+    (131072, 64, 10, 1, 1024),   # fused, blocks of 128 rows: 512 pairs per round, 1023 rounds + the diagonal
+    (150000, 64, 10, 0, 1),      # 586 blocks of 256 rows leave the rounds 57 % full: the fused square is cheaper
+    (262144, 64, 10, 1, 1024),   # fused, blocks of 256 rows
+    (262144, 64, 100, 0, 1),     # long lists: the mirror merges make the triangle no cheaper yet
+    (20000, 256, 100, 1, 2),     # the shape of the paper's Table 1: matrix written out, each pair once
+    (40000, 64, 10, 1, 2),       # small enough for the two-phase form whatever d and k
+    (60000, 64, 10, 0, 1),       # d = 64 and not small: the matrix would cost more than it saves
+    (60000, 128, 10, 1, 2),      # d = 128: it pays
 ])
-def test_default_schedule_choice(n, k, sym, launches):
-    """With no option set the library takes the symmetric schedule where its rounds fill the
-    device and the square otherwise; a non-power-of-two n gets the block size whose rounds fit
-    best.  Sampled rows are checked against the oracle either way."""
-    _say(f"  default schedule n={n} k={k}")
-    X = workloads.mixture(n, 64, 32, seed=77)
+def test_default_schedule_choice(n, d, k, sym, launches):
+    """With no option set the library takes the two-phase form where the matrix is cheap next
+    to the arithmetic it saves, else the symmetric schedule where its rounds fill the device,
+    else the fused square.  Sampled rows are checked against the oracle either way."""
+    _say(f"  default schedule n={n} d={d} k={k}")
+    X = workloads.mixture(n, d, 32, seed=77)
     res = knn_build(X.cuda(), k, profile=True)
     torch.cuda.synchronize()
     assert res.profile.symmetric == sym
-    if launches is not None:
-        assert res.profile.main_launches == launches
+    assert res.profile.main_launches == launches
     rows = _sample_rows(n, 64, seed=n % 97)
     _check_rows(X.numpy(), rows, 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
@@ -240,7 +243,7 @@ def test_search_equals_build():
 # ---------------------------------------------------------------------------
 # exact cases: ties must go to the lower index, bit-exact distances
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_lattice_exact(variant):
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
@@ -252,7 +255,7 @@ def test_lattice_exact(variant):
     assert gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 @pytest.mark.parametrize("metric", ["sqeuclidean", "cosine"])
 def test_all_equidistant(metric, variant):
     n, k = 200, 17
@@ -266,7 +269,7 @@ def test_all_equidistant(metric, variant):
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, gi, gd, strict=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_duplicate_rows(variant):
     base = workloads.gaussian(300, 20, seed=9)
     X = base.repeat_interleave(2, dim=0).contiguous()
@@ -280,7 +283,7 @@ def test_duplicate_rows(variant):
     _check_rows(X.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_deterministic(variant):
     X = workloads.mixture(3000, 64, 16, seed=4).cuda()
     a = knn_build(X, 10, variant=variant)
@@ -335,7 +338,7 @@ def test_device_error_paths():
 # the benchmark configurations at full size (oracle on sampled rows where the full
 # oracle would take hours)
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_config1_full(variant):
     w = workloads.config(1)
     _say(f"  {w.name} variant={variant}")
