@@ -45,7 +45,7 @@ def main() -> int:
                          "8 = Kullback-Leibler)")
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
-    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query-resident")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query tile in LDS, 3 query tile in registers, 4 two-phase")
     ap.add_argument("--block-rows", type=int, default=0, help="symmetric schedule: rows per block")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -78,7 +78,8 @@ def main() -> int:
     gen_s = time.time() - t0
 
     ws = torch.empty(knn_workspace_bytes(nq, nr, d, k, w.metric, symmetric=w.symmetric,
-                                         variant=args.variant),
+                                         variant=args.variant, schedule=args.symmetric,
+                                         block_rows=args.block_rows),
                      dtype=torch.uint8, device=dev)
     idx = torch.empty((nq, k), dtype=torch.int32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
@@ -94,7 +95,7 @@ def main() -> int:
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
-    main_ms, launches, pairs_computed, symmetric = [], 1, 0, 0
+    main_ms, launches, pairs_computed, symmetric, two_phase, select_ms = [], 1, 0, 0, 0, []
     t0 = time.perf_counter()
     for _ in range(args.steps):
         res = step(True)           # events around the fused kernel, on the launch stream
@@ -102,6 +103,8 @@ def main() -> int:
         launches = max(1, res.profile.main_launches)
         pairs_computed = res.profile.pairs_computed
         symmetric = res.profile.symmetric
+        two_phase = res.profile.two_phase
+        select_ms.append(res.profile.ms_select)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -109,7 +112,12 @@ def main() -> int:
     pairs_served = float(nq) * float(nr)
     value = pairs_served / (ms_per_step * 1e-3)
     # dominant kernel: the fused tile kernel; algorithmic work = 2*d flop per pair it evaluates
-    kern_ms = float(np.mean(main_ms)) / launches
+    if two_phase:
+        # matrix written out, then selected from: the dominant kernel is the one that writes it
+        launches = 1
+        kern_ms = float(np.mean(main_ms)) - float(np.mean(select_ms))
+    else:
+        kern_ms = float(np.mean(main_ms)) / launches
     flop_per_launch = 2.0 * d * pairs_computed / launches
     achieved = flop_per_launch / (kern_ms * 1e-3) / 1e12
 
@@ -127,15 +135,19 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "nq": nq, "nr": nr, "d": d, "k": k, "metric": w.metric,
-                   "schedule": "triangle" if symmetric else "full-square",
+                   "schedule": ("two-phase " if two_phase else "") + ("triangle" if symmetric else "full-square"),
                    "pairs_computed_per_step": pairs_computed,
                    "fused_kernel_ms": float(np.mean(main_ms)),
                    "datagen_s": round(gen_s, 2)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                     "traffic": None, "kernel": "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
+                     "traffic": None, "kernel": "knn_dist_qreg" if two_phase else "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
+
+    if two_phase:
+        out["config"]["select_rows_ms"] = float(np.mean(select_ms))
+        out["config"]["matrix_bytes"] = 4.0 * (float((nq + 127) // 128 * 128) * float((nr + 127) // 128 * 128 + 64))
 
     # the fp32 matrix rate this machine sustains (matrix instructions only, ~0.25 s), beside the nominal peak
     from paper_0906_0231_amd import knn_mfma_calibration

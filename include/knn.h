@@ -77,6 +77,8 @@ typedef struct {
                               or the symmetric form of variant 4) */
     int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
                               padding of ragged tiles included */
+    float ms_select;       /* variant 4 only: the part of ms_main spent selecting from the matrix */
+    int32_t two_phase;     /* 1 if variant 4 was used (matrix written out, then selected from) */
 } knn_profile_t;
 
 /* Optional knobs; pass NULL for defaults.  Zero-initialise, then set fields. */

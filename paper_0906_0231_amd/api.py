@@ -37,7 +37,8 @@ class KnnProfile(ctypes.Structure):
     _fields_ = [("ms_prepare", ctypes.c_float), ("ms_main", ctypes.c_float),
                 ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
                 ("main_launches", ctypes.c_int32), ("symmetric", ctypes.c_int32),
-                ("pairs_computed", ctypes.c_int64)]
+                ("pairs_computed", ctypes.c_int64), ("ms_select", ctypes.c_float),
+                ("two_phase", ctypes.c_int32)]
 
 
 class KnnOptions(ctypes.Structure):
@@ -131,9 +132,12 @@ def _dev_matrix(x: torch.Tensor, name: str) -> torch.Tensor:
 
 
 def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
-                        symmetric: bool = False, r_splits: int = 0, variant: int = 0) -> int:
+                        symmetric: bool = False, r_splits: int = 0, variant: int = 0,
+                        schedule: int = 0, block_rows: int = 0) -> int:
+    """Workspace of knn_build (symmetric=True) or knn_search for the same options; `schedule`
+    is the value of their `symmetric` option (0 auto, 1 triangle, 2 full square)."""
     lib = load_library()
-    opt, _ = _options(0, 0, r_splits, False, variant)
+    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows)
     return int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), int(symmetric),
                                           ctypes.byref(opt)))
 

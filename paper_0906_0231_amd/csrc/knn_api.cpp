@@ -281,7 +281,7 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
 }
 
 struct Events {
-    hipEvent_t e[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t e[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool on = false;
     hipError_t create()
     {
@@ -409,6 +409,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         da.n_qtiles = p.n_qtiles;
         e = launch_dist_qreg(da, p.n_qtiles, p.msym, stream);
         if (e != hipSuccess) { set_error("knn_dist_qreg", e); return KNN_EDEVICE; }
+        ev.record(4, stream);
         SelectArgs sa;
         sa.A = da.D;
         sa.lists = lists;
@@ -542,6 +543,8 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pr->main_launches = launches;
         pr->symmetric = (p.tri || p.msym) ? 1 : 0;
         pr->pairs_computed = pairs_computed;
+        pr->two_phase = p.matrix ? 1 : 0;
+        if (p.matrix) (void)hipEventElapsedTime(&pr->ms_select, ev.e[4], ev.e[2]);
     }
     return KNN_OK;
 }

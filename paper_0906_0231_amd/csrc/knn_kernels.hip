@@ -215,7 +215,12 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
 
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(finalize_rows, dim3((unsigned)a.nq), dim3(64), 0, stream, a);
+    int npow = 1, kpow = 1;
+    while (npow < a.S * a.kcap) npow <<= 1;
+    while (kpow < a.k) kpow <<= 1;
+    if (npow > KNN_FIN_MAX || kpow > KNN_MAX_KCAP) return hipErrorInvalidValue;
+    const size_t lds = (size_t)(npow + kpow) * sizeof(u64);
+    hipLaunchKernelGGL(finalize_rows, dim3((unsigned)a.nq), dim3(64), lds, stream, a);
     return hipGetLastError();
 }
 

@@ -32,9 +32,11 @@ __device__ __forceinline__ global_float *scalar_ptr(float *p)
     return (global_float *)(((u64)hi << 32) | lo);
 }
 
+constexpr int DT_PITCH = QG_TR + 4;               // floats per row of a wave's transposition buffer
 struct __attribute__((aligned(16))) DistSmem {
     float r[2][QG_RBUF];
     float c[2][QG_TR];                            // by tile parity: read again in the epilogue
+    float tr[4][32 * DT_PITCH];                   // per wave: its 32 x 64 tile, query-major
 };
 
 template <int DPAD, bool SYM>
@@ -134,7 +136,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
             // register 4 gg + e of block t is reference row j0 + 32 t + 8 gg + 4 h + e
             const int64_t j0 = (int64_t)rt * QG_TR;
             const float INF = __builtin_inff();
-            float *drow = a.D + myq * a.ldd + j0 + 4 * h;
+            // Direct part, through the wave's own LDS buffer: in the accumulators a lane holds 4
+            // consecutive columns of ITS row, so storing from there would write 32 bytes per row
+            // and instruction; read back row-wise, 16 lanes cover the 256 bytes of a row.
+            float *tw = &sm.tr[w][ql * DT_PITCH + 4 * h];
             // does the tile hold the entry of one of this wave's queries with itself?
             const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
                              j0 + QG_TR > a.self_offset + qbase + 32 * w;
@@ -149,8 +154,17 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                         if (j0 + 32 + 8 * gg + 4 * h + e == selfj) v1[e] = INF;
                     }
                 }
-                *(f32x4 *)(drow + 8 * gg) = v0;
-                *(f32x4 *)(drow + 32 + 8 * gg) = v1;
+                *(f32x4 *)(tw + 8 * gg) = v0;
+                *(f32x4 *)(tw + 32 + 8 * gg) = v1;
+            }
+            {
+                const int rr = lane >> 4, cc = (lane & 15) * 4;
+                float *drow = a.D + (qbase + 32 * w + rr) * a.ldd + j0 + cc;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 4 * i) * DT_PITCH + cc];
+                    *(f32x4 *)(drow + (int64_t)(4 * i) * a.ldd) = v;
+                }
             }
             if (SYM && rt >= first + 2) {
                 // beyond the diagonal block: the same pairs as rows j see them; for a fixed

@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 // ---------------------------------------------------------------------------
 // finalize_rows: one wave per query.
 // ---------------------------------------------------------------------------
-constexpr int FIN_MAX = KNN_FIN_MAX;   // most keys one query can bring (S * kcap)
+
 
 __device__ __forceinline__ void bitonic_sort_lds(u64 *keys, int n, int lane)
 {
@@ -210,14 +210,18 @@ __device__ __forceinline__ double group16_sum_f64(double v)
 
 __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
 {
-    __shared__ u64 keys[FIN_MAX];
-    __shared__ u64 outk[KNN_MAX_KCAP];
+    // sized by the launcher to what this call needs (S * kcap keys rounded up to a power of two,
+    // then k rounded up likewise): with one list per query that is 2 KB instead of 17, and three
+    // times as many queries in flight per CU for the row gathers below
+    extern __shared__ u64 fin_lds[];
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
 
     const int nin = a.S * a.kcap;
     int npow = 1;
     while (npow < nin) npow <<= 1;
+    u64 *keys = fin_lds;
+    u64 *outk = fin_lds + npow;
     for (int i = lane; i < npow; i += 64) {
         u64 v = KEY_INF;
         if (i < nin) {

@@ -348,15 +348,17 @@ def test_config1_full(variant):
                 res.dist.cpu().numpy())
 
 
-def _full_size(which, sample):
+def _full_size(which, sample, variant=0, two_phase=None):
     w = workloads.config(which)
-    _say(f"  {w.name}: generated")
+    _say(f"  {w.name}: generated (variant {variant})")
     Rd = w.R.cuda()
     if w.symmetric:
-        res = knn_build(Rd, w.k, w.metric, profile=True)
+        res = knn_build(Rd, w.k, w.metric, variant=variant, profile=True)
     else:
-        res = knn_search(Rd[:w.nq], Rd, w.k, w.metric, self_offset=0, profile=True)
+        res = knn_search(Rd[:w.nq], Rd, w.k, w.metric, self_offset=0, variant=variant, profile=True)
     torch.cuda.synchronize()
+    if two_phase is not None:
+        assert res.profile.two_phase == two_phase
     _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms fused kernel")
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     del Rd
@@ -370,8 +372,9 @@ def _full_size(which, sample):
     assert np.all(s[:, 1:] != s[:, :-1])
 
 
-def test_config2_full():
-    _full_size(2, 1024)
+@pytest.mark.parametrize("variant,two_phase", [(0, 1), (3, 0)])
+def test_config2_full(variant, two_phase):
+    _full_size(2, 1024, variant, two_phase)      # by default the two-phase form (d = 128, matrix of 16 GiB)
 
 
 def test_config3_full():
@@ -384,3 +387,10 @@ def test_config4_full():
 
 def test_config5_full():
     _full_size(5, 48)
+
+
+@pytest.mark.parametrize("variant,two_phase", [(0, 1), (3, 0)])
+def test_paper_table1_shape_full(variant, two_phase):
+    """n = 80 000, d = 256, k = 100, Hellinger (the largest row of the paper's Table 1): the
+    two-phase form by default, the fused kernel on request."""
+    _full_size(6, 256, variant, two_phase)

@@ -50,6 +50,36 @@ def test_workspace_bytes(lib):
     assert f(n, n, d + 1, k, 0, 1) > b            # ragged d: padded copies of both sides
 
 
+def test_workspace_of_the_two_phase_form(lib):
+    """Where the plan writes the distance matrix out, the workspace holds it; the choice follows
+    k, d, the matrix size and the options, and can be overridden."""
+    def ws(n, d, k, **kw):
+        return api.knn_workspace_bytes(n, n, d, k, "sqeuclidean", symmetric=True, **kw)
+
+    def matrix(n):
+        pad = (n + 127) // 128 * 128
+        return pad * (pad + 64) * 4
+
+    # the shape of the paper's Table 1 (n = 80 000, d = 256, k = 100): two-phase by default
+    assert ws(80000, 256, 100) >= matrix(80000)
+    assert ws(80000, 256, 100, variant=3) < matrix(80000) // 8          # fused on request
+    assert ws(80000, 256, 100, schedule=1) < matrix(80000) // 8         # the triangle schedule is fused
+    # short lists and d = 64: only while the problem is small
+    assert ws(40000, 64, 10) >= matrix(40000)
+    assert ws(60000, 64, 10) < matrix(60000) // 8
+    assert ws(60000, 128, 10) >= matrix(60000)
+    # never by default beyond 72 GiB of matrix
+    assert ws(150000, 256, 100) < 72 * 2**30
+    assert ws(150000, 256, 100, variant=4) >= matrix(150000)
+    # d > 256 has no two-phase form: the request falls back to the fused kernels
+    assert ws(20000, 300, 100, variant=4) == ws(20000, 300, 100) < matrix(20000)
+    # queries against a separate reference set: long lists, or a matrix of at most 4 GiB
+    f = api.knn_workspace_bytes
+    assert f(8192, 131072, 128, 100) >= 8192 * 131072 * 4
+    assert f(4096, 131072, 128, 16) >= 4096 * 131072 * 4
+    assert f(65536, 131072, 128, 16) < 65536 * 131072 * 4 // 8
+
+
 def test_bad_arguments_are_rejected_on_the_host(lib):
     one = ctypes.c_void_p(256)                  # never dereferenced: checks fail first
     ws = ctypes.c_void_p(4096)
