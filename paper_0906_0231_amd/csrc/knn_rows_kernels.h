@@ -272,13 +272,40 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
         const float *x = a.Q + q * (int64_t)a.d;
         const bool cosine = a.mode == FIN_RESCORE_COS;
         const bool root = a.mode == FIN_RESCORE_HEL;
+        // Hellinger: the square roots of the query's own coordinates are the same for every
+        // winner; a lane takes them once (its 4 of every 64 coordinates, up to d = 256)
+        const bool pre = root && a.vec4 && a.d <= 256;
+        double xs[4][4];
+        if (pre) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = gl * 4 + 64 * i;
+                f32x4 u = {0.f, 0.f, 0.f, 0.f};
+                if (c < a.d) u = *(const f32x4 *)(x + c);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xs[i][e] = sqrt((double)u[e]);
+            }
+        }
         for (int r0 = 0; r0 < a.k; r0 += 4) {
             const int r = r0 + g16;
             const int32_t j = r < a.k ? (int32_t)(uint32_t)keys[r] : -1;
             const bool ok = j >= 0 && j < a.nr;
             const float *y = a.R + (int64_t)(ok ? j : 0) * a.d;
             double s = 0.0, uu = 0.0, vv = 0.0;
-            if (ok && a.vec4) {
+            if (ok && pre) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = gl * 4 + 64 * i;
+                    if (c < a.d) {
+                        f32x4 v = *(const f32x4 *)(y + c);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            double t = xs[i][e] - sqrt((double)v[e]);
+                            s = fma(t, t, s);
+                        }
+                    }
+                }
+            } else if (ok && a.vec4) {
                 for (int c = gl * 4; c < a.d; c += 64) {
                     f32x4 u = *(const f32x4 *)(x + c), v = *(const f32x4 *)(y + c);
 #pragma unroll
