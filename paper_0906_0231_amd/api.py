@@ -142,6 +142,21 @@ def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
                                           ctypes.byref(opt)))
 
 
+def _own_workspace(lib, opt, nq, nr, d, k, metric, self_flag, device) -> torch.Tensor:
+    """Workspace for a call that brought none.  The default plan may want the whole distance
+    matrix (up to 72 GiB); if the device cannot spare that, the fused plan, which needs none, is
+    requested instead (opt.variant is changed accordingly)."""
+    nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), self_flag, ctypes.byref(opt)))
+    try:
+        return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    except torch.cuda.OutOfMemoryError:
+        if opt.variant != 0:
+            raise
+        opt.variant = 3
+        nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), self_flag, ctypes.byref(opt)))
+        return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
 @dataclass
 class KnnResult:
     idx: torch.Tensor                 # [nq, k] int32
@@ -163,8 +178,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
             torch.empty((n, k), dtype=torch.float32, device=X.device))
         opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows)
         if workspace is None:
-            nbytes = int(lib.knn_workspace_bytes_ex(n, n, d, k, _metric(metric), 1, ctypes.byref(opt)))
-            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
+            workspace = _own_workspace(lib, opt, n, n, d, k, metric, 1, X.device)
         stream = torch.cuda.current_stream(X.device).cuda_stream
         _check(lib.knn_build_ex(X.data_ptr(), n, d, k, _metric(metric), idx.data_ptr(),
                                 dist.data_ptr(), workspace.data_ptr(), workspace.numel(),
@@ -190,8 +204,7 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
             torch.empty((nq, k), dtype=torch.float32, device=Q.device))
         opt, prof = _options(0, rescore, r_splits, profile, variant)
         if workspace is None:
-            nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), 0, ctypes.byref(opt)))
-            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=Q.device)
+            workspace = _own_workspace(lib, opt, nq, nr, d, k, metric, 0, Q.device)
         stream = torch.cuda.current_stream(Q.device).cuda_stream
         _check(lib.knn_search_ex(Q.data_ptr(), nq, R.data_ptr(), nr, d, k, _metric(metric),
                                  self_offset, idx.data_ptr(), dist.data_ptr(),
