@@ -161,7 +161,8 @@ def main() -> int:
         knn_valu_calibration(1 << 16, 4)
         valu_tops, _ = knn_valu_calibration(1 << 21, 4)
         out["roofline"].update({"bound": "alu", "peak": VALU_F32_PLAIN_TOPS,
-                                "frac": achieved / VALU_F32_PLAIN_TOPS, "kernel": "knn_fold",
+                                "frac": achieved / VALU_F32_PLAIN_TOPS,
+                                "kernel": "knn_fold_dist" if two_phase else "knn_fold",
                                 "peak_derivation": "256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz, one flop per "
                                                    "instruction (sub, add|.|): half the published FMA rate",
                                 "measured_peak": valu_tops,

@@ -123,6 +123,49 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
         p.n_cpad = (nr + KNN_FOLD_NR - 1) / KNN_FOLD_NR * KNN_FOLD_NR;
         p.B = p.NB = p.NBp = 0;
+        // Two-phase form of the fold (distances written out, then select_rows): on request, or by
+        // default while the matrix is at most 72 GiB for long lists, for knn_build with d >= 64,
+        // where computing each pair once halves the vector work that bounds this path (measured:
+        // n = 65 536, d = 128, k = 32 28.0 -> 18.2 ms; d = 64 13.5 -> 11.7 ms), and for small
+        // problems (n = 16 384: 4.0 -> 1.5 ms).
+        {
+            const int64_t cpad128 = (nr + KNN_TILE - 1) / KNN_TILE * KNN_TILE;
+            p.ldd = cpad128 + 64;
+            const double matrix_bytes = (double)p.nq_pad * (double)p.ldd * sizeof(float);
+            const bool msym = self && symmetric != 2;
+            const bool matrix_ok = cpad128 < ((int64_t)1 << 28);
+            if (variant == 4)
+                p.matrix = matrix_ok;
+            else if (variant == 0 && matrix_ok && matrix_bytes <= 72.0 * 1073741824.0)
+                p.matrix = p.kcap > 32 || (msym ? d >= 64 : matrix_bytes <= 4.0 * 1073741824.0);
+            if (p.matrix) {
+                p.msym = msym;
+                p.n_rt64 = (int32_t)((nr + KNN_FOLD_NR - 1) / KNN_FOLD_NR);
+                const int64_t qblocks = (nq + 255) / 256;
+                const int64_t tiles = qblocks * p.n_rt64 / (p.msym ? 2 : 1);
+                int64_t chunk = (tiles + 2047) / 2048;     // 4 workgroups fit a CU: aim at two rounds of them
+                if (chunk < 4) chunk = 4;
+                if (chunk > 64) chunk = 64;
+                p.chunk = (int32_t)chunk;
+                p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
+                int32_t skcap;
+                select_plan(nq, nr, k, skcap, p.S, p.sel_seg);
+                p.nlists = p.S;
+                p.rt_per_split = 0;
+                size_t o = 0;
+                p.off_qp = o;
+                o = align_up(o + (size_t)p.nq_pad * p.dpad * sizeof(float), 256);
+                p.off_rp = o;
+                o = align_up(o + (size_t)p.n_cpad * p.dpad * sizeof(float), 256) + 256;
+                p.off_c = p.off_sq = p.off_bound = o;
+                p.off_D = o;
+                o = align_up(o + (size_t)p.nq_pad * p.ldd * sizeof(float), 256);
+                p.off_lists = o;
+                o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
+                p.total = o;
+                return true;
+            }
+        }
         const int64_t groups = (nq + 63) / 64;
         int64_t S = r_splits > 0 ? r_splits : (8192 + groups - 1) / groups;
         const int64_t smax = KNN_FIN_MAX / p.kcap;
@@ -347,7 +390,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
 
     // ---- prologue: norms and scaled copies ----
     if (p.fold) {
-        PackArgs pq = {Q, qp, nq, d, p.dpad, 64, (uint32_t *)cr};
+        PackArgs pq = {Q, qp, nq, d, p.dpad, 64, p.matrix ? nullptr : (uint32_t *)cr};
         e = launch_pack(pq, stream);
         if (e != hipSuccess) { set_error("pack_tiles(Q)", e); return KNN_EDEVICE; }
         PackArgs pk = {R, rp, nr, d, p.dpad, KNN_FOLD_NR, nullptr};
@@ -370,7 +413,47 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     // ---- fused distance + selection ----
     int32_t launches = 1;
     int64_t pairs_computed = p.nq_pad * p.n_cpad;
-    if (p.fold) {
+    if (p.fold && p.matrix) {
+        FoldDistArgs fd;
+        fd.Qpk = qp;
+        fd.Rpk = rp;
+        fd.D = (float *)(ws + p.off_D);
+        fd.ldd = p.ldd;
+        fd.nq = nq;
+        fd.nr = nr;
+        fd.self_offset = self_offset;
+        fd.n_tiles = p.n_rt64;
+        fd.dpad = p.dpad;
+        fd.metric = (int32_t)metric;
+        fd.chunk = p.chunk;
+        fd.n_chunks = p.n_chunks;
+        fd.n_qblocks = (int32_t)((nq + 255) / 256);
+        e = launch_fold_dist(fd, p.msym, stream);
+        if (e != hipSuccess) { set_error("knn_fold_dist", e); return KNN_EDEVICE; }
+        ev.record(4, stream);
+        SelectArgs sa;
+        sa.A = fd.D;
+        sa.lists = lists;
+        sa.m = nq;
+        sa.n = nr;
+        sa.lda = p.ldd;
+        sa.seg = p.sel_seg;
+        sa.k = k;
+        sa.kcap = p.kcap;
+        sa.S = p.S;
+        sa.vec4 = 1;
+        e = launch_select(sa, stream);
+        if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+        launches = 2;
+        const int64_t groups = (nq + 63) / 64;
+        if (p.msym) {
+            pairs_computed = 0;
+            for (int64_t g = 0; g < groups; ++g)
+                if (p.n_rt64 > g) pairs_computed += (int64_t)(p.n_rt64 - g) * 64 * KNN_FOLD_NR;
+        } else {
+            pairs_computed = groups * 64 * (int64_t)p.n_rt64 * KNN_FOLD_NR;
+        }
+    } else if (p.fold) {
         FoldArgs fa;
         fa.Qpk = qp;
         fa.Rpk = rp;

@@ -60,6 +60,21 @@ struct FoldArgs {
     int32_t dpad, k, kcap, metric, S;
 };
 
+// the fold with its distances written out (two-phase form)
+struct FoldDistArgs {
+    const float *Qpk;  // as FoldArgs
+    const float *Rpk;
+    float *D;          // [ceil(nq/128)*128, ldd]
+    int64_t ldd;
+    int64_t nq, nr;
+    int64_t self_offset;
+    int64_t n_tiles;   // reference tiles of KNN_FOLD_NR rows
+    int32_t dpad, metric;
+    int32_t chunk;     // reference tiles per workgroup
+    int32_t n_chunks;  // workgroups per block of query groups (those past the end leave at once)
+    int32_t n_qblocks; // blocks of 4 query groups (256 rows)
+};
+
 struct PackArgs {
     const float *X;    // [n, d]
     float *Xpk;        // [ceil(n/NR)][dpad/4][NR][4]; zero where the source has no value
@@ -127,6 +142,7 @@ struct SelectArgs {
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
+hipError_t launch_fold_dist(const FoldDistArgs &a, bool sym, hipStream_t stream);
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);

@@ -152,6 +152,120 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
     merge_queues<FOLD_QCAP, 64>(st, a.kcap, a.k, lane);
 }
 
+// ---------------------------------------------------------------------------
+// knn_fold_dist<METRIC, SYM>: the fold of knn_fold with the paper's two phases kept apart
+// (Sect. 5-6): the distances are written out, select_rows picks the k smallest per row
+// afterwards.  With SYM (knn_build: these distances are symmetric, Sect. 3) a wave computes only
+// the tiles from its own diagonal tile on and stores each value beyond it twice, D[q][j] and
+// D[j][q] -- half the vector instructions, which are what bounds this path.
+// Same loop as knn_fold: lane = query, one accumulator per reference of a 64-row tile, reference
+// coordinates through scalar registers.  The waves of a workgroup take consecutive query groups
+// and walk the same tiles together (the scalar cache fetches a line once for all of them); a
+// wave skips the at most three tiles below its own diagonal.
+// Stores: in the mirrored part the lanes hold 64 consecutive queries of one row (256 bytes per
+// instruction); the direct part, where a lane holds 64 consecutive columns of ITS row, goes
+// through a per-wave LDS buffer 16 columns at a time and leaves as 64-byte row segments.
+// ---------------------------------------------------------------------------
+constexpr int FD_PITCH = 20;                       // floats per row of the transposition buffer (16 + pad, 16-byte aligned)
+
+template <int METRIC, bool SYM>
+__global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOLD_WAVES) void knn_fold_dist(FoldDistArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float s_tr[FOLD_WAVES][64 * FD_PITCH];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    // chunk-major numbering, as in knn_dist_qreg: the 8 XCDs get equal shares of every chunk index
+    const int chunk = blockIdx.x / a.n_qblocks;
+    const int qb = blockIdx.x - chunk * a.n_qblocks;
+    const int64_t qg = (int64_t)qb * FOLD_WAVES + w;
+    const int64_t q0 = qg * 64;
+    if (q0 >= a.nq) return;                        // whole wave; the kernel has no barrier
+    const int64_t myq = q0 + lane;                 // < nq_pad: the matrix and the packed copy are that tall
+    const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
+
+    // tiles of 64 references; the workgroup's first diagonal tile is that of its first wave
+    const int64_t t_first = SYM ? (int64_t)qb * FOLD_WAVES : 0;
+    const int64_t t0 = t_first + (int64_t)chunk * a.chunk;
+    const int64_t t1 = min(t0 + a.chunk, a.n_tiles);
+
+    const f32x4 *qp = (const f32x4 *)(a.Qpk + qg * (int64_t)(a.dpad >> 2) * 256) + lane;
+    const_f32_ptr Rc = (const_f32_ptr)a.Rpk;       // never written while this kernel runs
+    const int ncq = a.dpad >> 2;
+    float *tr = &s_tr[w][0];
+
+    for (int64_t tj = t0; tj < t1; ++tj) {
+        if (SYM && tj < qg) continue;              // below this wave's diagonal: the other wave's mirror writes it
+        const int64_t j0 = tj * FOLD_NR;
+        f32x16 acc[FOLD_NR / 16];                  // register 16 t + r: reference j0 + 16 t + r
+#pragma unroll
+        for (int t = 0; t < FOLD_NR / 16; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        const_f32x16_ptr tile = (const_f32x16_ptr)(Rc + tj * (int64_t)ncq * (FOLD_NR * 4));
+        f32x4 qn = qp[0];
+        f32x16 cur0 = tile[0], cur1 = tile[1];     // scalar loads run one batch ahead, as in knn_fold
+        for (int cq = 0; cq < ncq; ++cq) {
+            const f32x4 q = qn;
+            if (cq + 1 < ncq) qn = qp[(cq + 1) * 64];
+#pragma unroll
+            for (int b = 0; b < FOLD_NR / 8; ++b) {
+                const f32x16 nxt0 = tile[(cq * (FOLD_NR / 8) + b + 1) * 2];
+                const f32x16 nxt1 = tile[(cq * (FOLD_NR / 8) + b + 1) * 2 + 1];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[b >> 1][8 * (b & 1) + i] =
+                            fold_step<METRIC>(q[e], cur0[4 * i + e], acc[b >> 1][8 * (b & 1) + i]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[b >> 1][8 * (b & 1) + 4 + i] =
+                            fold_step<METRIC>(q[e], cur1[4 * i + e], acc[b >> 1][8 * (b & 1) + 4 + i]);
+                }
+                cur0 = nxt0;
+                cur1 = nxt1;
+            }
+        }
+        // a row with itself: +inf (only a tile that overlaps this wave's own rows can hold it)
+        if (a.self_offset >= 0 && j0 < a.self_offset + q0 + 64 && j0 + FOLD_NR > a.self_offset + q0) {
+#pragma unroll
+            for (int t = 0; t < FOLD_NR / 16; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (j0 + 16 * t + r == selfj) acc[t][r] = __builtin_inff();
+        }
+        // direct part: 16 columns at a time through the wave's LDS buffer
+        {
+            const int rr = lane >> 2, cc = (lane & 3) * 4;
+            float *drow = a.D + (q0 + rr) * a.ldd + j0 + cc;
+#pragma unroll
+            for (int t = 0; t < FOLD_NR / 16; ++t) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 v = {acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]};
+                    *(f32x4 *)(tr + lane * FD_PITCH + 4 * g) = v;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f32x4 v = *(const f32x4 *)(tr + (rr + 16 * i) * FD_PITCH + cc);
+                    *(f32x4 *)(drow + (int64_t)(16 * i) * a.ldd + 16 * t) = v;
+                }
+            }
+        }
+        if (SYM && tj > qg) {
+            // a row address every lane agrees on plus a 32-bit lane offset (keeps the 64 store
+            // addresses from taking two registers each)
+            global_float *mbase = scalar_ptr(a.D + j0 * a.ldd);
+            const uint32_t voff = (uint32_t)myq;
+#pragma unroll
+            for (int t = 0; t < FOLD_NR / 16; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) (mbase + (int64_t)(16 * t + r) * a.ldd)[voff] = acc[t][r];
+        }
+    }
+}
+
 // pack_tiles: Xpk[tile t][coordinate quad cq][row r][e] = X[T t + r][4 cq + e], zero outside
 // (T = rows_per_tile).
 // One thread per (row, quad); consecutive threads take consecutive quads of a row.

@@ -197,6 +197,22 @@ hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_fold_dist(const FoldDistArgs &a, bool sym, hipStream_t stream)
+{
+    dim3 grid((unsigned)((int64_t)a.n_qblocks * a.n_chunks)), block(64 * FOLD_WAVES);
+    if (a.metric == 3 && sym)
+        hipLaunchKernelGGL((knn_fold_dist<3, true>), grid, block, 0, stream, a);
+    else if (a.metric == 3)
+        hipLaunchKernelGGL((knn_fold_dist<3, false>), grid, block, 0, stream, a);
+    else if (a.metric == 4 && sym)
+        hipLaunchKernelGGL((knn_fold_dist<4, true>), grid, block, 0, stream, a);
+    else if (a.metric == 4)
+        hipLaunchKernelGGL((knn_fold_dist<4, false>), grid, block, 0, stream, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream)
 {
     int64_t total = (a.n + a.rows_per_tile - 1) / a.rows_per_tile * a.rows_per_tile * (int64_t)(a.dpad >> 2);

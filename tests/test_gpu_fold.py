@@ -34,7 +34,9 @@ def _check(Q, R, self_idx, k, metric, g_idx, g_dist, strict=False, atol=0.0):
 
 
 # several query groups of 64, ragged tails in n and d (d not a multiple of 4), every list capacity,
-# k = n - 1, slices of the reference range
+# k = n - 1, slices of the reference range; fused (3) and two-phase (4: matrix written out, each
+# pair of rows once, then select_rows)
+@pytest.mark.parametrize("variant", [3, 4])
 @pytest.mark.parametrize("metric", ["l1", "linf"])
 @pytest.mark.parametrize("n,d,k,splits", [
     (1500, 64, 10, 0),
@@ -47,21 +49,23 @@ def _check(Q, R, self_idx, k, metric, g_idx, g_dist, strict=False, atol=0.0):
     (70, 3, 69, 0),
     (4100, 20, 12, 7),
 ])
-def test_fold_build_small(metric, n, d, k, splits):
-    _say(f"  fold build {metric} n={n} d={d} k={k} splits={splits}")
+def test_fold_build_small(metric, n, d, k, splits, variant):
+    _say(f"  fold build {metric} n={n} d={d} k={k} splits={splits} variant={variant}")
     X = workloads.gaussian(n, d, seed=4000 + n + d)
-    res = knn_build(X.cuda(), k, metric, r_splits=splits)
+    res = knn_build(X.cuda(), k, metric, r_splits=splits, variant=variant, profile=True)
+    assert res.profile.two_phase == (1 if variant == 4 else 0)
     torch.cuda.synchronize()
     _check(X.numpy(), X.numpy(), np.arange(n), k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
+@pytest.mark.parametrize("variant", [3, 4])
 @pytest.mark.parametrize("metric", ["l1", "linf"])
 @pytest.mark.parametrize("nq,nr,off", [(100, 3000, -1), (257, 2000, 300), (64, 64, 0), (1, 5000, 4999)])
-def test_fold_search(metric, nq, nr, off):
-    _say(f"  fold search {metric} nq={nq} nr={nr} off={off}")
+def test_fold_search(metric, nq, nr, off, variant):
+    _say(f"  fold search {metric} nq={nq} nr={nr} off={off} variant={variant}")
     R = workloads.mixture(nr, 24, 5, seed=50 + nr)
     Q = R[off:off + nq].contiguous() if off >= 0 else workloads.gaussian(nq, 24, seed=51)
-    res = knn_search(Q.cuda(), R.cuda(), 8, metric, self_offset=off)
+    res = knn_search(Q.cuda(), R.cuda(), 8, metric, self_offset=off, variant=variant)
     torch.cuda.synchronize()
     self_idx = np.arange(nq) + off if off >= 0 else None
     _check(Q.numpy(), R.numpy(), self_idx, 8, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
@@ -74,8 +78,8 @@ def test_fold_exact_on_integers(metric):
     without the re-pricing pass."""
     rng = np.random.default_rng(8)
     X = torch.from_numpy(rng.integers(-6, 7, size=(900, 6)).astype(np.float32))
-    for rescore in (0, 2):
-        res = knn_build(X.cuda(), 9, metric, rescore=rescore)
+    for rescore, variant in ((0, 3), (2, 3), (0, 4), (2, 4)):
+        res = knn_build(X.cuda(), 9, metric, rescore=rescore, variant=variant)
         torch.cuda.synchronize()
         o_idx, o_dist, _ = oracle.build_knn(X.numpy(), 9, metric)
         assert np.array_equal(res.idx.cpu().numpy(), o_idx)
@@ -87,29 +91,33 @@ def test_fold_matches_hamming_on_bits():
     the matrix-core kernel must give the same lists."""
     rng = np.random.default_rng(9)
     X = torch.from_numpy((rng.random((2000, 96)) < 0.3).astype(np.float32)).cuda()
-    a = knn_build(X, 10, "l1")
     b = knn_build(X, 10, "sqeuclidean", symmetric=2)
-    torch.cuda.synchronize()
-    assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
+    for variant in (3, 4):
+        a = knn_build(X, 10, "l1", variant=variant)
+        torch.cuda.synchronize()
+        assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
 
 
-def test_fold_deterministic_and_search_equals_build():
+@pytest.mark.parametrize("variant", [3, 4])
+def test_fold_deterministic_and_search_equals_build(variant):
     X = workloads.gaussian(3000, 33, seed=12).cuda()
-    a = knn_build(X, 7, "l1")
-    b = knn_build(X, 7, "l1")
-    c = knn_search(X, X, 7, "l1", self_offset=0)
+    a = knn_build(X, 7, "l1", variant=variant)
+    b = knn_build(X, 7, "l1", variant=variant)
+    c = knn_search(X, X, 7, "l1", self_offset=0, variant=variant)    # full square where a, b take the triangle
     torch.cuda.synchronize()
     assert torch.equal(a.idx, b.idx) and torch.equal(a.dist, b.dist)
     assert torch.equal(a.idx, c.idx) and torch.equal(a.dist, c.dist)
 
 
-def test_fold_config_sampled():
+@pytest.mark.parametrize("variant,two_phase", [(0, 1), (3, 0)])
+def test_fold_config_sampled(variant, two_phase):
     """The benchmark's Manhattan workload at full size (n = 65 536, d = 128, k = 32), oracle on
-    sampled rows."""
+    sampled rows: two-phase by default (each pair of rows once), fused on request."""
     w = workloads.config(7)
-    res = knn_build(w.R.cuda(), w.k, w.metric, profile=True)
+    res = knn_build(w.R.cuda(), w.k, w.metric, variant=variant, profile=True)
     torch.cuda.synchronize()
-    _say(f"    gpu: {res.profile.ms_main:.1f} ms fused kernel")
+    assert res.profile.two_phase == two_phase and res.profile.symmetric == two_phase
+    _say(f"    gpu: {res.profile.ms_main:.1f} ms main kernel(s), variant {variant}")
     rng = np.random.default_rng(7)
     rows = np.unique(np.concatenate([rng.choice(w.n, 300, replace=False), [0, 63, 64, w.n - 1]]))
     R = w.R.numpy()
@@ -123,7 +131,7 @@ def test_fold_lists_short_of_k_for_long(metric, k):
     (it did once, as a (+inf, index) key, and the duplicate keys stalled the rank merge)."""
     _say(f"  fold short lists {metric} k={k}")
     w = workloads.config(7)
-    res = knn_build(w.R.cuda(), k, metric)
+    res = knn_build(w.R.cuda(), k, metric, variant=3)
     torch.cuda.synchronize()
     rng = np.random.default_rng(70 + k)
     rows = np.unique(np.concatenate([rng.choice(w.n, 150, replace=False), [0, 63, 64, w.n - 1]]))
