@@ -77,8 +77,9 @@ typedef struct {
                               or the symmetric form of variant 4) */
     int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
                               padding of ragged tiles included */
-    float ms_select;       /* variant 4 only: the part of ms_main spent selecting from the matrix */
-    int32_t two_phase;     /* 1 if variant 4 was used (matrix written out, then selected from) */
+    float ms_select;       /* two_phase == 1 only: the part of ms_main spent selecting from the matrix */
+    int32_t two_phase;     /* 0: fused kernels.  1: variant 4, the matrix written out whole, then selected
+                              from.  2: variant 4 block by block (pairs of row panels) */
 } knn_profile_t;
 
 /* Optional knobs; pass NULL for defaults.  Zero-initialise, then set fields. */
@@ -110,11 +111,19 @@ typedef struct {
                            KNN_LINF.  Auto takes it when that matrix is at most 72 GiB,
                            symmetric != 1 and: k > 32; or knn_build (symmetric distance) with
                            d > 96 or n <= 49152 (KNN_L1, KNN_LINF: d >= 64); or the matrix is
-                           at most 4 GiB */
-    int32_t block_rows; /* symmetric schedule only.  Rows per block; rounded up to a multiple
+                           at most 4 GiB.  A larger matrix is never written out whole: knn_build
+                           with a symmetric distance walks it by pairs of row panels (auto: for
+                           KNN_L1 / KNN_LINF with d >= 64; on the matrix cores for d > 96 and
+                           either k > 32 or a fused triangle schedule that would fill the device
+                           badly), other calls stay fused */
+    int32_t block_rows; /* Fused symmetric schedule: rows per block; rounded up to a multiple
                            of 128.  A round launches ceil(ceil(n/block_rows)/2) workgroups.
                            0 = auto: the multiple of 128 for which the rounds fill the device's
-                           512 workgroup slots best (n/1024 when n is a power of two >= 2^17) */
+                           512 workgroup slots best (n/1024 when n is a power of two >= 2^17).
+                           With variant 4 and knn_build (symmetric distance): rows per panel of
+                           the block-by-block form, rounded up to a multiple of 256, which is then
+                           used whatever the size; 0 = auto (whole matrix up to 72 GiB, panels
+                           of 65536 rows beyond) */
     int32_t reserved;   /* must be 0 */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
                            kernels with events, waits for them and fills this in */

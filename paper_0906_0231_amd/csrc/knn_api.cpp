@@ -40,7 +40,10 @@ struct Plan {
     bool msym;      // ... computing each unordered pair of rows once
     int32_t n_rt64, chunk, n_chunks; // ... reference tiles of 64 rows, tiles per workgroup, workgroups per query tile
     int64_t sel_seg;                 // ... columns per segment of select_rows
-    size_t off_D;                    // ... the matrix, [nq_pad, ldd]
+    bool blocked;                    // ... panel pair by panel pair (the whole matrix would not fit)
+    int64_t P;                       // ... rows per panel (multiple of 256)
+    size_t off_D2;                   // ... blocked: buffer of the transposed block
+    size_t off_D;                    // ... the matrix, [nq_pad, ldd]; blocked: one block, [P, ldd]
     int64_t ldd;                     // ... its row pitch in floats: n_cpad + 64, an odd multiple of 256 bytes, so that
                                      //     a column of the matrix does not fall into one memory channel
     int32_t B, NB, NBp; // block rows, block count, block count rounded up to even
@@ -98,6 +101,28 @@ void select_plan(int64_t m, int64_t n, int32_t k, int32_t &kcap, int32_t &S, int
     S = (int32_t)((n + seg - 1) / seg);
 }
 
+// Two-phase plan: is the matrix written out whole or block by block, and with which panel size.
+// Whole while it is at most 72 GiB.  Beyond that, for knn_build with a symmetric distance, the
+// rows are cut into panels of 65 536 (two block buffers of 17 GB) and every pair of panels is
+// written once; block_rows > 0 with variant 4 sets the panel size and forces this form at any
+// size (tests).  Returns false if the two-phase plan cannot be used at all.
+constexpr double KNN_MATRIX_CAP_BYTES = 72.0 * 1073741824.0;
+bool two_phase_layout(Plan &p, int64_t cpad128, double matrix_bytes, bool msym, int32_t variant, int32_t block_rows)
+{
+    p.blocked = false;
+    p.P = 0;
+    int64_t P = 65536;
+    const bool forced = variant == 4 && block_rows > 0 && msym;
+    if (forced) P = (int64_t)align_up((size_t)block_rows, 256);
+    if ((forced || matrix_bytes > KNN_MATRIX_CAP_BYTES) && P < cpad128) {
+        if (!msym) return false;                  // no pair of rows to save: the fused kernels do that better
+        p.blocked = true;
+        p.P = P;
+        p.ldd = P + 64;
+    }
+    return true;
+}
+
 // Sizes are assumed validated.  r_splits == 0 picks the slice count of the reference range
 // (see below), block_rows == 0 and symmetric == 0 take the cost model above.
 bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
@@ -109,8 +134,10 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.matrix = p.msym = false;
     p.n_rt64 = p.chunk = p.n_chunks = 0;
     p.sel_seg = 0;
-    p.off_D = 0;
+    p.off_D = p.off_D2 = 0;
     p.ldd = 0;
+    p.blocked = false;
+    p.P = 0;
     if (p.fold) {
         // lane = query, 64 per wave; the reference range is cut so that the device has
         // several thousand waves to run
@@ -136,13 +163,16 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
             const bool matrix_ok = cpad128 < ((int64_t)1 << 28);
             if (variant == 4)
                 p.matrix = matrix_ok;
-            else if (variant == 0 && matrix_ok && matrix_bytes <= 72.0 * 1073741824.0)
+            else if (variant == 0 && matrix_ok && matrix_bytes <= KNN_MATRIX_CAP_BYTES)
                 p.matrix = p.kcap > 32 || (msym ? d >= 64 : matrix_bytes <= 4.0 * 1073741824.0);
+            else if (variant == 0 && matrix_ok)
+                p.matrix = msym && d >= 64;       // blocked: half the vector work at any size
+            if (p.matrix) p.matrix = two_phase_layout(p, cpad128, matrix_bytes, msym, variant, block_rows);
             if (p.matrix) {
                 p.msym = msym;
                 p.n_rt64 = (int32_t)((nr + KNN_FOLD_NR - 1) / KNN_FOLD_NR);
                 const int64_t qblocks = (nq + 255) / 256;
-                const int64_t tiles = qblocks * p.n_rt64 / (p.msym ? 2 : 1);
+                const int64_t tiles = p.blocked ? (p.P / 256) * (p.P / KNN_FOLD_NR) : qblocks * p.n_rt64 / (p.msym ? 2 : 1);
                 int64_t chunk = (tiles + 2047) / 2048;     // 4 workgroups fit a CU: aim at two rounds of them
                 if (chunk < 4) chunk = 4;
                 if (chunk > 64) chunk = 64;
@@ -150,6 +180,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                 p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
                 int32_t skcap;
                 select_plan(nq, nr, k, skcap, p.S, p.sel_seg);
+                if (p.blocked) p.S = 1;
                 p.nlists = p.S;
                 p.rt_per_split = 0;
                 size_t o = 0;
@@ -159,7 +190,9 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                 o = align_up(o + (size_t)p.n_cpad * p.dpad * sizeof(float), 256) + 256;
                 p.off_c = p.off_sq = p.off_bound = o;
                 p.off_D = o;
-                o = align_up(o + (size_t)p.nq_pad * p.ldd * sizeof(float), 256);
+                o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldd * sizeof(float), 256);
+                p.off_D2 = o;
+                if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
                 p.off_lists = o;
                 o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
                 p.total = o;
@@ -221,14 +254,25 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.matrix = false;
     if (variant == 4)
         p.matrix = matrix_ok;
-    else if (variant == 0 && symmetric != 1 && matrix_ok && matrix_bytes <= 72.0 * 1073741824.0)
+    else if (variant == 0 && symmetric != 1 && matrix_ok && matrix_bytes <= KNN_MATRIX_CAP_BYTES)
         p.matrix = p.kcap > 32 || (msym ? (dpad32 >= 128 || p.n_cpad <= 49152) : matrix_bytes <= 4.0 * 1073741824.0);
+    else if (variant == 0 && symmetric != 1 && matrix_ok)
+        // block by block (measured, ms fused -> blocked): long lists at any size (k = 100:
+        // n = 262 144 293 -> 200, n = 2^20 3201 -> 3080); short lists where the fused plan would
+        // be the full square (n = 150 000, d = 256: 99 -> 65; d = 128: 65 -> 45) or a triangle
+        // whose rounds fill the device badly (n = 200 000: 170 -> 114, n = 400 000: 515 -> 447;
+        // but n = 524 288: 656 against 766, and d = 128, n = 262 144: 119 against 134)
+        // -- all for d > 96: at d = 64 the stores bound it (n = 262 144, k = 100: 100 against 108)
+        p.matrix = msym && dpad32 >= 128 &&
+                   (p.kcap > 32 || !p.tri || (dpad32 >= 192 && pair_cost_ratio(nr, p.B, p.kcap) > 0.74));
+    if (p.matrix) p.matrix = two_phase_layout(p, p.n_cpad, matrix_bytes, msym, variant, block_rows);
     if (p.matrix) {
         p.dpad = dpad32;
         p.qreg = p.qres = p.tri = false;
         p.msym = msym;
         p.n_rt64 = (int32_t)((nr + 63) / 64);
-        const int64_t tiles = (int64_t)p.n_qtiles * p.n_rt64 / (p.msym ? 2 : 1);
+        const int64_t tiles = p.blocked ? (p.P / KNN_TILE) * (p.P / 64)
+                                        : (int64_t)p.n_qtiles * p.n_rt64 / (p.msym ? 2 : 1);
         int64_t chunk = (tiles + 1023) / 1024;
         if (chunk < 4) chunk = 4;
         if (chunk > 64) chunk = 64;
@@ -236,6 +280,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
         int32_t skcap;
         select_plan(nq, nr, k, skcap, p.S, p.sel_seg);
+        if (p.blocked) p.S = 1;                   // lists are continued from block to block: one per row
         p.nlists = p.S;
         p.rt_per_split = 0;
         p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
@@ -250,7 +295,9 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;
         p.off_bound = o;
         p.off_D = o;
-        o = align_up(o + (size_t)p.nq_pad * p.ldd * sizeof(float), 256);
+        o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldd * sizeof(float), 256);
+        p.off_D2 = o;
+        if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
         p.total = o;
@@ -346,6 +393,126 @@ struct Events {
     }
 };
 
+// Phase 1 + Phase 2 of the two-phase plan.  Whole matrix: one launch of the distance kernel
+// (all of it, or the triangle mirrored) and one of select_rows.  Blocked (the matrix would not
+// fit): the rows are cut into panels of p.P; for every unordered pair of panels (a, b) the block
+// D[a][b] is written once, together with its transpose if a != b, and select_rows continues the
+// lists of the rows of a (and of b) with the columns of that block.
+knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                           int32_t k, knn_metric_t metric, int64_t self_offset, float *qp, float *rp, float *cr,
+                           u64 *lists, char *ws, hipStream_t stream, Events &ev, int32_t &launches,
+                           int64_t &pairs_computed)
+{
+    (void)Q;
+    float *D0 = (float *)(ws + p.off_D);
+    float *D1 = (float *)(ws + p.off_D2);
+    launches = 0;
+    pairs_computed = 0;
+    hipError_t e;
+
+    // one block: queries [q0, q0 + mq) against references [r0, r0 + mr)
+    auto dist = [&](int64_t q0, int64_t mq, int64_t r0, int64_t mr, int mode, int64_t self_off) -> hipError_t {
+        ++launches;
+        if (p.fold) {
+            FoldDistArgs fd;
+            fd.Qpk = qp + q0 * p.dpad;              // packed by tiles of 64 rows; q0 is a multiple of 256
+            fd.Rpk = rp + r0 * p.dpad;
+            fd.D = D0;
+            fd.Dm = mode == DIST_RECT_MIRROR ? D1 : D0;
+            fd.ldd = p.ldd;
+            fd.nq = mq;
+            fd.nr = mr;
+            fd.self_offset = self_off;
+            fd.n_tiles = (mr + KNN_FOLD_NR - 1) / KNN_FOLD_NR;
+            fd.dpad = p.dpad;
+            fd.metric = (int32_t)metric;
+            fd.chunk = p.chunk;
+            fd.n_chunks = (int32_t)((fd.n_tiles + p.chunk - 1) / p.chunk);
+            fd.n_qblocks = (int32_t)((mq + 255) / 256);
+            const int64_t groups = (mq + 63) / 64;
+            if (mode == DIST_TRIANGLE) {
+                for (int64_t g = 0; g < groups; ++g)
+                    if (fd.n_tiles > g) pairs_computed += (fd.n_tiles - g) * 64 * KNN_FOLD_NR;
+            } else {
+                pairs_computed += groups * 64 * fd.n_tiles * KNN_FOLD_NR;
+            }
+            return launch_fold_dist(fd, mode, stream);
+        }
+        DistArgs da;
+        da.Qp = qp + q0 * p.dpad;
+        da.ldq = p.dpad;
+        da.ldr = p.rcopy ? p.dpad : d;
+        da.Rp = (p.rcopy ? rp : R) + r0 * da.ldr;
+        da.cR = cr + r0;
+        da.cQ = cr + q0;                           // read when values are mirrored: queries are rows of the same set
+        da.D = D0;
+        da.Dm = mode == DIST_RECT_MIRROR ? D1 : D0;
+        da.ldd = p.ldd;
+        da.nq = mq;
+        da.nr = mr;
+        da.self_offset = self_off;
+        da.dpad = p.dpad;
+        da.n_rt = (int32_t)((mr + 63) / 64);
+        da.chunk = p.chunk;
+        da.n_chunks = (da.n_rt + p.chunk - 1) / p.chunk;
+        da.n_qtiles = (int32_t)((mq + KNN_TILE - 1) / KNN_TILE);
+        if (mode == DIST_TRIANGLE) {
+            for (int32_t qt = 0; qt < da.n_qtiles; ++qt)
+                if (da.n_rt > 2 * qt) pairs_computed += (int64_t)(da.n_rt - 2 * qt) * KNN_TILE * 64;
+        } else {
+            pairs_computed += (int64_t)da.n_qtiles * KNN_TILE * da.n_rt * 64;
+        }
+        return launch_dist_qreg(da, da.n_qtiles, mode, stream);
+    };
+    auto select = [&](const float *A, int64_t row0, int64_t m, int64_t col0, int64_t ncols, int32_t S, int64_t seg,
+                      bool resume) -> hipError_t {
+        ++launches;
+        SelectArgs sa;
+        sa.A = A;
+        sa.lists = lists + row0 * p.kcap;
+        sa.m = m;
+        sa.n = ncols;
+        sa.lda = p.ldd;
+        sa.seg = seg;
+        sa.k = k;
+        sa.kcap = p.kcap;
+        sa.S = S;
+        sa.vec4 = 1;                               // rows of the matrix start on 256-byte boundaries
+        sa.resume = resume ? 1 : 0;
+        sa.col0 = col0;
+        return launch_select(sa, stream);
+    };
+
+    if (!p.blocked) {
+        e = dist(0, nq, 0, nr, p.msym ? DIST_TRIANGLE : DIST_FULL, self_offset);
+        if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : "knn_dist_qreg", e); return KNN_EDEVICE; }
+        ev.record(4, stream);
+        e = select(D0, 0, nq, 0, nr, p.S, p.sel_seg, false);
+        if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+        return KNN_OK;
+    }
+    // panel pairs; one list per row, continued from block to block (one wave per row: a block's
+    // row segment is at most p.P columns)
+    const int64_t G = (nr + p.P - 1) / p.P;
+    const int64_t seg = (p.P + 1023) / 1024 * 1024;
+    for (int64_t a = 0; a < G; ++a) {
+        const int64_t q0 = a * p.P, mq = nr - q0 < p.P ? nr - q0 : p.P;
+        for (int64_t b = a; b < G; ++b) {
+            const int64_t r0 = b * p.P, mr = nr - r0 < p.P ? nr - r0 : p.P;
+            e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1);
+            if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : "knn_dist_qreg", e); return KNN_EDEVICE; }
+            // rows of panel a were first seen in block (0, a) (mirrored) or, for a = 0, right here
+            e = select(D0, q0, mq, r0, mr, 1, seg, !(a == 0 && b == 0));
+            if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+            if (a != b) {
+                e = select(D1, r0, mr, q0, mq, 1, seg, a != 0);
+                if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
+            }
+        }
+    }
+    return KNN_OK;
+}
+
 knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d, int32_t k,
                  knn_metric_t metric, int64_t self_offset, bool self, int32_t *idx, float *dist,
                  void *workspace, size_t workspace_bytes, void *stream_v, const knn_options_t *opt)
@@ -413,46 +580,10 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     // ---- fused distance + selection ----
     int32_t launches = 1;
     int64_t pairs_computed = p.nq_pad * p.n_cpad;
-    if (p.fold && p.matrix) {
-        FoldDistArgs fd;
-        fd.Qpk = qp;
-        fd.Rpk = rp;
-        fd.D = (float *)(ws + p.off_D);
-        fd.ldd = p.ldd;
-        fd.nq = nq;
-        fd.nr = nr;
-        fd.self_offset = self_offset;
-        fd.n_tiles = p.n_rt64;
-        fd.dpad = p.dpad;
-        fd.metric = (int32_t)metric;
-        fd.chunk = p.chunk;
-        fd.n_chunks = p.n_chunks;
-        fd.n_qblocks = (int32_t)((nq + 255) / 256);
-        e = launch_fold_dist(fd, p.msym, stream);
-        if (e != hipSuccess) { set_error("knn_fold_dist", e); return KNN_EDEVICE; }
-        ev.record(4, stream);
-        SelectArgs sa;
-        sa.A = fd.D;
-        sa.lists = lists;
-        sa.m = nq;
-        sa.n = nr;
-        sa.lda = p.ldd;
-        sa.seg = p.sel_seg;
-        sa.k = k;
-        sa.kcap = p.kcap;
-        sa.S = p.S;
-        sa.vec4 = 1;
-        e = launch_select(sa, stream);
-        if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
-        launches = 2;
-        const int64_t groups = (nq + 63) / 64;
-        if (p.msym) {
-            pairs_computed = 0;
-            for (int64_t g = 0; g < groups; ++g)
-                if (p.n_rt64 > g) pairs_computed += (int64_t)(p.n_rt64 - g) * 64 * KNN_FOLD_NR;
-        } else {
-            pairs_computed = groups * 64 * (int64_t)p.n_rt64 * KNN_FOLD_NR;
-        }
+    if (p.matrix) {
+        st = run_two_phase(p, Q, nq, R, nr, d, k, metric, self_offset, qp, rp, cr, lists, ws, stream, ev,
+                           launches, pairs_computed);
+        if (st != KNN_OK) return st;
     } else if (p.fold) {
         FoldArgs fa;
         fa.Qpk = qp;
@@ -472,48 +603,6 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         e = launch_fold(fa, stream);
         if (e != hipSuccess) { set_error("knn_fold", e); return KNN_EDEVICE; }
         pairs_computed = (nq + 63) / 64 * 64 * p.n_cpad;
-    } else if (p.matrix) {
-        DistArgs da;
-        da.Qp = qp;
-        da.Rp = p.rcopy ? rp : R;
-        da.cR = cr;
-        da.cQ = cr;                                // read in symmetric mode only: queries == references
-        da.D = (float *)(ws + p.off_D);
-        da.ldq = p.dpad;
-        da.ldr = p.rcopy ? p.dpad : d;
-        da.ldd = p.ldd;
-        da.nq = nq;
-        da.nr = nr;
-        da.self_offset = self_offset;
-        da.dpad = p.dpad;
-        da.n_rt = p.n_rt64;
-        da.chunk = p.chunk;
-        da.n_chunks = p.n_chunks;
-        da.n_qtiles = p.n_qtiles;
-        e = launch_dist_qreg(da, p.n_qtiles, p.msym, stream);
-        if (e != hipSuccess) { set_error("knn_dist_qreg", e); return KNN_EDEVICE; }
-        ev.record(4, stream);
-        SelectArgs sa;
-        sa.A = da.D;
-        sa.lists = lists;
-        sa.m = nq;
-        sa.n = nr;
-        sa.lda = p.ldd;
-        sa.seg = p.sel_seg;
-        sa.k = k;
-        sa.kcap = p.kcap;
-        sa.S = p.S;
-        sa.vec4 = 1;                               // rows of the matrix start on 512-byte boundaries
-        e = launch_select(sa, stream);
-        if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
-        launches = 2;
-        if (p.msym) {
-            pairs_computed = 0;
-            for (int32_t qt = 0; qt < p.n_qtiles; ++qt)
-                if (p.n_rt64 > 2 * qt) pairs_computed += (int64_t)(p.n_rt64 - 2 * qt) * KNN_TILE * 64;
-        } else {
-            pairs_computed = p.nq_pad * (int64_t)p.n_rt64 * 64;
-        }
     } else if (p.tri) {
         // one launch for the diagonal blocks, then one per round of disjoint block pairs
         float *cmax = (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
@@ -626,8 +715,8 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pr->main_launches = launches;
         pr->symmetric = (p.tri || p.msym) ? 1 : 0;
         pr->pairs_computed = pairs_computed;
-        pr->two_phase = p.matrix ? 1 : 0;
-        if (p.matrix) (void)hipEventElapsedTime(&pr->ms_select, ev.e[4], ev.e[2]);
+        pr->two_phase = p.matrix ? (p.blocked ? 2 : 1) : 0;
+        if (p.matrix && !p.blocked) (void)hipEventElapsedTime(&pr->ms_select, ev.e[4], ev.e[2]);
     }
     return KNN_OK;
 }
@@ -703,6 +792,8 @@ knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32
     a.kcap = kcap;
     a.S = S;
     a.vec4 = (((uintptr_t)A & 15) == 0 && lda % 4 == 0) ? 1 : 0;
+    a.resume = 0;
+    a.col0 = 0;
     hipError_t e = launch_select(a, stream);
     if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
     FinArgs f;

@@ -65,6 +65,7 @@ struct FoldDistArgs {
     const float *Qpk;  // as FoldArgs
     const float *Rpk;
     float *D;          // [ceil(nq/128)*128, ldd]
+    float *Dm;         // mirrored values: D, or the buffer of the transposed block (see DistArgs)
     int64_t ldd;
     int64_t nq, nr;
     int64_t self_offset;
@@ -83,6 +84,11 @@ struct PackArgs {
     uint32_t *bound;   // optional [n]: set to "no bound yet" (all ones) on the way
 };
 
+// What a Phase-1 kernel covers: all of the block (direct values only); the triangle of a square
+// block from the diagonal on, mirrored into the same buffer; or all of a rectangle of two
+// different row panels, mirrored into the buffer of the transposed block.
+enum { DIST_FULL = 0, DIST_TRIANGLE = 1, DIST_RECT_MIRROR = 2 };
+
 // Phase 1 of the two-phase organisation: the matrix of p(q, j), written out
 struct DistArgs {
     const float *Qp;   // [nq, ldq]
@@ -90,6 +96,8 @@ struct DistArgs {
     const float *cR;   // [>= n_rt * 64], +inf past the end
     const float *cQ;   // [nq] c of the queries (symmetric mode; the same array as cR)
     float *D;          // [ceil(nq/128)*128, ldd]
+    float *Dm;         // where the mirrored values go: D itself (triangle of one square block), or the
+                       // buffer of the transposed block [ceil(nr/128)*128, ldd] (rectangle of two row panels)
     int64_t ldq, ldr, ldd;
     int64_t nq, nr;
     int64_t self_offset;
@@ -137,19 +145,21 @@ struct SelectArgs {
     int64_t m, n, lda;
     int64_t seg;       // columns per segment (multiple of 1024)
     int32_t k, kcap, S, vec4;
+    int32_t resume;    // 0: lists start empty; 1: they hold the result of earlier calls (other column blocks)
+    int64_t col0;      // index of column 0 in the keys
 };
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
-hipError_t launch_fold_dist(const FoldDistArgs &a, bool sym, hipStream_t stream);
+hipError_t launch_fold_dist(const FoldDistArgs &a, int mode, hipStream_t stream);
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
-hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, bool sym, hipStream_t stream);   // dpad: multiple of 32, <= 256
+hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream);
 hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream);

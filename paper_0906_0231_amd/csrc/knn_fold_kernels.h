@@ -153,11 +153,13 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
 }
 
 // ---------------------------------------------------------------------------
-// knn_fold_dist<METRIC, SYM>: the fold of knn_fold with the paper's two phases kept apart
+// knn_fold_dist<METRIC, MODE>: the fold of knn_fold with the paper's two phases kept apart
 // (Sect. 5-6): the distances are written out, select_rows picks the k smallest per row
-// afterwards.  With SYM (knn_build: these distances are symmetric, Sect. 3) a wave computes only
-// the tiles from its own diagonal tile on and stores each value beyond it twice, D[q][j] and
-// D[j][q] -- half the vector instructions, which are what bounds this path.
+// afterwards.  With DIST_TRIANGLE (knn_build: these distances are symmetric, Sect. 3) a wave
+// computes only the tiles from its own diagonal tile on and stores each value beyond it twice,
+// D[q][j] and D[j][q] -- half the vector instructions, which are what bounds this path.
+// DIST_RECT_MIRROR: two different row panels of one data set, every value stored twice, the
+// mirrored one into the buffer of the transposed block (see knn_dist_qreg).
 // Same loop as knn_fold: lane = query, one accumulator per reference of a 64-row tile, reference
 // coordinates through scalar registers.  The waves of a workgroup take consecutive query groups
 // and walk the same tiles together (the scalar cache fetches a line once for all of them); a
@@ -168,7 +170,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
 // ---------------------------------------------------------------------------
 constexpr int FD_PITCH = 20;                       // floats per row of the transposition buffer (16 + pad, 16-byte aligned)
 
-template <int METRIC, bool SYM>
+template <int METRIC, int MODE>
 __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOLD_WAVES) void knn_fold_dist(FoldDistArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_tr[FOLD_WAVES][64 * FD_PITCH];
@@ -184,7 +186,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
 
     // tiles of 64 references; the workgroup's first diagonal tile is that of its first wave
-    const int64_t t_first = SYM ? (int64_t)qb * FOLD_WAVES : 0;
+    constexpr bool TRI = MODE == DIST_TRIANGLE;
+    const int64_t t_first = TRI ? (int64_t)qb * FOLD_WAVES : 0;
     const int64_t t0 = t_first + (int64_t)chunk * a.chunk;
     const int64_t t1 = min(t0 + a.chunk, a.n_tiles);
 
@@ -194,7 +197,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
     float *tr = &s_tr[w][0];
 
     for (int64_t tj = t0; tj < t1; ++tj) {
-        if (SYM && tj < qg) continue;              // below this wave's diagonal: the other wave's mirror writes it
+        if (TRI && tj < qg) continue;              // below this wave's diagonal: the other wave's mirror writes it
         const int64_t j0 = tj * FOLD_NR;
         f32x16 acc[FOLD_NR / 16];                  // register 16 t + r: reference j0 + 16 t + r
 #pragma unroll
@@ -253,10 +256,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
                 }
             }
         }
-        if (SYM && tj > qg) {
+        if (MODE == DIST_RECT_MIRROR || (TRI && tj > qg)) {
             // a row address every lane agrees on plus a 32-bit lane offset (keeps the 64 store
             // addresses from taking two registers each)
-            global_float *mbase = scalar_ptr(a.D + j0 * a.ldd);
+            global_float *mbase = scalar_ptr(a.Dm + j0 * a.ldd);
             const uint32_t voff = (uint32_t)myq;
 #pragma unroll
             for (int t = 0; t < FOLD_NR / 16; ++t)

@@ -131,27 +131,32 @@ hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream)
     return a.bound != nullptr && a.S > 1 ? launch_tiles_qreg_t<true>(a, stream) : launch_tiles_qreg_t<false>(a, stream);
 }
 
-template <bool SYM>
+template <int MODE>
 static hipError_t launch_dist_qreg_t(const DistArgs &a, int n_qtiles, hipStream_t stream)
 {
     dim3 grid((unsigned)((int64_t)n_qtiles * a.n_chunks)), block(256);
     switch (a.dpad) {
-    case 32: hipLaunchKernelGGL((knn_dist_qreg<32, SYM>), grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL((knn_dist_qreg<64, SYM>), grid, block, 0, stream, a); break;
-    case 96: hipLaunchKernelGGL((knn_dist_qreg<96, SYM>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((knn_dist_qreg<128, SYM>), grid, block, 0, stream, a); break;
-    case 160: hipLaunchKernelGGL((knn_dist_qreg<160, SYM>), grid, block, 0, stream, a); break;
-    case 192: hipLaunchKernelGGL((knn_dist_qreg<192, SYM>), grid, block, 0, stream, a); break;
-    case 224: hipLaunchKernelGGL((knn_dist_qreg<224, SYM>), grid, block, 0, stream, a); break;
-    case 256: hipLaunchKernelGGL((knn_dist_qreg<256, SYM>), grid, block, 0, stream, a); break;
+    case 32: hipLaunchKernelGGL((knn_dist_qreg<32, MODE>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_dist_qreg<64, MODE>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_dist_qreg<96, MODE>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_dist_qreg<128, MODE>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_dist_qreg<160, MODE>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_dist_qreg<192, MODE>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_dist_qreg<224, MODE>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((knn_dist_qreg<256, MODE>), grid, block, 0, stream, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, bool sym, hipStream_t stream)
+hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream)
 {
-    return sym ? launch_dist_qreg_t<true>(a, n_qtiles, stream) : launch_dist_qreg_t<false>(a, n_qtiles, stream);
+    switch (mode) {
+    case DIST_FULL: return launch_dist_qreg_t<DIST_FULL>(a, n_qtiles, stream);
+    case DIST_TRIANGLE: return launch_dist_qreg_t<DIST_TRIANGLE>(a, n_qtiles, stream);
+    case DIST_RECT_MIRROR: return launch_dist_qreg_t<DIST_RECT_MIRROR>(a, n_qtiles, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream)
@@ -197,20 +202,24 @@ hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_fold_dist(const FoldDistArgs &a, bool sym, hipStream_t stream)
+template <int METRIC>
+static hipError_t launch_fold_dist_t(const FoldDistArgs &a, int mode, hipStream_t stream)
 {
     dim3 grid((unsigned)((int64_t)a.n_qblocks * a.n_chunks)), block(64 * FOLD_WAVES);
-    if (a.metric == 3 && sym)
-        hipLaunchKernelGGL((knn_fold_dist<3, true>), grid, block, 0, stream, a);
-    else if (a.metric == 3)
-        hipLaunchKernelGGL((knn_fold_dist<3, false>), grid, block, 0, stream, a);
-    else if (a.metric == 4 && sym)
-        hipLaunchKernelGGL((knn_fold_dist<4, true>), grid, block, 0, stream, a);
-    else if (a.metric == 4)
-        hipLaunchKernelGGL((knn_fold_dist<4, false>), grid, block, 0, stream, a);
-    else
-        return hipErrorInvalidValue;
+    switch (mode) {
+    case DIST_FULL: hipLaunchKernelGGL((knn_fold_dist<METRIC, DIST_FULL>), grid, block, 0, stream, a); break;
+    case DIST_TRIANGLE: hipLaunchKernelGGL((knn_fold_dist<METRIC, DIST_TRIANGLE>), grid, block, 0, stream, a); break;
+    case DIST_RECT_MIRROR: hipLaunchKernelGGL((knn_fold_dist<METRIC, DIST_RECT_MIRROR>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
+}
+
+hipError_t launch_fold_dist(const FoldDistArgs &a, int mode, hipStream_t stream)
+{
+    if (a.metric == 3) return launch_fold_dist_t<3>(a, mode, stream);
+    if (a.metric == 4) return launch_fold_dist_t<4>(a, mode, stream);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream)

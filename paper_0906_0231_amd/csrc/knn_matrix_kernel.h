@@ -9,16 +9,19 @@
 namespace knn {
 
 // ---------------------------------------------------------------------------
-// knn_dist_qreg<DPAD, SYM>: Phase 1.  The matrix loop of knn_tiles_qreg (query operands in
+// knn_dist_qreg<DPAD, MODE>: Phase 1.  The matrix loop of knn_tiles_qreg (query operands in
 // registers, 64 reference rows x 32 coordinates per step through LDS); the epilogue stores
 // the tile instead of selecting from it:
 //   D[q][j] = p(q, j) = c_j + sum Q'[q] R'[j]        (the value the fused kernels select on;
 //                                                     finalize_rows adds the query's own term)
-// SYM (knn_build with a symmetric distance, Sect. 3): a workgroup starts its sweep at its own
-// diagonal block and every tile beyond it is stored twice, D[q][j] and, as row j sees the
-// same pair, D[j][q] = (p - c_j) + c_q -- half the matrix products, the zig-zag of Sect. 4
+// DIST_TRIANGLE (knn_build with a symmetric distance, Sect. 3): a workgroup starts its sweep at
+// its own diagonal block and every tile beyond it is stored twice, D[q][j] and, as row j sees
+// the same pair, D[j][q] = (p - c_j) + c_q -- half the matrix products, the zig-zag of Sect. 4
 // being unnecessary here because the sweeps are cut into chunks of equal length.  Stores to
 // distinct elements need no ownership, so one launch covers the triangle.
+// DIST_RECT_MIRROR: queries and references are two different row panels of one data set (a
+// matrix too large to write out whole is walked panel pair by panel pair); every tile is stored
+// twice, the mirrored values into the buffer of the transposed block.
 // The entry of a row with itself is stored as +inf; columns past the end hold +inf (direct)
 // or are never read (mirror).
 // ---------------------------------------------------------------------------
@@ -39,7 +42,7 @@ struct __attribute__((aligned(16))) DistSmem {
     float tr[4][32 * DT_PITCH];                   // per wave: its 32 x 64 tile, query-major
 };
 
-template <int DPAD, bool SYM>
+template <int DPAD, int MODE>
 __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
 {
     constexpr int NK = DPAD / QG_DC;
@@ -59,7 +62,9 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     const int chunk = blockIdx.x / a.n_qtiles;
     const int qt = blockIdx.x - chunk * a.n_qtiles;
     // the diagonal block of query tile qt is reference tiles 2 qt and 2 qt + 1
-    const int first = SYM ? 2 * qt : 0;
+    constexpr bool SYM = MODE != DIST_FULL;       // values are stored twice
+    const int first = MODE == DIST_TRIANGLE ? 2 * qt : 0;
+    const int mirror_from = MODE == DIST_TRIANGLE ? first + 2 : 0;   // first tile that is mirrored
     const int rt0 = first + chunk * a.chunk;
     const int rt1 = min(rt0 + a.chunk, a.n_rt);
     if (rt0 >= rt1) return;                       // whole workgroup
@@ -166,12 +171,12 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                     *(f32x4 *)(drow + (int64_t)(4 * i) * a.ldd) = v;
                 }
             }
-            if (SYM && rt >= first + 2) {
+            if (SYM && rt >= mirror_from) {
                 // beyond the diagonal block: the same pairs as rows j see them; for a fixed
                 // register the 32 lanes of a half hold 32 consecutive queries, 128 bytes of row j
                 // a row address every lane agrees on plus a 32-bit lane offset: keeps the 32 store
                 // addresses from occupying two registers each across the matrix loop
-                global_float *tbase = scalar_ptr(a.D + j0 * a.ldd);
+                global_float *tbase = scalar_ptr(a.Dm + j0 * a.ldd);
                 const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
 #pragma unroll
                 for (int gg = 0; gg < 4; ++gg) {

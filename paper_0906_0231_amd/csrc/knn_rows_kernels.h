@@ -113,13 +113,15 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
     const float *Arow = a.A + row * a.lda;
     u64 *L = &sList[w][0];
     u64 *Q = &sQueue[w][0];
-    for (int i = lane; i < a.kcap; i += 64) L[i] = KEY_INF;
+    // resume: the row's list holds the result of earlier calls over other column blocks
+    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
+    for (int i = lane; i < a.kcap; i += 64) L[i] = a.resume ? out[i] : KEY_INF;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
-    u64 tau_key = KEY_INF;
-    float tau_p = __builtin_inff();
-    int count = 0;                                // queued candidates (wave-uniform)
     const float INF = __builtin_inff();
+    u64 tau_key = a.resume ? L[a.k - 1] : KEY_INF;
+    float tau_p = tau_key == KEY_INF ? INF : ord2f((uint32_t)(tau_key >> 32));
+    int count = 0;                                // queued candidates (wave-uniform)
 
     auto flush = [&]() __attribute__((always_inline)) {
         if (count == 0) return;
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
                 const bool c = p <= tau_p;
                 if (__ballot(c)) {
                     const int64_t col = base + j * 256 + lane * 4 + e;
-                    const u64 key = make_key(p, (int32_t)col);
+                    const u64 key = make_key(p, (int32_t)(col + a.col0));
                     const bool pass = c && key < tau_key && col < c1;
                     u64 bal = __ballot(pass);
                     int np = __popcll(bal);
@@ -172,7 +174,6 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
         if (count >= 32 || tau_key == KEY_INF) flush();
     }
     flush();
-    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
     for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
 }
 

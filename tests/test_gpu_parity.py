@@ -157,7 +157,8 @@ def test_symmetric_equals_full_square():
     (131072, 64, 10, 1, 1024),   # fused, blocks of 128 rows: 512 pairs per round, 1023 rounds + the diagonal
     (150000, 64, 10, 0, 1),      # 586 blocks of 256 rows leave the rounds 57 % full: the fused square is cheaper
     (262144, 64, 10, 1, 1024),   # fused, blocks of 256 rows
-    (262144, 64, 100, 0, 1),     # long lists: the mirror merges make the triangle no cheaper yet
+    (262144, 64, 100, 0, 1),     # long lists: the mirror merges make the triangle no cheaper yet (and at d = 64 stores would bound the two-phase form)
+    (150000, 128, 100, 1, 15),   # beyond 72 GiB of matrix: two-phase by pairs of row panels (3 panels: 6 blocks, 9 selections)
     (20000, 256, 100, 1, 2),     # the shape of the paper's Table 1: matrix written out, each pair once
     (40000, 64, 10, 1, 2),       # small enough for the two-phase form whatever d and k
     (60000, 64, 10, 0, 1),       # d = 64 and not small: the matrix would cost more than it saves
@@ -175,6 +176,35 @@ def test_default_schedule_choice(n, d, k, sym, launches):
     assert res.profile.main_launches == launches
     rows = _sample_rows(n, 64, seed=n % 97)
     _check_rows(X.numpy(), rows, 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+# ---------------------------------------------------------------------------
+# two-phase form walked block by block (pairs of row panels, lists continued from block to block)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,k,metric,panel", [
+    (1500, 40, 10, "sqeuclidean", 256),      # 6 panels, ragged last one (220 rows)
+    (1500, 40, 10, "sqeuclidean", 1024),     # 2 panels
+    (2049, 64, 100, "hellinger", 512),       # long lists; last panel of a single row
+    (777, 37, 5, "cosine", 256),
+    (1300, 24, 33, "l1", 256),               # the fold kernel, same walk
+    (1300, 24, 12, "linf", 512),
+    (600, 130, 128, "l1", 256),
+    (5000, 256, 16, "sqeuclidean", 2048),
+])
+def test_two_phase_by_panel_pairs(n, d, k, metric, panel):
+    _say(f"  two-phase by panel pairs n={n} d={d} k={k} {metric} panel={panel}")
+    gen = workloads.uniform_rows if metric == "hellinger" else workloads.gaussian
+    X = gen(n, d, seed=9000 + n + d)
+    res = knn_build(X.cuda(), k, metric, variant=4, block_rows=panel, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.two_phase == 2 and res.profile.symmetric == 1
+    G = -(-n // ((panel + 255) // 256 * 256))
+    assert res.profile.main_launches == G * (G + 1) // 2 + G * G      # one block per pair, one selection per block and side
+    _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+    whole = knn_build(X.cuda(), k, metric, variant=4, profile=True)
+    torch.cuda.synchronize()
+    assert whole.profile.two_phase == 1
+    assert torch.equal(whole.idx, res.idx) and torch.equal(whole.dist, res.dist)
 
 
 def test_symmetric_exact_ties():

@@ -68,9 +68,17 @@ def test_workspace_of_the_two_phase_form(lib):
     assert ws(40000, 64, 10) >= matrix(40000)
     assert ws(60000, 64, 10) < matrix(60000) // 8
     assert ws(60000, 128, 10) >= matrix(60000)
-    # never by default beyond 72 GiB of matrix
-    assert ws(150000, 256, 100) < 72 * 2**30
-    assert ws(150000, 256, 100, variant=4) >= matrix(150000)
+    # never whole beyond 72 GiB of matrix: pairs of row panels instead (two blocks of 65536^2),
+    # by default for long lists; short lists stay fused there
+    block = 65536 * (65536 + 64) * 4
+    assert 2 * block <= ws(150000, 256, 100) < 2 * block + 2**30
+    assert ws(150000, 256, 100, variant=4) == ws(150000, 256, 100)
+    assert 2 * block <= ws(150000, 256, 10) < 2 * block + 2**30    # ... unless the fused triangle would fill the device badly
+    assert ws(524288, 256, 10) < 2**30
+    assert ws(150000, 64, 10) < 2**30
+    assert 2 * block <= ws(150000, 128, 10, variant=4) < 2 * block + 2**30
+    # a panel size on request (with variant 4) walks even a small matrix block by block
+    assert ws(20000, 256, 100, variant=4, block_rows=1000) < matrix(20000) // 8
     # d > 256 has no two-phase form: the request falls back to the fused kernels
     assert ws(20000, 300, 100, variant=4) == ws(20000, 300, 100) < matrix(20000)
     # queries against a separate reference set: long lists, or a matrix of at most 4 GiB
