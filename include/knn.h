@@ -107,8 +107,7 @@ typedef struct {
                            of distances written to the workspace ([nq, nr] floats, padded to
                            multiples of 128) and the k smallest per row selected from it;
                            knn_build computes each unordered pair once unless symmetric == 2.
-                           Needs d <= 256 on the matrix cores (else as 0); any d for KNN_L1 and
-                           KNN_LINF.  Auto takes it when that matrix is at most 72 GiB,
+                           Any d.  Auto takes it when that matrix is at most 72 GiB,
                            symmetric != 1 and: k > 32; or knn_build (symmetric distance) with
                            d > 96 or n <= 49152 (KNN_L1, KNN_LINF: d >= 64); or the matrix is
                            at most 4 GiB.  A larger matrix is never written out whole: knn_build

@@ -40,6 +40,7 @@ struct Plan {
     bool msym;      // ... computing each unordered pair of rows once
     int32_t n_rt64, chunk, n_chunks; // ... reference tiles of 64 rows, tiles per workgroup, workgroups per query tile
     int64_t sel_seg;                 // ... columns per segment of select_rows
+    bool mstream;                    // ... d > 256: both operands streamed through LDS (knn_dist_stream)
     bool blocked;                    // ... panel pair by panel pair (the whole matrix would not fit)
     int64_t P;                       // ... rows per panel (multiple of 256)
     size_t off_D2;                   // ... blocked: buffer of the transposed block
@@ -137,6 +138,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.off_D = p.off_D2 = 0;
     p.ldd = 0;
     p.blocked = false;
+    p.mstream = false;
     p.P = 0;
     if (p.fold) {
         // lane = query, 64 per wave; the reference range is cut so that the device has
@@ -246,10 +248,10 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     // computing each pair once saves more than the matrix costs to write and read back (below
     // that the stores bound it: 4 n^2 bytes against n^2 d flop); and small problems, which its
     // two-dimensional grid spreads over the device better than one sweep per query tile does.
-    // Needs the register-resident operand layout, i.e. d <= 256.
+    // d <= 256 uses the register-resident operand layout (knn_dist_qreg), larger d the streaming one.
     p.ldd = p.n_cpad + 64;
     const double matrix_bytes = (double)p.nq_pad * (double)p.ldd * sizeof(float);
-    const bool matrix_ok = dpad32 <= KNN_QRES_MAX_D && p.n_cpad < ((int64_t)1 << 28);   // 32-bit element offsets within four rows
+    const bool matrix_ok = p.n_cpad < ((int64_t)1 << 28);   // 32-bit element offsets within four rows
     const bool msym = self && metric != KNN_KL && symmetric != 2;
     p.matrix = false;
     if (variant == 4)
@@ -267,15 +269,17 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                    (p.kcap > 32 || !p.tri || (dpad32 >= 192 && pair_cost_ratio(nr, p.B, p.kcap) > 0.74));
     if (p.matrix) p.matrix = two_phase_layout(p, p.n_cpad, matrix_bytes, msym, variant, block_rows);
     if (p.matrix) {
-        p.dpad = dpad32;
+        p.mstream = dpad32 > KNN_QRES_MAX_D;       // p.dpad stays d rounded up to KNN_DC then
+        if (!p.mstream) p.dpad = dpad32;
         p.qreg = p.qres = p.tri = false;
         p.msym = msym;
-        p.n_rt64 = (int32_t)((nr + 63) / 64);
-        const int64_t tiles = p.blocked ? (p.P / KNN_TILE) * (p.P / 64)
+        const int32_t tr = p.mstream ? KNN_TILE : 64;              // reference rows per tile of the distance kernel
+        p.n_rt64 = (int32_t)((nr + tr - 1) / tr);
+        const int64_t tiles = p.blocked ? (p.P / KNN_TILE) * (p.P / tr)
                                         : (int64_t)p.n_qtiles * p.n_rt64 / (p.msym ? 2 : 1);
         int64_t chunk = (tiles + 1023) / 1024;
-        if (chunk < 4) chunk = 4;
-        if (chunk > 64) chunk = 64;
+        if (chunk < (p.mstream ? 2 : 4)) chunk = p.mstream ? 2 : 4;
+        if (chunk > (p.mstream ? 32 : 64)) chunk = p.mstream ? 32 : 64;
         p.chunk = (int32_t)chunk;
         p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
         int32_t skcap;
@@ -452,17 +456,20 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         da.nr = mr;
         da.self_offset = self_off;
         da.dpad = p.dpad;
-        da.n_rt = (int32_t)((mr + 63) / 64);
+        const int32_t tr = p.mstream ? KNN_TILE : 64;              // reference rows per tile
+        da.n_rt = (int32_t)((mr + tr - 1) / tr);
         da.chunk = p.chunk;
         da.n_chunks = (da.n_rt + p.chunk - 1) / p.chunk;
         da.n_qtiles = (int32_t)((mq + KNN_TILE - 1) / KNN_TILE);
+        const int32_t per_q = KNN_TILE / tr;                       // reference tiles per query tile
         if (mode == DIST_TRIANGLE) {
             for (int32_t qt = 0; qt < da.n_qtiles; ++qt)
-                if (da.n_rt > 2 * qt) pairs_computed += (int64_t)(da.n_rt - 2 * qt) * KNN_TILE * 64;
+                if (da.n_rt > per_q * qt) pairs_computed += (int64_t)(da.n_rt - per_q * qt) * KNN_TILE * tr;
         } else {
-            pairs_computed += (int64_t)da.n_qtiles * KNN_TILE * da.n_rt * 64;
+            pairs_computed += (int64_t)da.n_qtiles * KNN_TILE * da.n_rt * tr;
         }
-        return launch_dist_qreg(da, da.n_qtiles, mode, stream);
+        return p.mstream ? launch_dist_stream(da, da.n_qtiles, mode, stream)
+                         : launch_dist_qreg(da, da.n_qtiles, mode, stream);
     };
     auto select = [&](const float *A, int64_t row0, int64_t m, int64_t col0, int64_t ncols, int32_t S, int64_t seg,
                       bool resume) -> hipError_t {
@@ -485,7 +492,7 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
 
     if (!p.blocked) {
         e = dist(0, nq, 0, nr, p.msym ? DIST_TRIANGLE : DIST_FULL, self_offset);
-        if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : "knn_dist_qreg", e); return KNN_EDEVICE; }
+        if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
         ev.record(4, stream);
         e = select(D0, 0, nq, 0, nr, p.S, p.sel_seg, false);
         if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
@@ -500,7 +507,7 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         for (int64_t b = a; b < G; ++b) {
             const int64_t r0 = b * p.P, mr = nr - r0 < p.P ? nr - r0 : p.P;
             e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1);
-            if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : "knn_dist_qreg", e); return KNN_EDEVICE; }
+            if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
             // rows of panel a were first seen in block (0, a) (mirrored) or, for a = 0, right here
             e = select(D0, q0, mq, r0, mr, 1, seg, !(a == 0 && b == 0));
             if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }

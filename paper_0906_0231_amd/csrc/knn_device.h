@@ -102,7 +102,7 @@ struct DistArgs {
     int64_t nq, nr;
     int64_t self_offset;
     int32_t dpad;
-    int32_t n_rt;      // reference tiles of 64 rows
+    int32_t n_rt;      // reference tiles of 64 rows (knn_dist_stream: of 128 rows)
     int32_t chunk;     // reference tiles per workgroup
     int32_t n_chunks;  // workgroups per query tile (those past the end of their sweep leave at once)
     int32_t n_qtiles;  // query tiles of 128 rows
@@ -159,7 +159,8 @@ hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
-hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*   // dpad: multiple of 32, <= 256
+hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*
+hipError_t launch_dist_stream(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);    // any dpad (multiple of KNN_DC); n_rt, chunk in tiles of 128 rows   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream);
 hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream);

@@ -149,6 +149,18 @@ static hipError_t launch_dist_qreg_t(const DistArgs &a, int n_qtiles, hipStream_
     return hipGetLastError();
 }
 
+hipError_t launch_dist_stream(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream)
+{
+    dim3 grid((unsigned)((int64_t)n_qtiles * a.n_chunks)), block(256);
+    switch (mode) {
+    case DIST_FULL: hipLaunchKernelGGL(knn_dist_stream<DIST_FULL>, grid, block, 0, stream, a); break;
+    case DIST_TRIANGLE: hipLaunchKernelGGL(knn_dist_stream<DIST_TRIANGLE>, grid, block, 0, stream, a); break;
+    case DIST_RECT_MIRROR: hipLaunchKernelGGL(knn_dist_stream<DIST_RECT_MIRROR>, grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream)
 {
     switch (mode) {

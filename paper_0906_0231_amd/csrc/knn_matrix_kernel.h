@@ -197,6 +197,167 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     for (int rt = rt0; rt < rt1; ++rt) for_each_step<NK>(step, rt);
 }
 
+// ---------------------------------------------------------------------------
+// knn_dist_stream<MODE>: Phase 1 for any d -- the matrix loop of knn_tiles (both operands
+// through LDS 16 coordinates at a time, tile 128 x 128, four accumulator blocks per wave), the
+// epilogue a store as in knn_dist_qreg.  The diagonal block of query tile t is reference tile t.
+// The direct part leaves through a per-wave LDS buffer one 32 x 32 block at a time (128-byte
+// row segments); in the mirrored part the 32 lanes of a half hold 32 consecutive queries.
+// ---------------------------------------------------------------------------
+constexpr int DS_PITCH = 36;                      // floats per row of the transposition buffer
+
+struct __attribute__((aligned(16))) DistStreamSmem {
+    float q[2][TQ * LSTR];
+    float r[2][TR * LSTR];
+    float c[2][TR];                               // by tile parity: read again in the epilogue
+    float tr[4][32 * DS_PITCH];
+};
+
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
+{
+    __shared__ DistStreamSmem sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int h = lane >> 5;
+    const int ql = lane & 31;
+    constexpr bool SYM = MODE != DIST_FULL;
+
+    const int chunk = blockIdx.x / a.n_qtiles;    // chunk-major, see knn_dist_qreg
+    const int qt = blockIdx.x - chunk * a.n_qtiles;
+    const int first = MODE == DIST_TRIANGLE ? qt : 0;
+    const int mirror_from = MODE == DIST_TRIANGLE ? first + 1 : 0;
+    const int rt0 = first + chunk * a.chunk;      // a.n_rt, a.chunk: in tiles of 128 reference rows here
+    const int rt1 = min(rt0 + a.chunk, a.n_rt);
+    if (rt0 >= rt1) return;                       // whole workgroup
+    const int nk = a.dpad / DC;
+
+    const int64_t qbase = (int64_t)qt * TQ;
+    const int64_t myq = qbase + 32 * w + ql;
+    const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
+    const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
+
+    const int lcol = (tid % LD_PER_ROW) * 4;
+    const int lrow = tid / LD_PER_ROW;
+    const float *qsrc[NPASS];
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+        int64_t row = min(qbase + lrow + i * ROWS_PER_PASS, a.nq - 1);
+        qsrc[i] = a.Qp + row * a.ldq + lcol;
+    }
+    f32x4 gq[NPASS], gr[NPASS];
+    float gc = 0.f;
+    auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
+            gq[i] = *(const f32x4 *)(qsrc[i] + kc * DC);
+            int64_t row = min((int64_t)rt * TR + lrow + i * ROWS_PER_PASS, a.nr - 1);
+            gr[i] = *(const f32x4 *)(a.Rp + row * a.ldr + lcol + kc * DC);
+        }
+        if (kc == 0 && tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
+    };
+    auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
+            *(f32x4 *)&sm.q[buf][(lrow + i * ROWS_PER_PASS) * LSTR + lcol] = gq[i];
+            *(f32x4 *)&sm.r[buf][(lrow + i * ROWS_PER_PASS) * LSTR + lcol] = gr[i];
+        }
+        if (kc == 0 && tid < TR) sm.c[tb][tid] = gc;
+    };
+
+    f32x16 acc[4];
+    const int total = (rt1 - rt0) * nk;
+    issue(rt0, 0);
+    stash(0, 0, rt0 & 1);
+    __syncthreads();
+
+    int rt = rt0, kc = 0;
+    for (int it = 0; it < total; ++it) {
+        const int buf = it & 1;
+        int nrt = rt, nkc = kc + 1;
+        if (nkc == nk) { nkc = 0; nrt = rt + 1; }
+        const bool more = it + 1 < total;
+        if (more) issue(nrt, nkc);
+
+        if (kc == 0) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
+                    acc[t][4 * g + 0] = cv[0];
+                    acc[t][4 * g + 1] = cv[1];
+                    acc[t][4 * g + 2] = cv[2];
+                    acc[t][4 * g + 3] = cv[3];
+                }
+        }
+        {
+            const float *qp = &sm.q[buf][(32 * w + ql) * LSTR + h * 4];
+            const float *rp = &sm.r[buf][ql * LSTR + h * 4];
+#pragma unroll
+            for (int s = 0; s < NSLAB; ++s) {
+                f32x4 qf = *(const f32x4 *)(qp + s * 8);
+                f32x4 rf[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) rf[t] = *(const f32x4 *)(rp + t * 32 * LSTR + s * 8);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(rf[t][c], qf[c], acc[t], 0, 0, 0);
+            }
+        }
+
+        if (kc == nk - 1) {
+            // register 4 g + e of block t is reference row j0 + 32 t + 8 g + 4 h + e
+            const int64_t j0 = (int64_t)rt * TR;
+            const float INF = __builtin_inff();
+            const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
+                             j0 + TR > a.self_offset + qbase + 32 * w;
+            float *tw = &sm.tr[w][ql * DS_PITCH + 4 * h];
+            const int rr = lane >> 3, cc = (lane & 7) * 4;
+            float *drow = a.D + (qbase + 32 * w + rr) * a.ldd + j0 + cc;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 v = {acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]};
+                    if (own) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (j0 + 32 * t + 8 * g + 4 * h + e == selfj) v[e] = INF;
+                    }
+                    *(f32x4 *)(tw + 8 * g) = v;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 8 * i) * DS_PITCH + cc];
+                    *(f32x4 *)(drow + (int64_t)(8 * i) * a.ldd + 32 * t) = v;
+                }
+            }
+            if (SYM && rt >= mirror_from) {
+                global_float *tbase = scalar_ptr(a.Dm + j0 * a.ldd);
+                const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            (tbase + (int64_t)(32 * t + 8 * g + e) * a.ldd)[voff] = (acc[t][4 * g + e] - cv[e]) + cq;
+                    }
+            }
+        }
+
+        if (more) stash(buf ^ 1, nkc, nrt & 1);
+        __syncthreads();
+        rt = nrt;
+        kc = nkc;
+    }
+}
+
 }  // namespace knn
 
 #endif

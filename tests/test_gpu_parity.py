@@ -190,6 +190,8 @@ def test_default_schedule_choice(n, d, k, sym, launches):
     (1300, 24, 12, "linf", 512),
     (600, 130, 128, "l1", 256),
     (5000, 256, 16, "sqeuclidean", 2048),
+    (1500, 300, 10, "cosine", 512),          # d > 256: the streaming distance kernel, same walk
+    (1100, 1030, 100, "sqeuclidean", 256),
 ])
 def test_two_phase_by_panel_pairs(n, d, k, metric, panel):
     _say(f"  two-phase by panel pairs n={n} d={d} k={k} {metric} panel={panel}")
