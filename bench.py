@@ -146,7 +146,7 @@ def main() -> int:
                    "datagen_s": round(gen_s, 2)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                     "traffic": None, "kernel": "knn_dist_qreg" if two_phase else "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
+                     "traffic": None, "kernel": ("knn_dist_qreg" if d <= 256 else "knn_dist_stream") if two_phase else "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
 
