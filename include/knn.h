@@ -6,8 +6,11 @@
  * vector, the k reference vectors at the smallest distance, listed in
  * non-decreasing order of distance, every reference left out being at least as
  * far as the k-th one listed.  It does so by brute force, as the paper does
- * (Sect. 4-6): a tiled all-pairs distance computation fused with a per-row
- * selection of the k smallest, so that no distance matrix is ever stored.
+ * (Sect. 4-6): a tiled all-pairs distance computation and a per-row selection
+ * of the k smallest -- fused into one pass, so that no distance matrix is ever
+ * stored, or, where that is cheaper on this device, as the paper's two phases
+ * with the matrix (whole up to 72 GiB, else blocks of two row panels) kept in
+ * the caller's workspace between them; see knn_options_t.variant.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller; the library
@@ -171,6 +174,10 @@ knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t n
  * 0 if the sizes are invalid.  `symmetric` != 0 asks
  * for knn_build (nq is ignored, nr = n), 0 for knn_search.  The workspace must be
  * 256-byte aligned; its contents need not be initialised and are garbage after.
+ * Where the default plan writes the distance matrix out this is its size and more
+ * (up to 72 GiB); a caller who cannot spare that asks for variant 3 through
+ * knn_workspace_bytes_ex and the _ex entry points (copies of the inputs and the
+ * lists only: about 4 n d + 8 n kcap bytes).
  */
 size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
                            int32_t symmetric);
