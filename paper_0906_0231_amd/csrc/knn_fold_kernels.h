@@ -188,8 +188,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
     // tiles of 64 references; the workgroup's first diagonal tile is that of its first wave
     constexpr bool TRI = MODE == DIST_TRIANGLE;
     const int64_t t_first = TRI ? (int64_t)qb * FOLD_WAVES : 0;
-    const int64_t t0 = t_first + (int64_t)chunk * a.chunk;
-    const int64_t t1 = min(t0 + a.chunk, a.n_tiles);
+    // chunk boundaries do not depend on the query block (the workgroups of a chunk index walk
+    // the same tiles together); chunks that end below the block's diagonal have nothing to do
+    const int64_t t0 = max((int64_t)chunk * a.chunk, t_first);
+    const int64_t t1 = min((int64_t)chunk * a.chunk + a.chunk, a.n_tiles);
 
     const f32x4 *qp = (const f32x4 *)(a.Qpk + qg * (int64_t)(a.dpad >> 2) * 256) + lane;
     const_f32_ptr Rc = (const_f32_ptr)a.Rpk;       // never written while this kernel runs

@@ -65,8 +65,11 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     constexpr bool SYM = MODE != DIST_FULL;       // values are stored twice
     const int first = MODE == DIST_TRIANGLE ? 2 * qt : 0;
     const int mirror_from = MODE == DIST_TRIANGLE ? first + 2 : 0;   // first tile that is mirrored
-    const int rt0 = first + chunk * a.chunk;
-    const int rt1 = min(rt0 + a.chunk, a.n_rt);
+    // chunk boundaries are the same for every query tile, so the workgroups of one chunk index
+    // walk the same reference tiles at the same time and share them in the L2; the chunk that
+    // holds the diagonal starts there, those below it leave at once
+    const int rt0 = max(chunk * a.chunk, first);
+    const int rt1 = min(chunk * a.chunk + a.chunk, a.n_rt);
     if (rt0 >= rt1) return;                       // whole workgroup
 
     const int64_t qbase = (int64_t)qt * TQ;
@@ -228,8 +231,8 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
     const int qt = blockIdx.x - chunk * a.n_qtiles;
     const int first = MODE == DIST_TRIANGLE ? qt : 0;
     const int mirror_from = MODE == DIST_TRIANGLE ? first + 1 : 0;
-    const int rt0 = first + chunk * a.chunk;      // a.n_rt, a.chunk: in tiles of 128 reference rows here
-    const int rt1 = min(rt0 + a.chunk, a.n_rt);
+    const int rt0 = max(chunk * a.chunk, first);  // a.n_rt, a.chunk: in tiles of 128 reference rows here
+    const int rt1 = min(chunk * a.chunk + a.chunk, a.n_rt);
     if (rt0 >= rt1) return;                       // whole workgroup
     const int nk = a.dpad / DC;
 
