@@ -44,6 +44,8 @@ struct Plan {
     bool blocked;                    // ... panel pair by panel pair (the whole matrix would not fit)
     int64_t P;                       // ... rows per panel (multiple of 256)
     size_t off_D2;                   // ... blocked: buffer of the transposed block
+    int64_t ldm;                     // ... chunk minima (knn_dist_qreg only): row pitch in floats, 0 = none
+    size_t off_M, off_M2;            // ... [rows of D, ldm] for D and for the transposed block
     size_t off_D;                    // ... the matrix, [nq_pad, ldd]; blocked: one block, [P, ldd]
     int64_t ldd;                     // ... its row pitch in floats: n_cpad + 64, an odd multiple of 256 bytes, so that
                                      //     a column of the matrix does not fall into one memory channel
@@ -136,6 +138,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.n_rt64 = p.chunk = p.n_chunks = 0;
     p.sel_seg = 0;
     p.off_D = p.off_D2 = 0;
+    p.off_M = p.off_M2 = 0;
+    p.ldm = 0;
     p.ldd = 0;
     p.blocked = false;
     p.mstream = false;
@@ -302,6 +306,14 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldd * sizeof(float), 256);
         p.off_D2 = o;
         if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
+        if (!p.mstream) {
+            // minimum of every chunk of 32 columns, so that select_rows can skip most of a row
+            p.ldm = (p.ldd / 32 + 3) / 4 * 4;
+            p.off_M = o;
+            o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldm * sizeof(float), 256);
+            p.off_M2 = o;
+            if (p.blocked) o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
+        }
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
         p.total = o;
@@ -410,6 +422,8 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
     (void)Q;
     float *D0 = (float *)(ws + p.off_D);
     float *D1 = (float *)(ws + p.off_D2);
+    float *M0 = p.ldm ? (float *)(ws + p.off_M) : nullptr;
+    float *M1 = p.ldm ? (float *)(ws + p.off_M2) : nullptr;
     launches = 0;
     pairs_computed = 0;
     hipError_t e;
@@ -451,6 +465,9 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         da.cQ = cr + q0;                           // read when values are mirrored: queries are rows of the same set
         da.D = D0;
         da.Dm = mode == DIST_RECT_MIRROR ? D1 : D0;
+        da.M = M0;
+        da.Mm = mode == DIST_RECT_MIRROR ? M1 : M0;
+        da.ldm = p.ldm;
         da.ldd = p.ldd;
         da.nq = mq;
         da.nr = mr;
@@ -487,6 +504,8 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         sa.vec4 = 1;                               // rows of the matrix start on 256-byte boundaries
         sa.resume = resume ? 1 : 0;
         sa.col0 = col0;
+        sa.M = A == D0 ? M0 : M1;
+        sa.ldm = p.ldm;
         return launch_select(sa, stream);
     };
 
@@ -801,6 +820,8 @@ knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32
     a.vec4 = (((uintptr_t)A & 15) == 0 && lda % 4 == 0) ? 1 : 0;
     a.resume = 0;
     a.col0 = 0;
+    a.M = nullptr;
+    a.ldm = 0;
     hipError_t e = launch_select(a, stream);
     if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
     FinArgs f;

@@ -98,7 +98,10 @@ struct DistArgs {
     float *D;          // [ceil(nq/128)*128, ldd]
     float *Dm;         // where the mirrored values go: D itself (triangle of one square block), or the
                        // buffer of the transposed block [ceil(nr/128)*128, ldd] (rectangle of two row panels)
-    int64_t ldq, ldr, ldd;
+    float *M;          // per row and chunk of 32 columns the smallest value stored in D, [rows of D, ldm], or
+                       // null (knn_dist_qreg only): lets select_rows skip the chunks that cannot matter
+    float *Mm;         // the same for the mirrored values (rows of Dm)
+    int64_t ldq, ldr, ldd, ldm;
     int64_t nq, nr;
     int64_t self_offset;
     int32_t dpad;
@@ -147,6 +150,8 @@ struct SelectArgs {
     int32_t k, kcap, S, vec4;
     int32_t resume;    // 0: lists start empty; 1: they hold the result of earlier calls (other column blocks)
     int64_t col0;      // index of column 0 in the keys
+    const float *M;    // [m, ldm] smallest value of every chunk of 32 columns, or null (every column is read)
+    int64_t ldm;
 };
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);

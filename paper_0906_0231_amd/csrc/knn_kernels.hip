@@ -246,7 +246,10 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t stream)
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
 {
     int64_t blocks = (a.m * a.S + 3) / 4;
-    hipLaunchKernelGGL(select_rows, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    if (a.M != nullptr)
+        hipLaunchKernelGGL(select_rows_sparse, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL(select_rows, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

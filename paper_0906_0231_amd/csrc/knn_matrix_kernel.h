@@ -36,6 +36,8 @@ __device__ __forceinline__ global_float *scalar_ptr(float *p)
 }
 
 constexpr int DT_PITCH = QG_TR + 4;               // floats per row of a wave's transposition buffer
+constexpr int DM_PITCH = 34;                      // the same buffer as 64 rows of 32 (+2) for the mirrored minima
+static_assert(64 * DM_PITCH <= 32 * DT_PITCH, "the mirrored tile must fit the transposition buffer");
 struct __attribute__((aligned(16))) DistSmem {
     float r[2][QG_RBUF];
     float c[2][QG_TR];                            // by tile parity: read again in the epilogue
@@ -76,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     const int64_t myq = qbase + 32 * w + ql;      // < nq_pad: D has that many rows
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
     const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
+    const bool qin = myq < a.nq;
 
     f32x4 qreg[NS];
     {
@@ -148,6 +151,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
             // consecutive columns of ITS row, so storing from there would write 32 bytes per row
             // and instruction; read back row-wise, 16 lanes cover the 256 bytes of a row.
             float *tw = &sm.tr[w][ql * DT_PITCH + 4 * h];
+            float dmin0 = INF, dmin1 = INF;
             // does the tile hold the entry of one of this wave's queries with itself?
             const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
                              j0 + QG_TR > a.self_offset + qbase + 32 * w;
@@ -164,6 +168,14 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 }
                 *(f32x4 *)(tw + 8 * gg) = v0;
                 *(f32x4 *)(tw + 32 + 8 * gg) = v1;
+                dmin0 = fminf(dmin0, fminf(fminf(v0[0], v0[1]), fminf(v0[2], v0[3])));
+                dmin1 = fminf(dmin1, fminf(fminf(v1[0], v1[1]), fminf(v1[2], v1[3])));
+            }
+            if (a.M != nullptr) {
+                // chunk 2 rt is block 0, chunk 2 rt + 1 block 1; a row's 32 columns of a block sit in
+                // its two lanes (halves): the first half writes the one, the second the other
+                const float o0 = __shfl_xor(dmin0, 32, 64), o1 = __shfl_xor(dmin1, 32, 64);
+                a.M[myq * a.ldm + 2 * rt + h] = h == 0 ? fminf(dmin0, o0) : fminf(dmin1, o1);
             }
             {
                 const int rr = lane >> 4, cc = (lane & 15) * 4;
@@ -181,15 +193,40 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 // addresses from occupying two registers each across the matrix loop
                 global_float *tbase = scalar_ptr(a.Dm + j0 * a.ldd);
                 const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
+                // The minima of the mirrored values: a chunk of row j's columns is this wave's 32
+                // queries, i.e. one value per lane of a half -- a reduction across lanes for each
+                // of the 32 register pairs.  Cheaper through the wave's LDS buffer: the values go in
+                // row-major (row = reference j of the tile, column = query), lane j reads its row
+                // back and keeps the minimum in its own registers.  Columns past the end of the
+                // set must not lower a minimum: they go in as +inf.
+                const bool want_min = a.Mm != nullptr;
+                float *tm = &sm.tr[w][(4 * h) * DM_PITCH + ql];
 #pragma unroll
                 for (int gg = 0; gg < 4; ++gg) {
                     f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
                     f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = (acc0[4 * gg + e] - c0[e]) + cq;
-                        (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = (acc1[4 * gg + e] - c1[e]) + cq;
+                        const float m0 = (acc0[4 * gg + e] - c0[e]) + cq;
+                        const float m1 = (acc1[4 * gg + e] - c1[e]) + cq;
+                        (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
+                        (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
+                        if (want_min) {
+                            tm[(8 * gg + e) * DM_PITCH] = qin ? m0 : INF;
+                            tm[(32 + 8 * gg + e) * DM_PITCH] = qin ? m1 : INF;
+                        }
                     }
+                }
+                if (want_min) {
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    const float *tr_row = &sm.tr[w][lane * DM_PITCH];
+                    float m = INF;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        f32x2 v = *(const f32x2 *)(tr_row + 2 * i);
+                        m = fminf(m, fminf(v[0], v[1]));
+                    }
+                    a.Mm[(j0 + lane) * a.ldm + (qbase >> 5) + w] = m;
                 }
             }
         }

@@ -178,6 +178,136 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// select_rows_sparse: select_rows for a matrix that comes with the minimum of every chunk of 32
+// columns (written by the distance kernel on the way).  One wave per (row, column segment):
+//   1. the k-th smallest of the row's chunk minima bounds the k-th smallest value from above
+//      (k chunks hold at least one value each that is no larger), so
+//   2. only chunks whose minimum is within the bound (and within the list's own threshold as
+//      it tightens) are read, eight chunks per wave load; for k << n / 32 that is a small part
+//      of the row, and the kernel reads n / 8 + a few k * 128 bytes per row instead of 4 n.
+// Same list, queue and merge as select_rows; ties, `resume` and `col0` likewise.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
+{
+    __shared__ u64 sList[4][KNN_MAX_KCAP];
+    __shared__ u64 sBound[4][KNN_MAX_KCAP];       // step 1: the k smallest chunk minima
+    __shared__ u64 sQueue[4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t gw = (int64_t)blockIdx.x * 4 + w;
+    if (gw >= a.m * a.S) return;                  // whole wave; no barriers in this kernel
+    const int64_t row = gw / a.S;
+    const int seg = (int)(gw - row * a.S);
+    const int64_t c0 = (int64_t)seg * a.seg;      // multiple of 1024
+    const int64_t c1 = min(c0 + a.seg, a.n);
+    const float *Arow = a.A + row * a.lda;
+    const float *Mrow = a.M + row * a.ldm;
+    const int64_t ch0 = c0 >> 5, ch1 = (c1 + 31) >> 5;
+    u64 *L = &sList[w][0];
+    u64 *Q = &sQueue[w][0];
+    const float INF = __builtin_inff();
+    int count = 0;                                // queued candidates (wave-uniform)
+
+    // ---- step 1: bound = k-th smallest chunk minimum (none if the segment has fewer than k chunks)
+    float bound = INF;
+    if (ch1 - ch0 >= a.k) {
+        u64 *B = &sBound[w][0];
+        for (int i = lane; i < a.kcap; i += 64) B[i] = KEY_INF;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        u64 bkey = KEY_INF;
+        float bp = INF;
+        for (int64_t base = ch0; base < ch1; base += 64) {
+            const int64_t ch = base + lane;
+            const float p = ch < ch1 ? Mrow[ch] : INF;
+            const u64 key = make_key(p, (int32_t)(ch - ch0));
+            const bool pass = ch < ch1 && p <= bp && key < bkey;
+            const u64 bal = __ballot(pass);
+            const int np = __popcll(bal);
+            if (np) {
+                const int pos = __popcll(bal & ((1ull << lane) - 1ull));
+                if (pass) Q[pos] = key;
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                bkey = merge_one(B, a.kcap, a.k, Q, np, lane);
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                bp = bkey == KEY_INF ? INF : ord2f((uint32_t)(bkey >> 32));
+            }
+        }
+        bound = bp;
+    }
+
+    // ---- step 2: the chunks within the bound
+    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
+    for (int i = lane; i < a.kcap; i += 64) L[i] = a.resume ? out[i] : KEY_INF;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    u64 tau_key = a.resume ? L[a.k - 1] : KEY_INF;
+    float tau_p = tau_key == KEY_INF ? bound : fminf(bound, ord2f((uint32_t)(tau_key >> 32)));
+
+    auto flush = [&]() __attribute__((always_inline)) {
+        if (count == 0) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        u64 nt = merge_one(L, a.kcap, a.k, Q, count, lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        tau_key = nt;
+        tau_p = nt == KEY_INF ? bound : fminf(bound, ord2f((uint32_t)(nt >> 32)));
+        count = 0;
+    };
+
+    const int sub = lane >> 3;                    // which of the 8 chunks of a wave load
+    const int part = (lane & 7) * 4;              // which 4 of its 32 columns
+    for (int64_t base = ch0; base < ch1; base += 64) {
+        const int64_t mych = base + lane;
+        const float mc = mych < ch1 ? Mrow[mych] : INF;
+        u64 todo = __ballot(mych < ch1 && mc <= tau_p);
+        while (todo) {
+            // the next (up to) 8 marked chunks, one per group of 8 lanes
+            int pick = -1;
+            u64 rest = todo;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int b = rest ? __builtin_ctzll(rest) : -1;
+                if (rest) rest &= rest - 1;
+                if (sub == i) pick = b;
+            }
+            todo = rest;
+            // the threshold may have tightened since the chunk was marked
+            const float pm = __shfl(mc, pick < 0 ? 0 : pick, 64);
+            const bool live = pick >= 0 && pm <= tau_p;
+            const int64_t col = ((base + (pick < 0 ? 0 : pick)) << 5) + part;
+            f32x4 v = {INF, INF, INF, INF};
+            if (live) {
+                if (a.vec4 && col + 3 < c1) {
+                    v = *(const f32x4 *)(Arow + col);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = col + e < c1 ? Arow[col + e] : INF;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p = v[e];
+                const bool c = live && p <= tau_p;
+                if (__ballot(c)) {
+                    const u64 key = make_key(p, (int32_t)(col + e + a.col0));
+                    const bool pass = c && key < tau_key && col + e < c1;
+                    u64 bal = __ballot(pass);
+                    int np = __popcll(bal);
+                    if (np) {
+                        if (count + np > 64) flush();     // entries already chosen stay valid candidates
+                        int pos = count + __popcll(bal & ((1ull << lane) - 1ull));
+                        if (pass) Q[pos] = key;
+                        count += np;
+                    }
+                }
+            }
+            // (while the list is short of k the bound does the filtering; no need to merge eagerly)
+            if (count >= 32 || (tau_key == KEY_INF && bound == INF)) flush();
+        }
+    }
+    flush();
+    for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
+}
+
+// ---------------------------------------------------------------------------
 // finalize_rows: one wave per query.
 // ---------------------------------------------------------------------------
 

@@ -71,12 +71,12 @@ def test_workspace_of_the_two_phase_form(lib):
     # never whole beyond 72 GiB of matrix: pairs of row panels instead (two blocks of 65536^2),
     # by default for long lists; short lists stay fused there
     block = 65536 * (65536 + 64) * 4
-    assert 2 * block <= ws(150000, 256, 100) < 2 * block + 2**30
+    assert 2 * block <= ws(150000, 256, 100) < 2 * block + 2**31
     assert ws(150000, 256, 100, variant=4) == ws(150000, 256, 100)
-    assert 2 * block <= ws(150000, 256, 10) < 2 * block + 2**30    # ... unless the fused triangle would fill the device badly
+    assert 2 * block <= ws(150000, 256, 10) < 2 * block + 2**31    # ... unless the fused triangle would fill the device badly
     assert ws(524288, 256, 10) < 2**30
     assert ws(150000, 64, 10) < 2**30
-    assert 2 * block <= ws(150000, 128, 10, variant=4) < 2 * block + 2**30
+    assert 2 * block <= ws(150000, 128, 10, variant=4) < 2 * block + 2**31
     # a panel size on request (with variant 4) walks even a small matrix block by block
     assert ws(20000, 256, 100, variant=4, block_rows=1000) < matrix(20000) // 8
     # any d: beyond 256 the distance kernel streams both operands
