@@ -199,6 +199,11 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                 o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldd * sizeof(float), 256);
                 p.off_D2 = o;
                 if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
+                p.ldm = (p.ldd / 32 + 15) / 16 * 16;  // minimum of every chunk of 32 columns, for select_rows_sparse
+                p.off_M = o;
+                o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldm * sizeof(float), 256);
+                p.off_M2 = o;
+                if (p.blocked) o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
                 p.off_lists = o;
                 o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
                 p.total = o;
@@ -308,7 +313,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
         if (!p.mstream) {
             // minimum of every chunk of 32 columns, so that select_rows can skip most of a row
-            p.ldm = (p.ldd / 32 + 3) / 4 * 4;
+            p.ldm = (p.ldd / 32 + 15) / 16 * 16;
             p.off_M = o;
             o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldm * sizeof(float), 256);
             p.off_M2 = o;
@@ -437,6 +442,9 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
             fd.Rpk = rp + r0 * p.dpad;
             fd.D = D0;
             fd.Dm = mode == DIST_RECT_MIRROR ? D1 : D0;
+            fd.M = M0;
+            fd.Mm = mode == DIST_RECT_MIRROR ? M1 : M0;
+            fd.ldm = p.ldm;
             fd.ldd = p.ldd;
             fd.nq = mq;
             fd.nr = mr;

@@ -66,6 +66,8 @@ struct FoldDistArgs {
     const float *Rpk;
     float *D;          // [ceil(nq/128)*128, ldd]
     float *Dm;         // mirrored values: D, or the buffer of the transposed block (see DistArgs)
+    float *M, *Mm;     // chunk minima of D and of the mirrored values (see DistArgs), or null
+    int64_t ldm;
     int64_t ldd;
     int64_t nq, nr;
     int64_t self_offset;

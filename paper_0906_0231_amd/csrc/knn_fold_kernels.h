@@ -169,11 +169,15 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
 // through a per-wave LDS buffer 16 columns at a time and leaves as 64-byte row segments.
 // ---------------------------------------------------------------------------
 constexpr int FD_PITCH = 20;                       // floats per row of the transposition buffer (16 + pad, 16-byte aligned)
+constexpr int FB_PITCH = 20;                       // 16 chunk minima per row (+ pad, 16-byte aligned)
+constexpr int FM_PITCH = 66;                       // the same buffer as 16 rows of 64 (+2) for the mirrored minima
+static_assert(16 * FM_PITCH <= 64 * FD_PITCH, "the mirrored rows must fit the transposition buffer");
 
 template <int METRIC, int MODE>
 __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOLD_WAVES) void knn_fold_dist(FoldDistArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_tr[FOLD_WAVES][64 * FD_PITCH];
+    __shared__ __attribute__((aligned(16))) float s_min[FOLD_WAVES][64 * FB_PITCH];   // chunk minima of 8 tiles per row
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     // chunk-major numbering, as in knn_dist_qreg: the 8 XCDs get equal shares of every chunk index
@@ -240,6 +244,38 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
                 for (int r = 0; r < 16; ++r)
                     if (j0 + 16 * t + r == selfj) acc[t][r] = __builtin_inff();
         }
+        // minimum of each chunk of 32 columns (for select_rows_sparse); references past the end
+        // of the set are zero rows in the packed copy and must not count
+        if (a.M != nullptr) {
+            const bool ragged = j0 + FOLD_NR > a.nr;
+            float m0 = __builtin_inff(), m1 = __builtin_inff();
+#pragma unroll
+            for (int t = 0; t < FOLD_NR / 16; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = (ragged && j0 + 16 * t + r >= a.nr) ? __builtin_inff() : acc[t][r];
+                    if (t < FOLD_NR / 32) m0 = fminf(m0, v);
+                    else m1 = fminf(m1, v);
+                }
+            // Written 4 bytes at a time these would leave every 64-byte segment of the row half
+            // filled for many tiles, and the L2 cannot hold that many open lines: it evicts them
+            // partly written, which costs the memory a read-modify-write each (measured: 2.3 of
+            // 16.3 ms).  So the wave collects 8 tiles (16 chunks, 64 bytes per row) in LDS first.
+            float *slot = &s_min[w][lane * FB_PITCH + 2 * (int)(tj & 7)];
+            slot[0] = m0;
+            slot[1] = m1;
+            if ((tj & 7) == 7 || tj + 1 == t1) {
+                const int first_t = (int)max(tj & ~(int64_t)7, max(t0, TRI ? qg : (int64_t)0));
+                float *mrow = a.M + myq * a.ldm + 2 * (tj & ~(int64_t)7);
+                const float *src = &s_min[w][lane * FB_PITCH];
+                if ((first_t & 7) == 0 && (tj & 7) == 7) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) *(f32x4 *)(mrow + 4 * i) = *(const f32x4 *)(src + 4 * i);
+                } else {
+                    for (int c = 2 * (first_t & 7); c <= 2 * (int)(tj & 7) + 1; ++c) mrow[c] = src[c];
+                }
+            }
+        }
         // direct part: 16 columns at a time through the wave's LDS buffer
         {
             const int rr = lane >> 2, cc = (lane & 3) * 4;
@@ -261,12 +297,40 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
         if (MODE == DIST_RECT_MIRROR || (TRI && tj > qg)) {
             // a row address every lane agrees on plus a 32-bit lane offset (keeps the 64 store
             // addresses from taking two registers each)
-            global_float *mbase = scalar_ptr(a.Dm + j0 * a.ldd);
+            // (the address walks from row to row: 64 independent row addresses would be computed
+            // ahead and spill the scalar registers that hold the reference operands)
+            global_float *mrow = scalar_ptr(a.Dm + j0 * a.ldd);
             const uint32_t voff = (uint32_t)myq;
 #pragma unroll
             for (int t = 0; t < FOLD_NR / 16; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) (mbase + (int64_t)(16 * t + r) * a.ldd)[voff] = acc[t][r];
+                for (int r = 0; r < 16; ++r) {
+                    mrow[voff] = acc[t][r];
+                    mrow += a.ldd;
+                }
+            // minima of the mirrored values: a chunk of row j's columns is one half of this wave's
+            // queries.  16 rows at a time through the LDS buffer (row = reference, column = query);
+            // lane 2 r + c reads chunk c of row r back and keeps the minimum.  Queries past the end
+            // of the set go in as +inf.
+            if (a.Mm != nullptr) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                const bool qin = myq < a.nq;
+#pragma unroll
+                for (int t = 0; t < FOLD_NR / 16; ++t) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) tr[r * FM_PITCH + lane] = qin ? acc[t][r] : __builtin_inff();
+                    if (lane < 32) {
+                        const float *src = tr + (lane >> 1) * FM_PITCH + 32 * (lane & 1);
+                        float m = __builtin_inff();
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            f32x2 v = *(const f32x2 *)(src + 2 * i);
+                            m = fminf(m, fminf(v[0], v[1]));
+                        }
+                        a.Mm[(j0 + 16 * t + (lane >> 1)) * a.ldm + (q0 >> 5) + (lane & 1)] = m;
+                    }
+                }
+            }
         }
     }
 }

@@ -36,12 +36,14 @@ __device__ __forceinline__ global_float *scalar_ptr(float *p)
 }
 
 constexpr int DT_PITCH = QG_TR + 4;               // floats per row of a wave's transposition buffer
+constexpr int DB_PITCH = 20;                      // 16 chunk minima per row (+ pad, 16-byte aligned)
 constexpr int DM_PITCH = 34;                      // the same buffer as 64 rows of 32 (+2) for the mirrored minima
 static_assert(64 * DM_PITCH <= 32 * DT_PITCH, "the mirrored tile must fit the transposition buffer");
 struct __attribute__((aligned(16))) DistSmem {
     float r[2][QG_RBUF];
     float c[2][QG_TR];                            // by tile parity: read again in the epilogue
     float tr[4][32 * DT_PITCH];                   // per wave: its 32 x 64 tile, query-major
+    float mn[4][32 * DB_PITCH];                   // per wave: the chunk minima of 8 tiles for its 32 rows
 };
 
 template <int DPAD, int MODE>
@@ -175,7 +177,22 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 // chunk 2 rt is block 0, chunk 2 rt + 1 block 1; a row's 32 columns of a block sit in
                 // its two lanes (halves): the first half writes the one, the second the other
                 const float o0 = __shfl_xor(dmin0, 32, 64), o1 = __shfl_xor(dmin1, 32, 64);
-                a.M[myq * a.ldm + 2 * rt + h] = h == 0 ? fminf(dmin0, o0) : fminf(dmin1, o1);
+                // collected in LDS for 8 tiles (16 chunks = 64 bytes of the row) before they go
+                // out: written 4 bytes at a time the half-filled lines outnumber what the L2 can
+                // keep open, and every one evicted early costs the memory a read-modify-write
+                sm.mn[w][ql * DB_PITCH + 2 * (rt & 7) + h] = h == 0 ? fminf(dmin0, o0) : fminf(dmin1, o1);
+                if ((rt & 7) == 7 || rt + 1 == rt1) {
+                    const int first_t = max(rt & ~7, rt0);
+                    const int rowl = lane >> 1, part = (lane & 1) * 8;      // 32 rows x two halves of 8 chunks
+                    float *mrow = a.M + (qbase + 32 * w + rowl) * a.ldm + 2 * (rt & ~7);
+                    const float *src = &sm.mn[w][rowl * DB_PITCH];
+                    if ((first_t & 7) == 0 && (rt & 7) == 7) {
+                        *(f32x4 *)(mrow + part) = *(const f32x4 *)(src + part);
+                        *(f32x4 *)(mrow + part + 4) = *(const f32x4 *)(src + part + 4);
+                    } else {
+                        for (int c = max(2 * (first_t & 7), part); c <= min(2 * (rt & 7) + 1, part + 7); ++c) mrow[c] = src[c];
+                    }
+                }
             }
             {
                 const int rr = lane >> 4, cc = (lane & 15) * 4;
