@@ -44,7 +44,7 @@ struct Plan {
     bool blocked;                    // ... panel pair by panel pair (the whole matrix would not fit)
     int64_t P;                       // ... rows per panel (multiple of 256)
     size_t off_D2;                   // ... blocked: buffer of the transposed block
-    int64_t ldm;                     // ... chunk minima (knn_dist_qreg only): row pitch in floats, 0 = none
+    int64_t ldm;                     // ... chunk minima: row pitch in floats, 0 = none
     size_t off_M, off_M2;            // ... [rows of D, ldm] for D and for the transposed block
     size_t off_D;                    // ... the matrix, [nq_pad, ldd]; blocked: one block, [P, ldd]
     int64_t ldd;                     // ... its row pitch in floats: n_cpad + 64, an odd multiple of 256 bytes, so that
@@ -311,7 +311,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldd * sizeof(float), 256);
         p.off_D2 = o;
         if (p.blocked) o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
-        if (!p.mstream) {
+        {
             // minimum of every chunk of 32 columns, so that select_rows can skip most of a row
             p.ldm = (p.ldd / 32 + 15) / 16 * 16;
             p.off_M = o;

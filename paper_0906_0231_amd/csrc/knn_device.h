@@ -101,7 +101,7 @@ struct DistArgs {
     float *Dm;         // where the mirrored values go: D itself (triangle of one square block), or the
                        // buffer of the transposed block [ceil(nr/128)*128, ldd] (rectangle of two row panels)
     float *M;          // per row and chunk of 32 columns the smallest value stored in D, [rows of D, ldm], or
-                       // null (knn_dist_qreg only): lets select_rows skip the chunks that cannot matter
+                       // null: lets select_rows skip the chunks that cannot matter
     float *Mm;         // the same for the mirrored values (rows of Dm)
     int64_t ldq, ldr, ldd, ldm;
     int64_t nq, nr;

@@ -268,7 +268,9 @@ struct __attribute__((aligned(16))) DistStreamSmem {
     float r[2][TR * LSTR];
     float c[2][TR];                               // by tile parity: read again in the epilogue
     float tr[4][32 * DS_PITCH];
+    float mn[4][32 * DB_PITCH];                   // per wave: the chunk minima of 4 tiles for its 32 rows
 };
+static_assert(32 * DM_PITCH <= 32 * DS_PITCH, "a mirrored block must fit the transposition buffer");
 
 template <int MODE>
 __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
@@ -294,6 +296,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
     const int64_t myq = qbase + 32 * w + ql;
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
     const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
+    const bool qin = myq < a.nq;
 
     const int lcol = (tid % LD_PER_ROW) * 4;
     const int lrow = tid / LD_PER_ROW;
@@ -373,6 +376,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
             const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
                              j0 + TR > a.self_offset + qbase + 32 * w;
             float *tw = &sm.tr[w][ql * DS_PITCH + 4 * h];
+            float dmin = INF;
             const int rr = lane >> 3, cc = (lane & 7) * 4;
             float *drow = a.D + (qbase + 32 * w + rr) * a.ldd + j0 + cc;
 #pragma unroll
@@ -386,25 +390,64 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
                             if (j0 + 32 * t + 8 * g + 4 * h + e == selfj) v[e] = INF;
                     }
                     *(f32x4 *)(tw + 8 * g) = v;
+                    dmin = fminf(dmin, fminf(fminf(v[0], v[1]), fminf(v[2], v[3])));
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 8 * i) * DS_PITCH + cc];
                     *(f32x4 *)(drow + (int64_t)(8 * i) * a.ldd + 32 * t) = v;
                 }
+                // chunk 4 rt + t is block t; its 32 columns sit in the row's two lanes.  Collected
+                // in LDS for 4 tiles (16 chunks, 64 bytes of the row), see knn_dist_qreg
+                if (a.M != nullptr) {
+                    dmin = fminf(dmin, __shfl_xor(dmin, 32, 64));
+                    if (h == 0) sm.mn[w][ql * DB_PITCH + 4 * (rt & 3) + t] = dmin;
+                    dmin = INF;
+                }
+            }
+            if (a.M != nullptr && ((rt & 3) == 3 || rt + 1 == rt1)) {
+                const int first_t = max(rt & ~3, rt0);
+                const int rowl = lane >> 1, part = (lane & 1) * 8;
+                float *mrow = a.M + (qbase + 32 * w + rowl) * a.ldm + 4 * (rt & ~3);
+                const float *src = &sm.mn[w][rowl * DB_PITCH];
+                if ((first_t & 3) == 0 && (rt & 3) == 3) {
+                    *(f32x4 *)(mrow + part) = *(const f32x4 *)(src + part);
+                    *(f32x4 *)(mrow + part + 4) = *(const f32x4 *)(src + part + 4);
+                } else {
+                    for (int c = max(4 * (first_t & 3), part); c <= min(4 * (rt & 3) + 3, part + 7); ++c) mrow[c] = src[c];
+                }
             }
             if (SYM && rt >= mirror_from) {
                 global_float *tbase = scalar_ptr(a.Dm + j0 * a.ldd);
                 const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
+                // minima of the mirrored values: one block of 32 reference rows at a time through
+                // the wave's LDS buffer (row = reference, column = query), lane r reads row r back
+                const bool want_min = a.Mm != nullptr;
+                float *tm = &sm.tr[w][(4 * h) * DM_PITCH + ql];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < 4; ++t) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            (tbase + (int64_t)(32 * t + 8 * g + e) * a.ldd)[voff] = (acc[t][4 * g + e] - cv[e]) + cq;
+                        for (int e = 0; e < 4; ++e) {
+                            const float m = (acc[t][4 * g + e] - cv[e]) + cq;
+                            (tbase + (int64_t)(32 * t + 8 * g + e) * a.ldd)[voff] = m;
+                            if (want_min) tm[(8 * g + e) * DM_PITCH] = qin ? m : INF;
+                        }
                     }
+                    if (want_min && lane < 32) {
+                        typedef float f32x2 __attribute__((ext_vector_type(2)));
+                        const float *tr_row = &sm.tr[w][lane * DM_PITCH];
+                        float m = INF;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            f32x2 v = *(const f32x2 *)(tr_row + 2 * i);
+                            m = fminf(m, fminf(v[0], v[1]));
+                        }
+                        a.Mm[(j0 + 32 * t + lane) * a.ldm + (qbase >> 5) + w] = m;
+                    }
+                }
             }
         }
 
