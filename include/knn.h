@@ -113,7 +113,14 @@ typedef struct {
                            Any d.  Auto takes it when that matrix is at most 72 GiB,
                            symmetric != 1 and: k > 32; or knn_build (symmetric distance) with
                            d > 96 or n <= 49152 (KNN_L1, KNN_LINF: d >= 64); or the matrix is
-                           at most 4 GiB.  A larger matrix is never written out whole: knn_build
+                           at most 4 GiB.
+                           5 = as 3, and where the triangle schedule is used (symmetric) its
+                           lists start from the pairs inside super-blocks of 65536 rows, which
+                           are evaluated in the two-phase form first; the rounds then play only
+                           pairs of blocks from different super-blocks (r_splits > 0 here sets
+                           the blocks per super-block).  Never taken by auto: it gains 0.5-5 %
+                           at n = 2^20 and needs 17.7 GB more workspace.
+                           A larger matrix is never written out whole: knn_build
                            with a symmetric distance walks it by pairs of row panels (auto: for
                            KNN_L1 / KNN_LINF with d >= 64; on the matrix cores for d > 96 and
                            either k > 32 or a fused triangle schedule that would fill the device

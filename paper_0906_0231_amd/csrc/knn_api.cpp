@@ -35,6 +35,9 @@ struct Plan {
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
+    bool warm;      // symmetric schedule whose lists start from the pairs inside super-blocks, evaluated
+                    // in two-phase form; the tournament then plays pairs of different super-blocks only
+    int32_t sb, nsbp; // ... blocks per super-block, number of super-blocks rounded up to even
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     bool matrix;    // two-phase organisation: distance matrix written out (knn_dist_qreg), then select_rows
     bool msym;      // ... computing each unordered pair of rows once
@@ -144,6 +147,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.blocked = false;
     p.mstream = false;
     p.P = 0;
+    p.warm = false;
+    p.sb = p.nsbp = 0;
     if (p.fold) {
         // lane = query, 64 per wave; the reference range is cut so that the device has
         // several thousand waves to run
@@ -235,7 +240,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     }
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
     const int32_t dpad32 = (int32_t)align_up((size_t)d, 32);
-    p.qreg = (variant == 0 || variant == 3) && dpad32 <= KNN_QRES_MAX_D;
+    p.qreg = (variant == 0 || variant == 3 || variant == 5) && dpad32 <= KNN_QRES_MAX_D;
     if (p.qreg) p.dpad = dpad32;
     p.kcap = list_capacity(k);
     p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
@@ -355,6 +360,30 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     if (S > smax) S = smax;
     if (S < 1) S = 1;
     if (p.tri) S = 1;
+    // Warm start of the symmetric schedule: on request only (variant 5; r_splits then gives the
+    // blocks per super-block).  Measured at n = 2^20, d = 256: 2487 -> 2474 ms for k = 10, 3193 ->
+    // 3044 ms for k = 100 -- the rounds stay slower than their floor long after the lists hold the
+    // best of 65 536 candidates -- which does not pay for 17.7 GB more workspace by default.
+    if (p.tri && variant == 5) {
+        int32_t sb = variant == 5 && r_splits > 0 ? r_splits : 65536 / p.B;
+        if (sb < 1) sb = 1;
+        const int32_t nsb = (p.NB + sb - 1) / sb;
+        if (nsb >= 2) {
+            p.warm = true;
+            p.sb = sb;
+            p.nsbp = nsb + (nsb & 1);
+            p.blocked = true;                     // run_two_phase walks panels of p.P rows
+            p.msym = true;
+            p.P = (int64_t)sb * p.B;
+            p.ldd = p.P + 64;
+            p.ldm = (p.ldd / 32 + 15) / 16 * 16;
+            const int64_t tiles = (p.P / KNN_TILE) * (p.P / 64) / 2;
+            int64_t chunk = (tiles + 1023) / 1024;
+            if (chunk < 4) chunk = 4;
+            if (chunk > 64) chunk = 64;
+            p.chunk = (int32_t)chunk;
+        }
+    }
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
     p.nlists = p.S * per_slice;
@@ -371,6 +400,12 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;   // + one scalar (max c_j)
     p.off_bound = o;                                 // one word per query: bound shared by the slices
     o = align_up(o + (size_t)nq * sizeof(uint32_t), 256);
+    if (p.warm) {
+        p.off_D = p.off_D2 = o;
+        o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
+        p.off_M = p.off_M2 = o;
+        o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
+    }
     p.off_lists = o;
     o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
@@ -418,11 +453,12 @@ struct Events {
 // (all of it, or the triangle mirrored) and one of select_rows.  Blocked (the matrix would not
 // fit): the rows are cut into panels of p.P; for every unordered pair of panels (a, b) the block
 // D[a][b] is written once, together with its transpose if a != b, and select_rows continues the
-// lists of the rows of a (and of b) with the columns of that block.
+// lists of the rows of a (and of b) with the columns of that block.  diag_only: only the blocks
+// (a, a) -- the warm start of the fused symmetric schedule.
 knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
                            int32_t k, knn_metric_t metric, int64_t self_offset, float *qp, float *rp, float *cr,
                            u64 *lists, char *ws, hipStream_t stream, Events &ev, int32_t &launches,
-                           int64_t &pairs_computed)
+                           int64_t &pairs_computed, bool diag_only = false)
 {
     (void)Q;
     float *D0 = (float *)(ws + p.off_D);
@@ -531,12 +567,12 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
     const int64_t seg = (p.P + 1023) / 1024 * 1024;
     for (int64_t a = 0; a < G; ++a) {
         const int64_t q0 = a * p.P, mq = nr - q0 < p.P ? nr - q0 : p.P;
-        for (int64_t b = a; b < G; ++b) {
+        for (int64_t b = a; b < (diag_only ? a + 1 : G); ++b) {
             const int64_t r0 = b * p.P, mr = nr - r0 < p.P ? nr - r0 : p.P;
             e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1);
             if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
             // rows of panel a were first seen in block (0, a) (mirrored) or, for a = 0, right here
-            e = select(D0, q0, mq, r0, mr, 1, seg, !(a == 0 && b == 0));
+            e = select(D0, q0, mq, r0, mr, 1, seg, !diag_only && !(a == 0 && b == 0));
             if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
             if (a != b) {
                 e = select(D1, r0, mr, q0, mq, 1, seg, a != 0);
@@ -561,7 +597,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
     if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
-        o.variant < 0 || o.variant > 4 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
+        o.variant < 0 || o.variant > 5 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
         return KNN_EINVAL;
 
     Plan p;
@@ -659,15 +695,36 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pa.B = p.B;
         pa.NB = p.NB;
         pa.NBp = p.NBp;
-        pa.round = -1;
-        e = launch_pairs_qreg(pa, p.NB, stream);
-        if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
-        for (int32_t r = 0; r + 1 < p.NBp; ++r) {
-            pa.round = r;
-            e = launch_pairs_qreg(pa, p.NBp / 2, stream);
-            if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
+        pa.sb_blocks = 0;
+        pa.nsbp = 0;
+        if (p.warm) {
+            // the pairs inside each super-block first, in two-phase form: every list starts the
+            // tournament with the k best of p.P candidates instead of the B of its own block
+            int32_t l0 = 0;
+            int64_t pc0 = 0;
+            st = run_two_phase(p, Q, nq, R, nr, d, k, metric, self_offset, qp, rp, cr, lists, ws, stream, ev, l0,
+                               pc0, true);
+            if (st != KNN_OK) return st;
+            pa.sb_blocks = p.sb;
+            pa.nsbp = p.nsbp;
+            for (int32_t s = 0; s + 1 < p.nsbp; ++s)
+                for (int32_t r = 0; r < p.sb; ++r) {
+                    pa.round = s * p.sb + r;
+                    e = launch_pairs_qreg(pa, (p.nsbp / 2) * p.sb, stream);
+                    if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
+                }
+            launches = l0 + (p.nsbp - 1) * p.sb;
+        } else {
+            pa.round = -1;
+            e = launch_pairs_qreg(pa, p.NB, stream);
+            if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
+            for (int32_t r = 0; r + 1 < p.NBp; ++r) {
+                pa.round = r;
+                e = launch_pairs_qreg(pa, p.NBp / 2, stream);
+                if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
+            }
+            launches = p.NBp;
         }
-        launches = p.NBp;
         // padded rows actually contracted: queries in tiles of 128, references in tiles of 64
         const int64_t last = nr - (int64_t)(p.NB - 1) * p.B;
         const int64_t lq = (last + KNN_TILE - 1) / KNN_TILE * KNN_TILE, lr = (last + 63) / 64 * 64;

@@ -125,7 +125,10 @@ struct PairArgs {
     int32_t B;         // rows per block, multiple of 128
     int32_t NB;        // number of blocks
     int32_t NBp;       // NB rounded up to even
-    int32_t round;     // 0 .. NBp-2, or -1
+    int32_t round;     // 0 .. NBp-2, or -1; with sb_blocks > 0: super-round * sb_blocks + shift
+    int32_t sb_blocks; // 0: every pair of blocks is played.  > 0: blocks per super-block; only pairs of
+                       // blocks from different super-blocks are played (see knn_pairs_qreg)
+    int32_t nsbp;      // number of super-blocks rounded up to even
 };
 
 enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3, FIN_SELECT = 4, FIN_RESCORE_HEL = 5,

@@ -209,6 +209,28 @@ def test_two_phase_by_panel_pairs(n, d, k, metric, panel):
     assert torch.equal(whole.idx, res.idx) and torch.equal(whole.dist, res.dist)
 
 
+@pytest.mark.parametrize("n,d,k,metric,block,sb", [
+    (1500, 40, 10, "sqeuclidean", 128, 2),     # 12 blocks in 6 super-blocks
+    (1500, 40, 10, "sqeuclidean", 128, 5),     # 3 super-blocks (odd: one dummy), the last one short
+    (3000, 96, 33, "cosine", 256, 3),
+    (2049, 64, 100, "hellinger", 128, 4),      # last block of a single row
+    (900, 256, 16, "sqeuclidean", 128, 1),     # super-block = block: every pair is a cross pair
+])
+def test_symmetric_schedule_with_warm_start(n, d, k, metric, block, sb):
+    """The triangle schedule whose lists start from the pairs inside super-blocks (two-phase
+    form) and whose rounds play pairs of different super-blocks only: every pair exactly once."""
+    _say(f"  warm-started triangle n={n} d={d} k={k} {metric} block={block} super-block={sb} blocks")
+    gen = workloads.uniform_rows if metric == "hellinger" else workloads.gaussian
+    X = gen(n, d, seed=9500 + n + d)
+    res = knn_build(X.cuda(), k, metric, symmetric=1, variant=5, block_rows=block, r_splits=sb, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.symmetric == 1 and res.profile.two_phase == 0
+    nb = -(-n // block)
+    nsb = -(-nb // sb)
+    assert res.profile.main_launches == 2 * nsb + (nsb + (nsb & 1) - 1) * sb
+    _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
 def test_symmetric_exact_ties():
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
