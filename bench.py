@@ -28,11 +28,14 @@ MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
 VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 # HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md).
+# WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md,
+# profiles/knn_two_phase_table1_shapes.md).
 # Keyed by (workload, schedule); reported per launch next to `achieved`.
 MEASURED_TRAFFIC_BYTES_PER_STEP = {
     ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.83e12 + 3.01e10,
     ("c3_lowrank32_n1048576_d256_k10", "full-square"): 5.85e12 + 1.59e9,
+    # knn_dist_qreg alone (profiles/knn_two_phase_table1_shapes.md)
+    ("paper_table1_n80000_d256_k100_hellinger", "two-phase triangle"): 1.24e10 + 2.68e10,
 }
 
 
@@ -177,7 +180,7 @@ def main() -> int:
                                 "frac_of_measured_peak": achieved / valu_tops})
 
     tkey = (w.name, out["config"]["schedule"])
-    if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3) and not args.block_rows:
+    if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3, 4) and not args.block_rows:
         out["roofline"]["traffic"] = MEASURED_TRAFFIC_BYTES_PER_STEP[tkey] / launches
         out["roofline"]["traffic_unit"] = "bytes per launch (offline rocprofv3 FETCH_SIZE+WRITE_SIZE)"
 
