@@ -204,10 +204,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 }
             }
             if (SYM && rt >= mirror_from) {
-                // beyond the diagonal block: the same pairs as rows j see them; for a fixed
-                // register the 32 lanes of a half hold 32 consecutive queries, 128 bytes of row j
-                // a row address every lane agrees on plus a 32-bit lane offset: keeps the 32 store
-                // addresses from occupying two registers each across the matrix loop
+                // Beyond the diagonal block: the same pairs as rows j see them; for a fixed
+                // register the 32 lanes of a half hold 32 consecutive queries, 128 bytes of row j.
+                // Addressed as a row address every lane agrees on plus a 32-bit lane offset, which
+                // keeps the 32 store addresses from occupying two registers each across the loop.
                 global_float *tbase = scalar_ptr(a.Dm + j0 * a.ldd);
                 const uint32_t voff = (uint32_t)(4 * h * a.ldd + myq);       // the host keeps it below 2^32
                 // The minima of the mirrored values: a chunk of row j's columns is this wave's 32
