@@ -309,6 +309,31 @@ def test_lattice_exact(variant):
     assert gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
 
 
+@pytest.mark.parametrize("kw", [
+    dict(variant=4, block_rows=512),                        # two-phase by pairs of row panels
+    dict(variant=5, symmetric=1, block_rows=128, r_splits=4),   # warm-started triangle
+])
+def test_ties_across_panels(kw):
+    """Ties across block boundaries: a lattice on a line (every distance tied between the two
+    sides) and a set where every pair is equidistant (the k lowest indices must win, whichever
+    panel or round brings them)."""
+    n, k = 2000, 6
+    X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
+    res = knn_build(X.cuda(), k, **kw)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", gi, gd, strict=True)
+    assert gi[1024].tolist() == [1023, 1025, 1022, 1026, 1021, 1027]
+    n, k = 1500, 17
+    E = torch.eye(n, dtype=torch.float32)
+    res = knn_build(E.cuda(), k, **kw)
+    torch.cuda.synchronize()
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    for i in (0, 1, 16, 17, 18, 511, 512, 1023, 1024, 1499):
+        assert gi[i].tolist() == [j for j in range(n) if j != i][:k]
+    assert np.all(gd == 2.0)
+
+
 @pytest.mark.parametrize("variant", [1, 2, 3, 4])
 @pytest.mark.parametrize("metric", ["sqeuclidean", "cosine"])
 def test_all_equidistant(metric, variant):
