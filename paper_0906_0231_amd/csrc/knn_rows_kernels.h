@@ -180,8 +180,8 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 // ---------------------------------------------------------------------------
 // select_rows_sparse: select_rows for a matrix that comes with the minimum of every chunk of 32
 // columns (written by the distance kernel on the way).  One wave per (row, column segment):
-//   1. the k-th smallest of the row's chunk minima bounds the k-th smallest value from above
-//      (k chunks hold at least one value each that is no larger), so
+//   1. the k-th smallest of (a sample of) the row's chunk minima bounds the k-th smallest value
+//      from above (k chunks hold at least one value each that is no larger), so
 //   2. only chunks whose minimum is within the bound (and within the list's own threshold as
 //      it tightens) are read, eight chunks per wave load; for k << n / 32 that is a small part
 //      of the row, and the kernel reads n / 8 + a few k * 128 bytes per row instead of 4 n.
@@ -190,7 +190,6 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
 {
     __shared__ u64 sList[4][KNN_MAX_KCAP];
-    __shared__ u64 sBound[4][KNN_MAX_KCAP];       // step 1: the k smallest chunk minima
     __shared__ u64 sQueue[4][64];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
@@ -208,31 +207,44 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
     const float INF = __builtin_inff();
     int count = 0;                                // queued candidates (wave-uniform)
 
-    // ---- step 1: bound = k-th smallest chunk minimum (none if the segment has fewer than k chunks)
+    // ---- step 1: a bound from the chunk minima.  Any k chunks whose minima are <= b prove that
+    // the k-th smallest value is <= b.  Every lane keeps the 4 smallest minima of the chunks it
+    // reads (256 candidates in registers, all from different chunks); the bound is the k-th
+    // smallest of those -- a little looser than the k-th smallest of all minima (a lane that
+    // holds more than 4 of the true k smallest drops some), at a small part of the cost of
+    // selecting exactly (which took more than half of this kernel's time).
     float bound = INF;
     if (ch1 - ch0 >= a.k) {
-        u64 *B = &sBound[w][0];
-        for (int i = lane; i < a.kcap; i += 64) B[i] = KEY_INF;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-        u64 bkey = KEY_INF;
-        float bp = INF;
-        for (int64_t base = ch0; base < ch1; base += 64) {
-            const int64_t ch = base + lane;
-            const float p = ch < ch1 ? Mrow[ch] : INF;
-            const u64 key = make_key(p, (int32_t)(ch - ch0));
-            const bool pass = ch < ch1 && p <= bp && key < bkey;
-            const u64 bal = __ballot(pass);
-            const int np = __popcll(bal);
-            if (np) {
-                const int pos = __popcll(bal & ((1ull << lane) - 1ull));
-                if (pass) Q[pos] = key;
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                bkey = merge_one(B, a.kcap, a.k, Q, np, lane);
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                bp = bkey == KEY_INF ? INF : ord2f((uint32_t)(bkey >> 32));
-            }
+        float s0 = INF, s1 = INF, s2 = INF, s3 = INF;            // ascending
+        for (int64_t ch = ch0 + lane; ch < ch1; ch += 64) {
+            float v = Mrow[ch];
+            float t;
+            t = fminf(s0, v); v = fmaxf(s0, v); s0 = t;
+            t = fminf(s1, v); v = fmaxf(s1, v); s1 = t;
+            t = fminf(s2, v); v = fmaxf(s2, v); s2 = t;
+            s3 = fminf(s3, v);
         }
-        bound = bp;
+        // rank: for each kept value, how many of the 256 are <= it
+        int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll 1
+        for (int l = 0; l < 64; ++l) {
+            const float x0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s0), l));
+            const float x1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s1), l));
+            const float x2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s2), l));
+            const float x3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s3), l));
+            c0 += (x0 <= s0) + (x1 <= s0) + (x2 <= s0) + (x3 <= s0);
+            c1 += (x0 <= s1) + (x1 <= s1) + (x2 <= s1) + (x3 <= s1);
+            c2 += (x0 <= s2) + (x1 <= s2) + (x2 <= s2) + (x3 <= s2);
+            c3 += (x0 <= s3) + (x1 <= s3) + (x2 <= s3) + (x3 <= s3);
+        }
+        float b = INF;
+        if (c0 >= a.k) b = fminf(b, s0);
+        if (c1 >= a.k) b = fminf(b, s1);
+        if (c2 >= a.k) b = fminf(b, s2);
+        if (c3 >= a.k) b = fminf(b, s3);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) b = fminf(b, __shfl_xor(b, o, 64));
+        bound = b;
     }
 
     // ---- step 2: the chunks within the bound
