@@ -80,7 +80,8 @@ typedef struct {
                               or the symmetric form of variant 4) */
     int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
                               padding of ragged tiles included */
-    float ms_select;       /* two_phase == 1 only: the part of ms_main spent selecting from the matrix */
+    float ms_select;       /* two-phase plans: the part of ms_main not spent in the distance kernel (the
+                              selection from the matrix; block by block also the gaps between launches) */
     int32_t two_phase;     /* 0: fused kernels.  1: variant 4, the matrix written out whole, then selected
                               from.  2: variant 4 block by block (pairs of row panels) */
 } knn_profile_t;

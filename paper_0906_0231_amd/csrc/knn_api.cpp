@@ -5,6 +5,8 @@
 #include <hip/hip_runtime_api.h>
 #include <string.h>
 
+#include <vector>
+
 #include "knn_device.h"
 
 namespace {
@@ -49,6 +51,8 @@ struct Plan {
     size_t off_D2;                   // ... blocked: buffer of the transposed block
     int64_t ldm;                     // ... chunk minima: row pitch in floats, 0 = none
     size_t off_M, off_M2;            // ... [rows of D, ldm] for D and for the transposed block
+    bool tau;                        // ... block by block with knn_dist_qreg: chunks above a row's threshold are not stored
+    size_t off_tau;                  // ... [nq_pad] value of the k-th entry of every row's list so far
     size_t off_D;                    // ... the matrix, [nq_pad, ldd]; blocked: one block, [P, ldd]
     int64_t ldd;                     // ... its row pitch in floats: n_cpad + 64, an odd multiple of 256 bytes, so that
                                      //     a column of the matrix does not fall into one memory channel
@@ -143,6 +147,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.off_D = p.off_D2 = 0;
     p.off_M = p.off_M2 = 0;
     p.ldm = 0;
+    p.tau = false;
+    p.off_tau = 0;
     p.ldd = 0;
     p.blocked = false;
     p.mstream = false;
@@ -273,14 +279,12 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     else if (variant == 0 && symmetric != 1 && matrix_ok && matrix_bytes <= KNN_MATRIX_CAP_BYTES)
         p.matrix = p.kcap > 32 || (msym ? (dpad32 >= 128 || p.n_cpad <= 49152) : matrix_bytes <= 4.0 * 1073741824.0);
     else if (variant == 0 && symmetric != 1 && matrix_ok)
-        // block by block (measured, ms fused -> blocked): long lists at any size (k = 100:
-        // n = 262 144 293 -> 200, n = 2^20 3201 -> 3080); short lists where the fused plan would
-        // be the full square (n = 150 000, d = 256: 99 -> 65; d = 128: 65 -> 45) or a triangle
-        // whose rounds fill the device badly (n = 200 000: 170 -> 114, n = 400 000: 515 -> 447;
-        // but n = 524 288: 656 against 766, and d = 128, n = 262 144: 119 against 134)
-        // -- all for d > 96: at d = 64 the stores bound it (n = 262 144, k = 100: 100 against 108)
-        p.matrix = msym && dpad32 >= 128 &&
-                   (p.kcap > 32 || !p.tri || (dpad32 >= 192 && pair_cost_ratio(nr, p.B, p.kcap) > 0.74));
+        // block by block, for d > 96 (below that the stores of the first sweep and the minima
+        // bound it: d = 64, n = 262 144, k = 100: 100 ms against 108).  Measured, ms fused ->
+        // blocked, k = 10: d = 256: n = 150 000 99 -> 65, 262 144 197 -> 149, 524 288 688 -> 572,
+        // 2^20 2457 -> 2254; d = 128: n = 262 144 101 -> 88, 524 288 343 -> 337, 2^20 1281 -> 1308
+        // (k = 32: 1409 -> 1356); k = 100, d = 256: n = 262 144 293 -> 156, 2^20 3201 -> 2700.
+        p.matrix = msym && dpad32 >= 128;
     if (p.matrix) p.matrix = two_phase_layout(p, p.n_cpad, matrix_bytes, msym, variant, block_rows);
     if (p.matrix) {
         p.mstream = dpad32 > KNN_QRES_MAX_D;       // p.dpad stays d rounded up to KNN_DC then
@@ -323,6 +327,9 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
             o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldm * sizeof(float), 256);
             p.off_M2 = o;
             if (p.blocked) o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
+            p.tau = p.blocked && !p.mstream;
+            p.off_tau = o;
+            if (p.tau) o = align_up(o + (size_t)p.nq_pad * sizeof(float), 256);
         }
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * nq * p.kcap * sizeof(u64), 256);
@@ -428,6 +435,7 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
 
 struct Events {
     hipEvent_t e[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> span;    // pairs (before, after) around the launches of one kind, see bracket()
     bool on = false;
     hipError_t create()
     {
@@ -442,10 +450,30 @@ struct Events {
     {
         if (on) (void)hipEventRecord(e[i], s);
     }
+    // one more event on the stream, kept in `span` (profiling only; a failure just drops it)
+    void bracket(hipStream_t s)
+    {
+        if (!on) return;
+        hipEvent_t x = nullptr;
+        if (hipEventCreate(&x) != hipSuccess) return;
+        (void)hipEventRecord(x, s);
+        span.push_back(x);
+    }
+    // sum over the pairs, once the stream has been waited for
+    float bracketed_ms() const
+    {
+        float sum = 0.f;
+        for (size_t i = 0; i + 1 < span.size(); i += 2) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, span[i], span[i + 1]) == hipSuccess) sum += t;
+        }
+        return sum;
+    }
     ~Events()
     {
         for (auto &x : e)
             if (x) (void)hipEventDestroy(x);
+        for (auto &x : span) (void)hipEventDestroy(x);
     }
 };
 
@@ -470,7 +498,10 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
     hipError_t e;
 
     // one block: queries [q0, q0 + mq) against references [r0, r0 + mr)
-    auto dist = [&](int64_t q0, int64_t mq, int64_t r0, int64_t mr, int mode, int64_t self_off) -> hipError_t {
+    // full_q / full_r: the query rows / the rows the mirrored values go to have been through select_rows (p.tau only)
+    float *tau = p.tau ? (float *)(ws + p.off_tau) : nullptr;
+    auto dist = [&](int64_t q0, int64_t mq, int64_t r0, int64_t mr, int mode, int64_t self_off, bool full_q,
+                    bool full_r) -> hipError_t {
         ++launches;
         if (p.fold) {
             FoldDistArgs fd;
@@ -511,6 +542,8 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         da.Dm = mode == DIST_RECT_MIRROR ? D1 : D0;
         da.M = M0;
         da.Mm = mode == DIST_RECT_MIRROR ? M1 : M0;
+        da.tauQ = tau && full_q && M0 ? tau + q0 : nullptr;
+        da.tauR = tau && full_r && M0 ? tau + r0 : nullptr;
         da.ldm = p.ldm;
         da.ldd = p.ldd;
         da.nq = mq;
@@ -550,11 +583,12 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         sa.col0 = col0;
         sa.M = A == D0 ? M0 : M1;
         sa.ldm = p.ldm;
+        sa.tau_out = tau && S == 1 ? tau + row0 : nullptr;
         return launch_select(sa, stream);
     };
 
     if (!p.blocked) {
-        e = dist(0, nq, 0, nr, p.msym ? DIST_TRIANGLE : DIST_FULL, self_offset);
+        e = dist(0, nq, 0, nr, p.msym ? DIST_TRIANGLE : DIST_FULL, self_offset, false, false);
         if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
         ev.record(4, stream);
         e = select(D0, 0, nq, 0, nr, p.S, p.sel_seg, false);
@@ -569,13 +603,16 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
         const int64_t q0 = a * p.P, mq = nr - q0 < p.P ? nr - q0 : p.P;
         for (int64_t b = a; b < (diag_only ? a + 1 : G); ++b) {
             const int64_t r0 = b * p.P, mr = nr - r0 < p.P ? nr - r0 : p.P;
-            e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1);
-            if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
             // rows of panel a were first seen in block (0, a) (mirrored) or, for a = 0, right here
-            e = select(D0, q0, mq, r0, mr, 1, seg, !diag_only && !(a == 0 && b == 0));
+            const bool seen_a = !diag_only && !(a == 0 && b == 0), seen_b = !diag_only && a != 0;
+            ev.bracket(stream);
+            e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1, seen_a, seen_b);
+            ev.bracket(stream);
+            if (e != hipSuccess) { set_error(p.fold ? "knn_fold_dist" : p.mstream ? "knn_dist_stream" : "knn_dist_qreg", e); return KNN_EDEVICE; }
+            e = select(D0, q0, mq, r0, mr, 1, seg, seen_a);
             if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
             if (a != b) {
-                e = select(D1, r0, mr, q0, mq, 1, seg, a != 0);
+                e = select(D1, r0, mr, q0, mq, 1, seg, seen_b);
                 if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
             }
         }
@@ -808,6 +845,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pr->pairs_computed = pairs_computed;
         pr->two_phase = p.matrix ? (p.blocked ? 2 : 1) : 0;
         if (p.matrix && !p.blocked) (void)hipEventElapsedTime(&pr->ms_select, ev.e[4], ev.e[2]);
+        if (p.matrix && p.blocked) pr->ms_select = pr->ms_main - ev.bracketed_ms();   // everything but the distance launches
     }
     return KNN_OK;
 }
@@ -887,6 +925,7 @@ knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32
     a.col0 = 0;
     a.M = nullptr;
     a.ldm = 0;
+    a.tau_out = nullptr;
     hipError_t e = launch_select(a, stream);
     if (e != hipSuccess) { set_error("select_rows", e); return KNN_EDEVICE; }
     FinArgs f;

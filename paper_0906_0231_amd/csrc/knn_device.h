@@ -103,6 +103,11 @@ struct DistArgs {
     float *M;          // per row and chunk of 32 columns the smallest value stored in D, [rows of D, ldm], or
                        // null: lets select_rows skip the chunks that cannot matter
     float *Mm;         // the same for the mirrored values (rows of Dm)
+    const float *tauQ; // [nq] or null: value of the k-th entry of the list a query row already has (+inf if it
+                       // is short of k).  A chunk of 32 columns whose minimum is above it cannot change the
+                       // list, select_rows will pass over it (it reads M first): it is not stored.
+                       // knn_dist_qreg only, and only together with M / Mm.
+    const float *tauR; // [nr] or null: the same for the rows the mirrored values go to
     int64_t ldq, ldr, ldd, ldm;
     int64_t nq, nr;
     int64_t self_offset;
@@ -157,6 +162,7 @@ struct SelectArgs {
     int64_t col0;      // index of column 0 in the keys
     const float *M;    // [m, ldm] smallest value of every chunk of 32 columns, or null (every column is read)
     int64_t ldm;
+    float *tau_out;    // [m] or null (requires S == 1): the value of the row's k-th entry afterwards, +inf if short of k
 };
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);

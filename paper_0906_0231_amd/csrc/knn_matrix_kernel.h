@@ -81,6 +81,12 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
     const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
     const bool qin = myq < a.nq;
+    // Rows that already have a full list (a matrix walked block by block): what cannot enter
+    // the list is not stored.  tq: threshold of this lane's query row; tr_next / tr_cur: of
+    // reference row 64 rt + lane, fetched a tile ahead.
+    const float tq = a.tauQ != nullptr ? a.tauQ[min(myq, a.nq - 1)] : __builtin_inff();
+    const bool filt_m = SYM && a.tauR != nullptr && a.Mm != nullptr;
+    float tr_next = __builtin_inff(), tr_cur = __builtin_inff();
 
     f32x4 qreg[NS];
     {
@@ -99,6 +105,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
         g0 = *(const f32x4 *)(a.Rp + r0 * a.ldr + kc * QG_DC + lunit * 4);
         g1 = *(const f32x4 *)(a.Rp + r1 * a.ldr + kc * QG_DC + lunit * 4);
         if (kc == 0 && tid < QG_TR) gc = a.cR[(int64_t)rt * QG_TR + tid];
+        if (kc == 0 && filt_m) tr_next = a.tauR[min((int64_t)rt * QG_TR + lane, a.nr - 1)];
     };
     auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
         *(f32x4 *)&sm.r[buf][st_off] = g0;
@@ -118,6 +125,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
         constexpr int kc = decltype(kc_tag)::value;
         constexpr bool last = kc == NK - 1;
         const bool more = !last || rt + 1 < rt1;
+        if (kc == 0) tr_cur = tr_next;            // this tile's; the fetch below is the next tile's
         if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
         __builtin_amdgcn_sched_barrier(0);
         if (kc == 0) {
@@ -153,34 +161,34 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
             // consecutive columns of ITS row, so storing from there would write 32 bytes per row
             // and instruction; read back row-wise, 16 lanes cover the 256 bytes of a row.
             float *tw = &sm.tr[w][ql * DT_PITCH + 4 * h];
-            float dmin0 = INF, dmin1 = INF;
-            // does the tile hold the entry of one of this wave's queries with itself?
+            // does the tile hold the entry of one of this wave's queries with itself?  (Only a
+            // tile of the diagonal block can, and those are not mirrored.)
             const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
                              j0 + QG_TR > a.self_offset + qbase + 32 * w;
+            if (own) {
 #pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                f32x4 v0 = {acc0[4 * gg], acc0[4 * gg + 1], acc0[4 * gg + 2], acc0[4 * gg + 3]};
-                f32x4 v1 = {acc1[4 * gg], acc1[4 * gg + 1], acc1[4 * gg + 2], acc1[4 * gg + 3]};
-                if (own) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (j0 + 8 * gg + 4 * h + e == selfj) v0[e] = INF;
-                        if (j0 + 32 + 8 * gg + 4 * h + e == selfj) v1[e] = INF;
-                    }
+                for (int i = 0; i < 16; ++i) {
+                    if (j0 + 8 * (i >> 2) + 4 * h + (i & 3) == selfj) acc0[i] = INF;
+                    if (j0 + 32 + 8 * (i >> 2) + 4 * h + (i & 3) == selfj) acc1[i] = INF;
                 }
-                *(f32x4 *)(tw + 8 * gg) = v0;
-                *(f32x4 *)(tw + 32 + 8 * gg) = v1;
-                dmin0 = fminf(dmin0, fminf(fminf(v0[0], v0[1]), fminf(v0[2], v0[3])));
-                dmin1 = fminf(dmin1, fminf(fminf(v1[0], v1[1]), fminf(v1[2], v1[3])));
             }
+            // the minimum of each of the two chunks of 32 columns of this lane's row (the two
+            // halves hold 16 columns of each)
+            float min0 = acc0[0], min1 = acc1[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) {
+                min0 = fminf(min0, acc0[i]);
+                min1 = fminf(min1, acc1[i]);
+            }
+            min0 = fminf(min0, __shfl_xor(min0, 32, 64));
+            min1 = fminf(min1, __shfl_xor(min1, 32, 64));
             if (a.M != nullptr) {
-                // chunk 2 rt is block 0, chunk 2 rt + 1 block 1; a row's 32 columns of a block sit in
-                // its two lanes (halves): the first half writes the one, the second the other
-                const float o0 = __shfl_xor(dmin0, 32, 64), o1 = __shfl_xor(dmin1, 32, 64);
-                // collected in LDS for 8 tiles (16 chunks = 64 bytes of the row) before they go
+                // chunk 2 rt is block 0, chunk 2 rt + 1 block 1: the first half writes the one,
+                // the second the other.
+                // Collected in LDS for 8 tiles (16 chunks = 64 bytes of the row) before they go
                 // out: written 4 bytes at a time the half-filled lines outnumber what the L2 can
                 // keep open, and every one evicted early costs the memory a read-modify-write
-                sm.mn[w][ql * DB_PITCH + 2 * (rt & 7) + h] = h == 0 ? fminf(dmin0, o0) : fminf(dmin1, o1);
+                sm.mn[w][ql * DB_PITCH + 2 * (rt & 7) + h] = h == 0 ? min0 : min1;
                 if ((rt & 7) == 7 || rt + 1 == rt1) {
                     const int first_t = max(rt & ~7, rt0);
                     const int rowl = lane >> 1, part = (lane & 1) * 8;      // 32 rows x two halves of 8 chunks
@@ -194,13 +202,21 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                     }
                 }
             }
-            {
+            // bit r: row r of the wave's 32 can use its chunk (always, without thresholds)
+            const uint32_t keep0 = (uint32_t)__ballot(min0 <= tq), keep1 = (uint32_t)__ballot(min1 <= tq);
+            if (keep0 | keep1) {
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    *(f32x4 *)(tw + 8 * gg) = f32x4{acc0[4 * gg], acc0[4 * gg + 1], acc0[4 * gg + 2], acc0[4 * gg + 3]};
+                    *(f32x4 *)(tw + 32 + 8 * gg) = f32x4{acc1[4 * gg], acc1[4 * gg + 1], acc1[4 * gg + 2], acc1[4 * gg + 3]};
+                }
                 const int rr = lane >> 4, cc = (lane & 15) * 4;
+                const uint32_t keep = (lane & 8) ? keep1 : keep0;         // 8 lanes cover a chunk of a row
                 float *drow = a.D + (qbase + 32 * w + rr) * a.ldd + j0 + cc;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 4 * i) * DT_PITCH + cc];
-                    *(f32x4 *)(drow + (int64_t)(4 * i) * a.ldd) = v;
+                    if ((keep >> (rr + 4 * i)) & 1u) *(f32x4 *)(drow + (int64_t)(4 * i) * a.ldd) = v;
                 }
             }
             if (SYM && rt >= mirror_from) {
@@ -226,8 +242,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                     for (int e = 0; e < 4; ++e) {
                         const float m0 = (acc0[4 * gg + e] - c0[e]) + cq;
                         const float m1 = (acc1[4 * gg + e] - c1[e]) + cq;
-                        (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
-                        (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
+                        if (!filt_m) {
+                            (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
+                            (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
+                        }
                         if (want_min) {
                             tm[(8 * gg + e) * DM_PITCH] = qin ? m0 : INF;
                             tm[(32 + 8 * gg + e) * DM_PITCH] = qin ? m1 : INF;
@@ -244,6 +262,25 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                         m = fminf(m, fminf(v[0], v[1]));
                     }
                     a.Mm[(j0 + lane) * a.ldm + (qbase >> 5) + w] = m;
+                    if (filt_m) {
+                        // bit j: row j0 + j can use the wave's chunk; the stores wait for this
+                        const u64 keep = __ballot(m <= tr_cur);
+                        if (keep) {
+                            const uint32_t k0 = (uint32_t)(keep >> (4 * h)), k1 = (uint32_t)(keep >> (32 + 4 * h));
+#pragma unroll
+                            for (int gg = 0; gg < 4; ++gg) {
+                                f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
+                                f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const float m0 = (acc0[4 * gg + e] - c0[e]) + cq;
+                                    const float m1 = (acc1[4 * gg + e] - c1[e]) + cq;
+                                    if ((k0 >> (8 * gg + e)) & 1u) (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
+                                    if ((k1 >> (8 * gg + e)) & 1u) (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
+                                }
+                            }
+                        }
+                    }
                 }
             }
         }

@@ -175,6 +175,8 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
     }
     flush();
     for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
+    if (a.tau_out != nullptr && lane == 0)
+        a.tau_out[row] = tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(tau_key >> 32));
 }
 
 // ---------------------------------------------------------------------------
@@ -213,16 +215,35 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
     // smallest of those -- a little looser than the k-th smallest of all minima (a lane that
     // holds more than 4 of the true k smallest drops some), at a small part of the cost of
     // selecting exactly (which took more than half of this kernel's time).
+    // (A list that is continued and already full brings its own threshold: the minima are then
+    // read once, in step 2 only.)
+    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
+    const bool full = a.resume && out[a.k - 1] != KEY_INF;
     float bound = INF;
-    if (ch1 - ch0 >= a.k) {
+    if (ch1 - ch0 >= a.k && !full) {
         float s0 = INF, s1 = INF, s2 = INF, s3 = INF;            // ascending
-        for (int64_t ch = ch0 + lane; ch < ch1; ch += 64) {
-            float v = Mrow[ch];
-            float t;
-            t = fminf(s0, v); v = fmaxf(s0, v); s0 = t;
-            t = fminf(s1, v); v = fmaxf(s1, v); s1 = t;
-            t = fminf(s2, v); v = fmaxf(s2, v); s2 = t;
-            s3 = fminf(s3, v);
+        // 1024 minima per step (four 16-byte loads per lane in flight: one wave per row has little
+        // else to hide the latency behind)
+        for (int64_t g0 = ch0; g0 < ch1; g0 += 1024) {
+            f32x4 m[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t g = g0 + j * 256 + lane * 4;
+                m[j] = g < ch1 ? *(const f32x4 *)(Mrow + g) : f32x4{INF, INF, INF, INF};
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t g = g0 + j * 256 + lane * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = g + e < ch1 ? m[j][e] : INF;
+                    float t;
+                    t = fminf(s0, v); v = fmaxf(s0, v); s0 = t;
+                    t = fminf(s1, v); v = fmaxf(s1, v); s1 = t;
+                    t = fminf(s2, v); v = fmaxf(s2, v); s2 = t;
+                    s3 = fminf(s3, v);
+                }
+            }
         }
         // rank: for each kept value, how many of the 256 are <= it
         int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
@@ -248,7 +269,6 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
     }
 
     // ---- step 2: the chunks within the bound
-    u64 *out = a.lists + ((int64_t)seg * a.m + row) * a.kcap;
     for (int i = lane; i < a.kcap; i += 64) L[i] = a.resume ? out[i] : KEY_INF;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     u64 tau_key = a.resume ? L[a.k - 1] : KEY_INF;
@@ -266,10 +286,23 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
 
     const int sub = lane >> 3;                    // which of the 8 chunks of a wave load
     const int part = (lane & 7) * 4;              // which 4 of its 32 columns
-    for (int64_t base = ch0; base < ch1; base += 64) {
-        const int64_t mych = base + lane;
-        const float mc = mych < ch1 ? Mrow[mych] : INF;
-        u64 todo = __ballot(mych < ch1 && mc <= tau_p);
+    for (int64_t g0 = ch0; g0 < ch1; g0 += 1024) {
+      // the minima of 1024 chunks: lane l holds chunks g0 + 256 j + 4 l + e as mm[4 j + e]
+      float mm[16];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+          const int64_t g = g0 + j * 256 + lane * 4;
+          const f32x4 m = g < ch1 ? *(const f32x4 *)(Mrow + g) : f32x4{INF, INF, INF, INF};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mm[4 * j + e] = g + e < ch1 ? m[e] : INF;
+      }
+#pragma unroll 1
+      for (int t = 0; t < 16; ++t) {
+        const float mc = mm[0];
+#pragma unroll
+        for (int i = 0; i < 15; ++i) mm[i] = mm[i + 1];
+        const int64_t base = g0 + (t >> 2) * 256 + (t & 3);      // lane l: chunk base + 4 l
+        u64 todo = __ballot(mc <= tau_p);
         while (todo) {
             // the next (up to) 8 marked chunks, one per group of 8 lanes
             int pick = -1;
@@ -284,7 +317,7 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
             // the threshold may have tightened since the chunk was marked
             const float pm = __shfl(mc, pick < 0 ? 0 : pick, 64);
             const bool live = pick >= 0 && pm <= tau_p;
-            const int64_t col = ((base + (pick < 0 ? 0 : pick)) << 5) + part;
+            const int64_t col = ((base + 4 * (pick < 0 ? 0 : pick)) << 5) + part;
             f32x4 v = {INF, INF, INF, INF};
             if (live) {
                 if (a.vec4 && col + 3 < c1) {
@@ -314,9 +347,12 @@ __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
             // (while the list is short of k the bound does the filtering; no need to merge eagerly)
             if (count >= 32 || (tau_key == KEY_INF && bound == INF)) flush();
         }
+      }
     }
     flush();
     for (int i = lane; i < a.kcap; i += 64) out[i] = L[i];
+    if (a.tau_out != nullptr && lane == 0)
+        a.tau_out[row] = tau_key == KEY_INF ? __builtin_inff() : ord2f((uint32_t)(tau_key >> 32));
 }
 
 // ---------------------------------------------------------------------------

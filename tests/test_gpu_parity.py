@@ -159,6 +159,7 @@ def test_symmetric_equals_full_square():
     (262144, 64, 10, 1, 1024),   # fused, blocks of 256 rows
     (262144, 64, 100, 0, 1),     # long lists: the mirror merges make the triangle no cheaper yet (and at d = 64 stores would bound the two-phase form)
     (150000, 128, 100, 1, 15),   # beyond 72 GiB of matrix: two-phase by pairs of row panels (3 panels: 6 blocks, 9 selections)
+    (300000, 128, 10, 1, 40),    # the same for short lists (5 panels: 15 blocks, 25 selections)
     (20000, 256, 100, 1, 2),     # the shape of the paper's Table 1: matrix written out, each pair once
     (40000, 64, 10, 1, 2),       # small enough for the two-phase form whatever d and k
     (60000, 64, 10, 0, 1),       # d = 64 and not small: the matrix would cost more than it saves
@@ -332,6 +333,25 @@ def test_ties_across_panels(kw):
     for i in (0, 1, 16, 17, 18, 511, 512, 1023, 1024, 1499):
         assert gi[i].tolist() == [j for j in range(n) if j != i][:k]
     assert np.all(gd == 2.0)
+
+
+@pytest.mark.parametrize("n,d,k,panel", [(1536, 48, 8, 512), (2300, 256, 20, 768), (3000, 33, 3, 256)])
+def test_panel_pairs_when_the_neighbours_come_late(n, d, k, panel):
+    """Walked by panel pairs, blocks that cannot change a row's list are not stored (a row's
+    threshold after the panels it has seen filters what later blocks write).  Here the true
+    neighbours of the first rows sit in the last panel and those of the last rows in the first,
+    and the middle is far from both: the thresholds stay loose until the very last blocks."""
+    _say(f"  neighbours in the last panel n={n} d={d} k={k} panel={panel}")
+    third = n // 3
+    A = workloads.gaussian(third, d, seed=31 + n)
+    far = workloads.gaussian(n - 2 * third, d, seed=32 + n) * 3.0 + 4.0
+    near = A + 0.05 * workloads.gaussian(third, d, seed=33 + n)
+    X = torch.cat([A, far, near]).contiguous()
+    res = knn_build(X.cuda(), k, variant=4, block_rows=panel, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.two_phase == 2
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+    assert (res.idx[:third, 0].cpu() == torch.arange(third) + (n - third)).all()
 
 
 @pytest.mark.parametrize("variant", [1, 2, 3, 4])

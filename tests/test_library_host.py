@@ -43,11 +43,17 @@ def test_workspace_bytes(lib):
     assert f(10, 10, 8, 3, 2, 0) > 0           # Hellinger
     assert f(10, 1000, 8, api.KNN_MAX_K + 1, 0, 0) == 0
     n, d, k = 1 << 20, 256, 10
-    b = f(n, n, d, k, 0, 1)
+    # by default two blocks of 65536^2 distances (the matrix is walked by pairs of row panels)
+    block = 65536 * (65536 + 64) * 4
+    assert 2 * block <= f(n, n, d, k, 0, 1) < 2 * block + 2**32
+
+    def fused(d, metric):
+        return api.knn_workspace_bytes(n, n, d, k, metric, symmetric=True, variant=3)
+    b = fused(d, "sqeuclidean")
     # scaled query copy + norms + one 16-slot list per query, and not much more
     assert n * d * 4 + n * 16 * 8 <= b <= n * d * 4 + n * 16 * 8 + n * 16 + (1 << 20)
-    assert f(n, n, d, k, 1, 1) >= b + n * d * 4   # cosine also keeps a normalised reference copy
-    assert f(n, n, d + 1, k, 0, 1) > b            # ragged d: padded copies of both sides
+    assert fused(d, "cosine") >= b + n * d * 4    # cosine also keeps a normalised reference copy
+    assert fused(d + 1, "sqeuclidean") > b        # ragged d: padded copies of both sides
 
 
 def test_workspace_of_the_two_phase_form(lib):
@@ -68,14 +74,13 @@ def test_workspace_of_the_two_phase_form(lib):
     assert ws(40000, 64, 10) >= matrix(40000)
     assert ws(60000, 64, 10) < matrix(60000) // 8
     assert ws(60000, 128, 10) >= matrix(60000)
-    # never whole beyond 72 GiB of matrix: pairs of row panels instead (two blocks of 65536^2),
-    # by default for long lists; short lists stay fused there
+    # never whole beyond 72 GiB of matrix: pairs of row panels instead (two blocks of 65536^2)
     block = 65536 * (65536 + 64) * 4
     assert 2 * block <= ws(150000, 256, 100) < 2 * block + 2**31
     assert ws(150000, 256, 100, variant=4) == ws(150000, 256, 100)
-    assert 2 * block <= ws(150000, 256, 10) < 2 * block + 2**31    # ... unless the fused triangle would fill the device badly
-    assert ws(524288, 256, 10) < 2**30
-    assert ws(150000, 64, 10) < 2**30
+    assert 2 * block <= ws(150000, 256, 10) < 2 * block + 2**31    # also for short lists from d = 128
+    assert 2 * block <= ws(524288, 128, 10) < 2 * block + 2**31
+    assert ws(150000, 64, 10) < 2**30                               # below that the fused kernels
     assert 2 * block <= ws(150000, 128, 10, variant=4) < 2 * block + 2**31
     # a panel size on request (with variant 4) walks even a small matrix block by block
     assert ws(20000, 256, 100, variant=4, block_rows=1000) < matrix(20000) // 8
