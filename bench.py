@@ -29,11 +29,13 @@ VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 # HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md,
-# profiles/knn_two_phase_table1_shapes.md).
+# profiles/knn_two_phase_c3_panel_pairs.md, profiles/knn_two_phase_table1_shapes.md).
 # Keyed by (workload, schedule); reported per launch next to `achieved`.
 MEASURED_TRAFFIC_BYTES_PER_STEP = {
     ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.83e12 + 3.01e10,
     ("c3_lowrank32_n1048576_d256_k10", "full-square"): 5.85e12 + 1.59e9,
+    # knn_dist_qreg, all 136 launches of a step (profiles/knn_two_phase_c3_panel_pairs.md)
+    ("c3_lowrank32_n1048576_d256_k10", "two-phase by panel pairs"): 3.195e11 + 4.858e11,
     # knn_dist_qreg alone (profiles/knn_two_phase_table1_shapes.md)
     ("paper_table1_n80000_d256_k100_hellinger", "two-phase triangle"): 1.24e10 + 2.68e10,
 }

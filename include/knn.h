@@ -123,9 +123,10 @@ typedef struct {
                            at n = 2^20 and needs 17.7 GB more workspace.
                            A larger matrix is never written out whole: knn_build
                            with a symmetric distance walks it by pairs of row panels (auto: for
-                           KNN_L1 / KNN_LINF with d >= 64; on the matrix cores for d > 96 and
-                           either k > 32 or a fused triangle schedule that would fill the device
-                           badly), other calls stay fused */
+                           KNN_L1 / KNN_LINF with d >= 64; on the matrix cores for d > 96),
+                           two blocks of 65536 x 65536 distances in the workspace; once a row has
+                           a full list, chunks of 32 distances that cannot enter it are not even
+                           stored (d <= 256).  Other calls stay fused */
     int32_t block_rows; /* Fused symmetric schedule: rows per block; rounded up to a multiple
                            of 128.  A round launches ceil(ceil(n/block_rows)/2) workgroups.
                            0 = auto: the multiple of 128 for which the rounds fill the device's
@@ -183,7 +184,8 @@ knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t n
  * for knn_build (nq is ignored, nr = n), 0 for knn_search.  The workspace must be
  * 256-byte aligned; its contents need not be initialised and are garbage after.
  * Where the default plan writes the distance matrix out this is its size and more
- * (up to 72 GiB); a caller who cannot spare that asks for variant 3 through
+ * (up to 72 GiB; 35 GB for the two blocks of a larger one); a caller who cannot
+ * spare that asks for variant 3 through
  * knn_workspace_bytes_ex and the _ex entry points (copies of the inputs and the
  * lists only: about 4 n d + 8 n kcap bytes).
  */
