@@ -447,12 +447,12 @@ def test_config1_full(variant):
                 res.dist.cpu().numpy())
 
 
-def _full_size(which, sample, variant=0, two_phase=None):
+def _full_size(which, sample, variant=0, two_phase=None, symmetric=0):
     w = workloads.config(which)
-    _say(f"  {w.name}: generated (variant {variant})")
+    _say(f"  {w.name}: generated (variant {variant}, symmetric {symmetric})")
     Rd = w.R.cuda()
     if w.symmetric:
-        res = knn_build(Rd, w.k, w.metric, variant=variant, profile=True)
+        res = knn_build(Rd, w.k, w.metric, variant=variant, symmetric=symmetric, profile=True)
     else:
         res = knn_search(Rd[:w.nq], Rd, w.k, w.metric, self_offset=0, variant=variant, profile=True)
     torch.cuda.synchronize()
@@ -476,8 +476,11 @@ def test_config2_full(variant, two_phase):
     _full_size(2, 1024, variant, two_phase)      # by default the two-phase form (d = 128, matrix of 16 GiB)
 
 
-def test_config3_full():
-    _full_size(3, 256)
+@pytest.mark.parametrize("symmetric,two_phase", [(0, 2), (1, 0)])
+def test_config3_full(symmetric, two_phase):
+    """The headline workload in the plan bench.py times (by pairs of row panels, stores filtered
+    by the lists' thresholds) and in the fused symmetric schedule."""
+    _full_size(3, 256, two_phase=two_phase, symmetric=symmetric)
 
 
 def test_config4_full():
