@@ -187,7 +187,9 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 //   2. only chunks whose minimum is within the bound (and within the list's own threshold as
 //      it tightens) are read, eight chunks per wave load; for k << n / 32 that is a small part
 //      of the row, and the kernel reads n / 8 + a few k * 128 bytes per row instead of 4 n.
-// Same list, queue and merge as select_rows; ties, `resume` and `col0` likewise.
+// Same list, queue and merge as select_rows; ties, `resume` and `col0` likewise.  A chunk whose
+// minimum is above the threshold the row's list had before this call is never read -- the
+// distance kernel relies on that and may have left such a chunk unwritten (DistArgs.tauQ).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void select_rows_sparse(SelectArgs a)
 {
