@@ -214,6 +214,12 @@ def main() -> int:
                                   "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
                                   "workload": f"{sm_rows} x {sm_cols} fp32 slab, k={k}",
                                   "ms": sel_ms, "elements_per_s": sm_rows * sm_cols / (sel_ms * 1e-3)}
+        # the read rate this machine sustains on the same slab (loads only), beside the nominal peak
+        from paper_0906_0231_amd import knn_read_calibration
+        knn_read_calibration(slab.view(-1), sm_cols)
+        read_gbs = max(knn_read_calibration(slab.view(-1), sm_cols)[0] for _ in range(3))
+        out["selection_stage"]["measured_peak"] = read_gbs
+        out["selection_stage"]["frac_of_measured_peak"] = gbs / read_gbs
         del slab, sws, sout
 
     if args.copy_calibration:

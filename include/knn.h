@@ -240,6 +240,18 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
 knn_status_t knn_valu_calibration(int64_t pairs_per_wave, int32_t waves_per_simd, float *sink,
                                   size_t sink_bytes, int64_t *total_waves, void *stream);
 
+/*
+ * The same for the memory: reads `n_floats` floats from `buf` (DEVICE pointer, 16-byte aligned)
+ * exactly once, the way the selection kernel of knn_select reads the rows of its matrix -- every
+ * wave a contiguous range of `floats_per_wave`, eight 16-byte loads in flight per lane -- and
+ * does nothing with them but keep a minimum.  A caller who times the launch learns the read
+ * rate the device's memory sustains (4 * n_floats bytes per launch), to put beside the nominal
+ * HBM peak and beside knn_select's own rate.  Both counts must be positive multiples of 2048;
+ * the sink (DEVICE pointer) must hold 1024 floats.  Errors as for knn_mfma_calibration.
+ */
+knn_status_t knn_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
+                                  size_t sink_bytes, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *knn_status_string(knn_status_t status);
 

@@ -30,7 +30,8 @@ METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KN
 
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_select", "knn_select_workspace_bytes",
-           "knn_mfma_calibration", "knn_valu_calibration", "knn_status_string", "knn_last_device_error"]
+           "knn_mfma_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
+           "knn_last_device_error"]
 
 
 class KnnProfile(ctypes.Structure):
@@ -87,6 +88,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_select_workspace_bytes.argtypes = [i64, i64, i32]
     lib.knn_mfma_calibration.restype = i32
     lib.knn_mfma_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
+    lib.knn_read_calibration.restype = i32
+    lib.knn_read_calibration.argtypes = [vp, i64, i64, vp, sz, vp]
     lib.knn_valu_calibration.restype = i32
     lib.knn_valu_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_status_string.restype = ctypes.c_char_p
@@ -274,3 +277,23 @@ def knn_valu_calibration(pairs_per_wave: int = 1 << 22, waves_per_simd: int = 4,
         stop.synchronize()
         ms = start.elapsed_time(stop)
     return waves.value * pairs_per_wave * 128.0 / (ms * 1e-3) / 1e12, ms
+
+
+def knn_read_calibration(buf: torch.Tensor, floats_per_wave: int = 1 << 18) -> Tuple[float, float]:
+    """Time the library's read-only kernel over `buf` (fp32, contiguous, a multiple of 2048
+    elements); returns (GB/s, ms).  See knn_read_calibration in knn.h."""
+    lib = load_library()
+    if buf.dtype != torch.float32 or not buf.is_contiguous() or not buf.is_cuda:
+        raise ValueError("buf must be a contiguous fp32 CUDA tensor")
+    dev = buf.device
+    with torch.cuda.device(dev):
+        sink = torch.empty(1024, dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream(dev)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        _check(lib.knn_read_calibration(buf.data_ptr(), buf.numel(), floats_per_wave, sink.data_ptr(),
+                                        sink.numel() * 4, stream.cuda_stream))
+        stop.record(stream)
+        stop.synchronize()
+        ms = start.elapsed_time(stop)
+    return buf.numel() * 4.0 / (ms * 1e-3) / 1e9, ms

@@ -980,6 +980,19 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
     return KNN_OK;
 }
 
+knn_status_t knn_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
+                                  size_t sink_bytes, void *stream)
+{
+    g_last_error[0] = 0;
+    if (!buf || !sink || ((uintptr_t)buf & 15) || n_floats < 2048 || n_floats % 2048 != 0 ||
+        floats_per_wave < 2048 || floats_per_wave % 2048 != 0 || sink_bytes < 1024 * sizeof(float))
+        return KNN_EINVAL;
+    if ((n_floats + floats_per_wave - 1) / floats_per_wave > ((int64_t)1 << 32)) return KNN_EINVAL;
+    hipError_t e = launch_read_calibration(buf, n_floats, floats_per_wave, sink, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("read_only", e); return KNN_EDEVICE; }
+    return KNN_OK;
+}
+
 knn_status_t knn_valu_calibration(int64_t pairs_per_wave, int32_t waves_per_simd, float *sink,
                                   size_t sink_bytes, int64_t *total_waves, void *stream)
 {

@@ -167,6 +167,8 @@ struct SelectArgs {
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
+hipError_t launch_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
+                                   hipStream_t stream);   // sizes: multiples of 2048 floats
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
 hipError_t launch_fold_dist(const FoldDistArgs &a, int mode, hipStream_t stream);
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);

@@ -54,6 +54,15 @@ hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *si
     return hipGetLastError();
 }
 
+hipError_t launch_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
+                                   hipStream_t stream)
+{
+    const int64_t n_pieces = n_floats / SEL_CHUNK, ppw = floats_per_wave / SEL_CHUNK;
+    const int64_t waves = (n_pieces + ppw - 1) / ppw;
+    hipLaunchKernelGGL(read_only, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, stream, buf, n_pieces, ppw, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream)
 {
     hipLaunchKernelGGL(mfma_only, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);

@@ -180,6 +180,33 @@ __global__ __launch_bounds__(256) void select_rows(SelectArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// read_only: calibration.  Reads a buffer once, the way select_rows reads its rows (every wave
+// a contiguous range, 8 KB per step, every lane eight 16-byte loads in flight, consecutive
+// lanes consecutive addresses), keeps the minimum and does nothing else: the read rate this
+// device's memory sustains, to put beside the nominal peak.  One value per workgroup goes to
+// the sink.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void read_only(const float *buf, int64_t n_pieces, int64_t pieces_per_wave,
+                                                 float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t p0 = wave * pieces_per_wave, p1 = min(p0 + pieces_per_wave, n_pieces);
+    float m = __builtin_inff();
+    for (int64_t piece = p0; piece < p1; ++piece) {                    // pieces of SEL_CHUNK floats
+        const f32x4 *src = (const f32x4 *)(buf + piece * SEL_CHUNK) + lane;
+        f32x4 v[SEL_LOADS];
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) v[j] = src[j * 64];
+#pragma unroll
+        for (int j = 0; j < SEL_LOADS; ++j) m = fminf(m, fminf(fminf(v[j][0], v[j][1]), fminf(v[j][2], v[j][3])));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fminf(m, __shfl_xor(m, o, 64));
+    if (threadIdx.x == 0) sink[blockIdx.x & 1023] = m;
+}
+
+// ---------------------------------------------------------------------------
 // select_rows_sparse: select_rows for a matrix that comes with the minimum of every chunk of 32
 // columns (written by the distance kernel on the way).  One wave per (row, column segment):
 //   1. the k-th smallest of (a sample of) the row's chunk minima bounds the k-th smallest value

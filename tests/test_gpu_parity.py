@@ -421,6 +421,11 @@ def test_mfma_calibration_runs():
     assert ms > 0 and 1.0 < tops < 100.0
     st = lib.knn_valu_calibration(1024, 2, sink.data_ptr(), sink.numel() * 4, None, None)
     assert st == api.KNN_EINVAL
+    from paper_0906_0231_amd import knn_read_calibration
+    buf = torch.full((1 << 24,), 3.0, dtype=torch.float32, device="cuda")
+    buf[12345678] = -7.0
+    gbs, ms = knn_read_calibration(buf, 1 << 16)
+    assert ms > 0 and 10.0 < gbs < 20000.0
 
 
 def test_device_error_paths():

@@ -137,3 +137,14 @@ def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(ValueError):
         api.knn_build(torch.zeros(10, 4), 2)
+
+
+def test_read_calibration_rejects_bad_arguments_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    call = lib.knn_read_calibration
+    assert call(None, 4096, 2048, one, 4096, None) == api.KNN_EINVAL     # no buffer
+    assert call(one, 4096, 2048, None, 4096, None) == api.KNN_EINVAL     # no sink
+    assert call(one, 1000, 2048, one, 4096, None) == api.KNN_EINVAL      # not a multiple of 2048
+    assert call(one, 4096, 100, one, 4096, None) == api.KNN_EINVAL
+    assert call(one, 4096, 2048, one, 100, None) == api.KNN_EINVAL       # sink too small
+    assert call(ctypes.c_void_p(260), 4096, 2048, one, 4096, None) == api.KNN_EINVAL   # misaligned
