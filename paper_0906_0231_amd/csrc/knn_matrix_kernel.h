@@ -79,8 +79,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     const int64_t qbase = (int64_t)qt * TQ;
     const int64_t myq = qbase + 32 * w + ql;      // < nq_pad: D has that many rows
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
-    const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
     const bool qin = myq < a.nq;
+    // the query's own term for the mirrored values; +inf past the end of the set, so that such a
+    // column comes out as +inf and never lowers a chunk minimum
+    const float cq = SYM ? (qin ? a.cQ[myq] : __builtin_inff()) : 0.f;
     // Rows that already have a full list (a matrix walked block by block): what cannot enter
     // the list is not stored.  tq: threshold of this lane's query row; tr_next / tr_cur: of
     // reference row 64 rt + lane, fetched a tile ahead.
@@ -230,8 +232,8 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 // queries, i.e. one value per lane of a half -- a reduction across lanes for each
                 // of the 32 register pairs.  Cheaper through the wave's LDS buffer: the values go in
                 // row-major (row = reference j of the tile, column = query), lane j reads its row
-                // back and keeps the minimum in its own registers.  Columns past the end of the
-                // set must not lower a minimum: they go in as +inf.
+                // back and keeps the minimum in its own registers.  (Columns past the end of the
+                // set have c_q = +inf.)
                 const bool want_min = a.Mm != nullptr;
                 float *tm = &sm.tr[w][(4 * h) * DM_PITCH + ql];
 #pragma unroll
@@ -247,8 +249,8 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                             (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
                         }
                         if (want_min) {
-                            tm[(8 * gg + e) * DM_PITCH] = qin ? m0 : INF;
-                            tm[(32 + 8 * gg + e) * DM_PITCH] = qin ? m1 : INF;
+                            tm[(8 * gg + e) * DM_PITCH] = m0;
+                            tm[(32 + 8 * gg + e) * DM_PITCH] = m1;
                         }
                     }
                 }
