@@ -416,6 +416,20 @@ __device__ __forceinline__ double group16_sum_f64(double v)
     return v;
 }
 
+// sqrt of a non-negative float as a double, to about 1e-13 relative: the hardware's single
+// precision reciprocal square root (1 ulp) and one Newton step in double.  With r = (1 + e)/sqrt(v),
+// h = v r and 1 - h r = -2e - e^2, h (1 + (1 - h r)/2) = sqrt(v) (1 - 1.5 e^2).  The library
+// routine for double costs three times as much, and the Hellinger re-pricing takes one root per
+// coordinate and winner.  Zero is exact; denormals (and NaN) take the library routine.
+__device__ __forceinline__ double sqrt_of_float(float v)
+{
+    if (v == 0.f) return 0.0;
+    if (!(v >= 1.17549435e-38f)) return sqrt((double)v);
+    const double r = (double)__builtin_amdgcn_rsqf(v);
+    const double h = (double)v * r;
+    return fma(0.5 * h, fma(-h, r, 1.0), h);
+}
+
 __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
 {
     // sized by the launcher to what this call needs (S * kcap keys rounded up to a power of two,
@@ -491,7 +505,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                 f32x4 u = {0.f, 0.f, 0.f, 0.f};
                 if (c < a.d) u = *(const f32x4 *)(x + c);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xs[i][e] = sqrt((double)u[e]);
+                for (int e = 0; e < 4; ++e) xs[i][e] = sqrt_of_float(u[e]);
             }
         }
         for (int r0 = 0; r0 < a.k; r0 += 4) {
@@ -508,7 +522,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                         f32x4 v = *(const f32x4 *)(y + c);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            double t = xs[i][e] - sqrt((double)v[e]);
+                            double t = xs[i][e] - sqrt_of_float(v[e]);
                             s = fma(t, t, s);
                         }
                     }
@@ -524,7 +538,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                             uu = fma(ud, ud, uu);
                             vv = fma(vd, vd, vv);
                         } else {
-                            double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
+                            double t = root ? sqrt_of_float(u[e]) - sqrt_of_float(v[e]) : ud - vd;
                             s = fma(t, t, s);
                         }
                     }
@@ -537,7 +551,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                         uu = fma(ud, ud, uu);
                         vv = fma(vd, vd, vv);
                     } else {
-                        double t = root ? sqrt(ud) - sqrt(vd) : ud - vd;
+                        double t = root ? sqrt_of_float(x[c]) - sqrt_of_float(y[c]) : ud - vd;
                         s = fma(t, t, s);
                     }
                 }
