@@ -276,6 +276,22 @@ def test_hellinger_perfect_squares_exact():
                 res.dist.cpu().numpy(), strict=True)
 
 
+def test_hellinger_sparse_histograms():
+    """Rows that are mostly exact zeros, with a few denormal entries: the square roots of the
+    re-pricing take their exact (zero) and their slow (denormal) branch."""
+    rng = np.random.default_rng(77)
+    n, d = 1300, 96
+    A = rng.random((n, d)).astype(np.float32)
+    A[rng.random((n, d)) < 0.7] = 0.0
+    A[rng.random((n, d)) < 0.02] = np.float32(3e-40)
+    A[:, 0] += 0.01                               # no empty row
+    X = torch.from_numpy((A / A.sum(axis=1, keepdims=True)).astype(np.float32))
+    for variant in (3, 4):
+        res = knn_build(X.cuda(), 12, "hellinger", variant=variant)
+        torch.cuda.synchronize()
+        _check_rows(X.numpy(), np.arange(n), 0, 12, "hellinger", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
 def test_paper_experiment_shape():
     """n = 10 000, d = 256, k = 100, Hellinger: the smallest column of the paper's Table 1."""
     w = workloads.config(6, n=10000)
