@@ -27,17 +27,19 @@ MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
 # lanes per clock; two or more waves of a SIMD reach the 32, measured by knn_valu_calibration.)
 VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
-# HBM/fabric bytes per step of the fused kernel(s), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script scaled by a 1 GiB copy kernel (profiles/knn_c3_registers_resident.md,
-# profiles/knn_two_phase_c3_panel_pairs.md, profiles/knn_two_phase_table1_shapes.md).
-# Keyed by (workload, schedule); reported per launch next to `achieved`.
-MEASURED_TRAFFIC_BYTES_PER_STEP = {
-    ("c3_lowrank32_n1048576_d256_k10", "triangle"): 5.83e12 + 3.01e10,
-    ("c3_lowrank32_n1048576_d256_k10", "full-square"): 5.85e12 + 1.59e9,
-    # knn_dist_qreg, all 136 launches of a step (profiles/knn_two_phase_c3_panel_pairs.md)
-    ("c3_lowrank32_n1048576_d256_k10", "two-phase by panel pairs"): 3.195e11 + 4.858e11,
-    # knn_dist_qreg alone (profiles/knn_two_phase_table1_shapes.md)
-    ("paper_table1_n80000_d256_k100_hellinger", "two-phase triangle"): 1.24e10 + 2.68e10,
+# HBM bytes per step of the dominant kernel, measured OFFLINE (two rocprofv3 --pmc runs of this
+# script, FETCH_SIZE then WRITE_SIZE, scaled by what the same counters read for a 1 GiB copy
+# kernel).  Keyed by (workload, kernel); each entry names the summary under profiles/ that
+# holds the run.  Reported per launch next to `achieved`; null for anything not listed.
+OFFLINE_TRAFFIC_BYTES_PER_STEP = {
+    ("c3_lowrank32_n1048576_d256_k10", "knn_dist_qreg"):
+        (3.195e11 + 4.858e11, "profiles/knn_two_phase_c3_panel_pairs.md"),
+    ("c3_lowrank32_n1048576_d256_k10", "knn_pairs_qreg"):
+        (5.83e12 + 3.01e10, "profiles/knn_c3_registers_resident.md"),
+    ("c3_lowrank32_n1048576_d256_k10", "knn_tiles_qreg"):
+        (5.85e12 + 1.59e9, "profiles/knn_c3_registers_resident.md"),
+    ("paper_table1_n80000_d256_k100_hellinger", "knn_dist_qreg"):
+        (1.24e10 + 2.68e10, "profiles/knn_two_phase_table1_shapes.md"),
 }
 
 
@@ -50,7 +52,9 @@ def main() -> int:
                          "8 = Kullback-Leibler)")
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
-    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 streaming, 2 query tile in LDS, 3 query tile in registers, 4 two-phase")
+    ap.add_argument("--variant", type=int, default=0, help="plan: 0 auto, 1 fused streaming, 3 fused with the query operands in registers, 4 two-phase")
+    ap.add_argument("--no-fused-legs", dest="fused_legs", action="store_false",
+                    help="skip the extra timing of the fused plans when the default plan is two-phase")
     ap.add_argument("--block-rows", type=int, default=0, help="symmetric schedule: rows per block")
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -82,55 +86,63 @@ def main() -> int:
     nq, nr, d, k = w.nq, w.n, w.d, w.k
     gen_s = time.time() - t0
 
-    ws = torch.empty(knn_workspace_bytes(nq, nr, d, k, w.metric, symmetric=w.symmetric,
-                                         variant=args.variant, schedule=args.symmetric,
-                                         block_rows=args.block_rows),
-                     dtype=torch.uint8, device=dev)
     idx = torch.empty((nq, k), dtype=torch.int32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
-    def step(profile):
-        if w.symmetric:
-            return knn_build(R, k, w.metric, symmetric=args.symmetric, variant=args.variant,
-                             block_rows=args.block_rows, profile=profile, workspace=ws,
-                             out=(idx, dist))
-        return knn_search(Q, R, k, w.metric, self_offset=w.self_offset, variant=args.variant,
-                          profile=profile, workspace=ws, out=(idx, dist))
+    def time_plan(symmetric, variant, block_rows, steps, warmup):
+        """`warmup` untimed calls, then `steps` calls timed as the ABI promises them -- enqueued
+        without waiting, one synchronisation at each end -- then ONE more call with a profile
+        record, whose HIP events around the kernels (on the launch stream, inside the library)
+        give the dominant kernel's time per launch."""
+        ws = torch.empty(knn_workspace_bytes(nq, nr, d, k, w.metric, symmetric=w.symmetric, variant=variant,
+                                             schedule=symmetric, block_rows=block_rows),
+                         dtype=torch.uint8, device=dev)
 
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    main_ms, launches, pairs_computed, symmetric, two_phase, select_ms = [], 1, 0, 0, 0, []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        res = step(True)           # events around the fused kernel, on the launch stream
-        main_ms.append(res.profile.ms_main)
-        launches = max(1, res.profile.main_launches)
-        pairs_computed = res.profile.pairs_computed
-        symmetric = res.profile.symmetric
-        two_phase = res.profile.two_phase
-        select_ms.append(res.profile.ms_select)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+        def step(profile):
+            if w.symmetric:
+                return knn_build(R, k, w.metric, symmetric=symmetric, variant=variant, block_rows=block_rows,
+                                 profile=profile, workspace=ws, out=(idx, dist))
+            return knn_search(Q, R, k, w.metric, self_offset=w.self_offset, variant=variant,
+                              profile=profile, workspace=ws, out=(idx, dist))
 
+        for _ in range(warmup):
+            step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            res = step(False)
+        torch.cuda.synchronize()
+        ms_per_step = 1e3 * (time.perf_counter() - t0) / steps
+        res = step(True)
+        plan, prof = res.plan, res.profile
+        kernel = plan.kernel.decode()
+        if plan.two_phase == 1:
+            # matrix written out, then selected from: the dominant kernel is the one that writes it
+            launches = 1
+            kern_ms = prof.ms_main - prof.ms_select
+        elif plan.two_phase == 2:
+            # by pairs of row panels: one distance launch per pair (the library brackets each with
+            # events), the selections after it.  G panels: G(G+1)/2 distance launches
+            G = int(round((-1.0 + (1.0 + 24.0 * plan.main_launches) ** 0.5) / 6.0))
+            launches = G * (G + 1) // 2
+            kern_ms = (prof.ms_main - prof.ms_select) / launches
+        else:
+            launches = max(1, plan.main_launches)
+            kern_ms = prof.ms_main / launches
+        work_per_launch = 2.0 * d * prof.pairs_computed / launches      # flop (matrix path) or lane operations (fold)
+        achieved = work_per_launch / (kern_ms * 1e-3) / 1e12
+        del ws
+        return {"ms_per_step": ms_per_step, "kernel": kernel, "launches": launches, "kern_ms": kern_ms,
+                "achieved": achieved, "pairs_computed": int(prof.pairs_computed), "symmetric": int(plan.symmetric),
+                "two_phase": int(plan.two_phase), "main_ms": float(prof.ms_main), "select_ms": float(prof.ms_select),
+                "workspace_bytes": int(plan.workspace_bytes)}
+
+    t = time_plan(args.symmetric, args.variant, args.block_rows, args.steps, args.warmup)
+    ms_per_step = t["ms_per_step"]
+    two_phase, symmetric, launches, kern_ms, achieved = t["two_phase"], t["symmetric"], t["launches"], t["kern_ms"], t["achieved"]
     pairs_served = float(nq) * float(nr)
     value = pairs_served / (ms_per_step * 1e-3)
-    # dominant kernel: the fused tile kernel; algorithmic work = 2*d flop per pair it evaluates
-    if two_phase == 1:
-        # matrix written out, then selected from: the dominant kernel is the one that writes it
-        launches = 1
-        kern_ms = float(np.mean(main_ms)) - float(np.mean(select_ms))
-    elif two_phase == 2:
-        # block by block: one distance launch per pair of row panels (the library brackets each
-        # with events), two selections after it.  G panels: G(G+1)/2 + G*G launches in all.
-        G = int(round((-1.0 + (1.0 + 24.0 * launches) ** 0.5) / 6.0))
-        launches = G * (G + 1) // 2
-        kern_ms = (float(np.mean(main_ms)) - float(np.mean(select_ms))) / launches
-    else:
-        kern_ms = float(np.mean(main_ms)) / launches
-    flop_per_launch = 2.0 * d * pairs_computed / launches
-    achieved = flop_per_launch / (kern_ms * 1e-3) / 1e12
+    schedule = {0: "", 1: "two-phase ", 2: "two-phase by panel pairs, "}[two_phase] + ("each pair once" if symmetric else "full square")
 
     out = {
         "metric": "pair-distances/sec incl. top-k",
@@ -146,22 +158,19 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "nq": nq, "nr": nr, "d": d, "k": k, "metric": w.metric,
-                   "schedule": ("two-phase " if two_phase else "") + ("triangle" if symmetric else "full-square"),
-                   "pairs_computed_per_step": pairs_computed,
-                   "fused_kernel_ms": float(np.mean(main_ms)),
+                   "value_counts": "pairs served, nq x nr; the pairs evaluated per step are pairs_computed_per_step",
+                   "schedule": schedule,
+                   "pairs_computed_per_step": t["pairs_computed"],
+                   "main_stage_ms": t["main_ms"],
+                   "workspace_bytes": t["workspace_bytes"],
                    "datagen_s": round(gen_s, 2)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                     "traffic": None, "kernel": ("knn_dist_qreg" if d <= 256 else "knn_dist_stream") if two_phase else "knn_pairs_qreg" if symmetric else "knn_tiles_qreg" if d <= 256 and args.variant in (0, 3) else "knn_tiles",
+                     "traffic": None, "kernel": t["kernel"],
                      "kernel_ms_per_launch": kern_ms, "launches_per_step": launches},
     }
-
-    if two_phase == 2:
-        out["config"]["schedule"] = "two-phase by panel pairs"
-        out["config"]["select_rows_ms"] = float(np.mean(select_ms))
-    if two_phase == 1:
-        out["config"]["select_rows_ms"] = float(np.mean(select_ms))
-        out["config"]["matrix_bytes"] = 4.0 * (float((nq + 127) // 128 * 128) * float((nr + 127) // 128 * 128 + 64))
+    if two_phase:
+        out["config"]["select_rows_ms"] = t["select_ms"]
 
     # the fp32 matrix rate this machine sustains (matrix instructions only, ~0.25 s), beside the nominal peak
     from paper_0906_0231_amd import knn_mfma_calibration
@@ -176,16 +185,35 @@ def main() -> int:
         valu_tops, _ = knn_valu_calibration(1 << 21, 4)
         out["roofline"].update({"bound": "alu", "peak": VALU_F32_PLAIN_TOPS,
                                 "frac": achieved / VALU_F32_PLAIN_TOPS,
-                                "kernel": "knn_fold_dist" if two_phase else "knn_fold",
+                                "unit": "1e12 lane operations/s",
                                 "peak_derivation": "256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz, one flop per "
                                                    "instruction (sub, add|.|): half the published FMA rate",
                                 "measured_peak": valu_tops,
                                 "frac_of_measured_peak": achieved / valu_tops})
 
-    tkey = (w.name, out["config"]["schedule"])
-    if tkey in MEASURED_TRAFFIC_BYTES_PER_STEP and args.variant in (0, 3, 4) and not args.block_rows:
-        out["roofline"]["traffic"] = MEASURED_TRAFFIC_BYTES_PER_STEP[tkey] / launches
-        out["roofline"]["traffic_unit"] = "bytes per launch (offline rocprofv3 FETCH_SIZE+WRITE_SIZE)"
+    tkey = (w.name, t["kernel"])
+    if tkey in OFFLINE_TRAFFIC_BYTES_PER_STEP and args.variant == 0 and not args.block_rows:
+        nbytes, source = OFFLINE_TRAFFIC_BYTES_PER_STEP[tkey]
+        out["roofline"]["traffic"] = nbytes / launches
+        out["roofline"]["traffic_source"] = ("bytes per launch, FETCH_SIZE + WRITE_SIZE, measured offline "
+                                             "(not by this run): " + source)
+
+    if args.fused_legs and two_phase and w.symmetric and w.metric not in ("l1", "linf"):
+        # The default plan keeps distances in the workspace between its two phases.  The fused plans
+        # (selection inside the distance kernel, nothing of the matrix stored) under the same clock:
+        # each pair once (the tournament of block pairs; d <= 256) and the full square.
+        legs = []
+        for sym in ((1, 2) if d <= 256 else (2,)):
+            f = time_plan(sym, 3, 0, 2, 1)
+            legs.append({"schedule": "fused, " + ("each pair once" if f["symmetric"] else "full square"),
+                         "kernel": f["kernel"], "ms_per_step": f["ms_per_step"],
+                         "value": pairs_served / (f["ms_per_step"] * 1e-3), "steps": 2, "warmup": 1,
+                         "kernel_ms_per_launch": f["kern_ms"], "launches_per_step": f["launches"],
+                         "achieved": f["achieved"], "frac": f["achieved"] / MFMA_F32_PEAK_TFLOPS,
+                         "pairs_computed_per_step": f["pairs_computed"], "workspace_bytes": f["workspace_bytes"]})
+        out["fused_plans"] = legs
+        # leave the default plan's answer in idx / dist for the parity check below
+        time_plan(args.symmetric, args.variant, args.block_rows, 1, 0)
 
     if not args.no_select:
         # Selection stage on its own (the paper's Phase 2 as stated in Sect. 6: rows of a
@@ -252,6 +280,12 @@ def main() -> int:
                                          f"(fp64 distances + full sort per row), {cpu_s:.1f} s"}
         out["parity"] = {"rows_checked": int(rep.rows), "ok": bool(rep.ok),
                          "max_rel_err": rep.max_rel_err, "rows_set_exempt": rep.rows_set_exempt}
+        if not rep.ok:
+            # a wrong answer has no throughput
+            out["value"] = None
+            out["parity"]["failures"] = rep.failures[:5]
+            print(json.dumps(out))
+            return 1
     print(json.dumps(out))
     return 0
 

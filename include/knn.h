@@ -7,10 +7,11 @@
  * non-decreasing order of distance, every reference left out being at least as
  * far as the k-th one listed.  It does so by brute force, as the paper does
  * (Sect. 4-6): a tiled all-pairs distance computation and a per-row selection
- * of the k smallest -- fused into one pass, so that no distance matrix is ever
- * stored, or, where that is cheaper on this device, as the paper's two phases
- * with the matrix (whole up to 72 GiB, else blocks of two row panels) kept in
- * the caller's workspace between them; see knn_options_t.variant.
+ * of the k smallest.  Two organisations exist (knn_plan_t): FUSED, one pass in
+ * which the selection runs on the distance tile while it is still in registers
+ * and no distance is ever stored; and TWO-PHASE, the paper's own organisation,
+ * which keeps distances in the caller's workspace between the two phases.  The
+ * library takes the faster one that fits the workspace it is given.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller; the library
@@ -28,6 +29,14 @@
  *     be a member of the reference set (Sect. 4: only pairs x > y are computed);
  *     exclusion is by row number, so another row with equal coordinates is an
  *     ordinary neighbour at distance 0.
+ *   - Which k references win is decided on single-precision values of the
+ *     expanded form (|r|^2 - 2 q.r for the squared Euclidean distance), whose
+ *     absolute error is a few 2^-24 (|q|^2 + |r|^2).  References whose true
+ *     distances to a query differ by less than that may be ranked either way;
+ *     for data far from the origin (all rows sharing a large offset) that band
+ *     is wide relative to the distances themselves: centre such data first
+ *     (subtracting one vector from every row changes no distance).  The
+ *     distances REPORTED are recomputed from the original rows in double.
  *   - NaN or infinite input values: behaviour undefined.
  */
 #ifndef KNN_H_
@@ -61,84 +70,68 @@ typedef enum {
 
 typedef enum {
     KNN_OK = 0,
-    KNN_EINVAL = 1,       /* null pointer, size out of range, k too large for the set */
-    KNN_EUNSUPPORTED = 2, /* k above KNN_MAX_K, or nr >= 2^31 */
-    KNN_ENOMEM = 3,       /* workspace smaller than knn_workspace_bytes() says */
+    KNN_EINVAL = 1,       /* null pointer, size or option out of range, k too large for the set */
+    KNN_EUNSUPPORTED = 2, /* k above KNN_MAX_K, nr >= 2^31, or a plan that cannot serve the call */
+    KNN_ENOMEM = 3,       /* workspace smaller than the smallest plan needs */
     KNN_EDEVICE = 4       /* a HIP call failed (no gfx950 device, launch error) */
 } knn_status_t;
 
 #define KNN_MAX_K 128
 
+/* How the two stages of the method (Sect. 5: distances, Sect. 6: k smallest per row) are run. */
+typedef enum {
+    KNN_PLAN_AUTO = 0,            /* the fastest plan whose workspace fits the one passed */
+    KNN_PLAN_FUSED_STREAMING = 1, /* fused; both operands staged through LDS; any d */
+    KNN_PLAN_FUSED = 3,           /* fused; query operands resident in registers (d <= 256,
+                                     else as 1).  Workspace about 4 n d + 8 n kcap bytes */
+    KNN_PLAN_TWO_PHASE = 4        /* distances written to the workspace, then selected from:
+                                     the whole matrix, or (knn_build, symmetric distance) two
+                                     blocks of block_rows^2 at a time, walked by pairs of row
+                                     panels; chunks of distances that can no longer enter a
+                                     row's list are then not stored */
+} knn_plan_t;
+
 /* Time spent by one call, filled in when knn_options_t.profile points here. */
 typedef struct {
     float ms_prepare;   /* row norms / scaled copies            (Sect. 5 prologue) */
-    float ms_main;      /* fused distance + selection kernel(s) (Sect. 5 and 6)    */
+    float ms_main;      /* distance + selection kernel(s)       (Sect. 5 and 6)    */
     float ms_finalize;  /* merge of partial lists, re-score, final order            */
     float ms_total;
     int32_t main_launches; /* kernel launches counted in ms_main */
-    int32_t symmetric;     /* 1 if each unordered pair of rows was evaluated once (triangle schedule,
-                              or the symmetric form of variant 4) */
+    int32_t symmetric;     /* 1 if each unordered pair of rows was evaluated once */
     int64_t pairs_computed;/* (query, reference) pairs whose distance was evaluated,
                               padding of ragged tiles included */
-    float ms_select;       /* two-phase plans: the part of ms_main not spent in the distance kernel (the
-                              selection from the matrix; block by block also the gaps between launches) */
-    int32_t two_phase;     /* 0: fused kernels.  1: variant 4, the matrix written out whole, then selected
-                              from.  2: variant 4 block by block (pairs of row panels) */
+    float ms_select;       /* two-phase plans: the part of ms_main not spent in the distance kernel */
+    int32_t two_phase;     /* 0: fused.  1: whole matrix.  2: by pairs of row panels */
 } knn_profile_t;
 
 /* Optional knobs; pass NULL for defaults.  Zero-initialise, then set fields. */
 typedef struct {
-    int32_t symmetric;  /* knn_build only.  0 = auto, 1 = force the triangle schedule
-                           (each unordered tile pair computed once, Sect. 3-4),
-                           2 = force the full square.  Auto (where variant 4 is not taken, see
-                           below) takes the triangle when n >= 65536 and a cost model of its rounds (fill of the device by the pairs of
-                           one round, fixed cost per pair, longer merges for k > 32) puts it
-                           below the full square */
-    int32_t rescore;    /* 0 = auto (on), 1 = on, 2 = off.
-                           On: the k reported distances of each query are recomputed
-                           from the original rows with double accumulation (a direct
-                           sum of squared differences, or 1 - cos from the three sums)
-                           so they do not carry the cancellation error of
-                           |u|^2+|v|^2-2u.v or of 1-cos in fp32.  Selection itself is
-                           always done on the fp32 matrix-core values */
-    int32_t r_splits;   /* 0 = auto.  Number of slices the reference range is cut
-                           into per query tile (partial lists are merged at the end) */
-    int32_t variant;    /* fused-kernel variant.  0 = auto (3 if d <= 256, else 1).
-                           1 = streaming: both operands through LDS chunk by chunk, any d.
-                           2 = query tile resident in LDS, 3 = query tile resident in
-                           registers; both need d <= 256 and fall back to 1 otherwise.
-                           4 = not fused: the paper's two phases as such (Sect. 5-6), the matrix
-                           of distances written to the workspace ([nq, nr] floats, padded to
-                           multiples of 128) and the k smallest per row selected from it;
-                           knn_build computes each unordered pair once unless symmetric == 2.
-                           Any d.  Auto takes it when that matrix is at most 72 GiB,
-                           symmetric != 1 and: k > 32; or knn_build (symmetric distance) with
-                           d > 96 or n <= 49152 (KNN_L1, KNN_LINF: d >= 64); or the matrix is
-                           at most 4 GiB.
-                           5 = as 3, and where the triangle schedule is used (symmetric) its
-                           lists start from the pairs inside super-blocks of 65536 rows, which
-                           are evaluated in the two-phase form first; the rounds then play only
-                           pairs of blocks from different super-blocks (r_splits > 0 here sets
-                           the blocks per super-block).  Never taken by auto: it gains 0.5-5 %
-                           at n = 2^20 and needs 17.7 GB more workspace.
-                           A larger matrix is never written out whole: knn_build
-                           with a symmetric distance walks it by pairs of row panels (auto: for
-                           KNN_L1 / KNN_LINF with d >= 64; on the matrix cores for d > 96),
-                           two blocks of 65536 x 65536 distances in the workspace; once a row has
-                           a full list, chunks of 32 distances that cannot enter it are not even
-                           stored (d <= 256).  Other calls stay fused */
-    int32_t block_rows; /* Fused symmetric schedule: rows per block; rounded up to a multiple
-                           of 128.  A round launches ceil(ceil(n/block_rows)/2) workgroups.
-                           0 = auto: the multiple of 128 for which the rounds fill the device's
-                           512 workgroup slots best (n/1024 when n is a power of two >= 2^17).
-                           With variant 4 and knn_build (symmetric distance): rows per panel of
-                           the block-by-block form, rounded up to a multiple of 256, which is then
-                           used whatever the size; 0 = auto (whole matrix up to 72 GiB, panels
-                           of 65536 rows beyond) */
+    int32_t symmetric;  /* knn_build only: 0 = auto, 1 = evaluate each unordered pair of rows once
+                           (Sect. 3-4; fused: a tournament of block pairs), 2 = the full square */
+    int32_t rescore;    /* 0 / 1 = report distances recomputed from the original rows with double
+                           accumulation; 2 = report the single-precision values selected on */
+    int32_t r_splits;   /* 0 = auto.  Fused plans: slices of the reference range per query tile,
+                           each with a partial list per query, merged at the end */
+    int32_t variant;    /* a knn_plan_t; KNN_PLAN_AUTO never fails for lack of workspace as long as
+                           the fused plan fits */
+    int32_t block_rows; /* 0 = auto.  Fused symmetric schedule: rows per block (multiple of 128).
+                           KNN_PLAN_TWO_PHASE with knn_build: rows per panel (multiple of 256),
+                           and the panel walk is used whatever the size */
     int32_t reserved;   /* must be 0 */
-    knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its
-                           kernels with events, waits for them and fills this in */
+    knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its kernels with
+                           events, waits for them and fills this in */
 } knn_options_t;
+
+/* What a call with these sizes, options and workspace size would do; see knn_plan(). */
+typedef struct {
+    int32_t plan;           /* the knn_plan_t taken */
+    int32_t symmetric;      /* 1: each unordered pair of rows evaluated once */
+    int32_t two_phase;      /* as knn_profile_t.two_phase */
+    int32_t main_launches;  /* kernel launches of the distance + selection stage */
+    uint64_t workspace_bytes; /* what this plan needs */
+    char kernel[32];        /* name of the kernel that does the distance arithmetic */
+} knn_plan_info_t;
 
 /*
  * All-pairs self kNN (Sect. 3): neighbours of every row of X among the other
@@ -146,6 +139,12 @@ typedef struct {
  *   X    [n, d]  device, read only
  *   idx  [n, k]  device, int32, out
  *   dist [n, k]  device, fp32, out, ascending per row
+ *   workspace    device, 256-byte aligned, uninitialised; garbage afterwards.
+ *                With default options: the plan is the fastest one that fits
+ *                workspace_bytes.  knn_workspace_bytes() is what the preferred plan
+ *                wants (it may hold distances: up to 72 GiB, 37 GB at n = 2^20),
+ *                knn_workspace_bytes_min() what the fused plan needs; anything in
+ *                between works, less is KNN_ENOMEM.
  * Requires 2 <= n < 2^31, 1 <= d, 1 <= k <= min(n-1, KNN_MAX_K).
  */
 knn_status_t knn_build(const float *X, int64_t n, int32_t d, int32_t k, knn_metric_t metric,
@@ -165,6 +164,7 @@ knn_status_t knn_build_ex(const float *X, int64_t n, int32_t d, int32_t k, knn_m
  *   self_offset >= 0: query i IS reference row self_offset + i and that pair is
  *                     skipped (requires self_offset + nq <= nr); -1: no such relation.
  *   idx [nq, k], dist [nq, k]  device, out
+ *   workspace: as for knn_build.
  * Requires 1 <= nq, 1 <= nr < 2^31, 1 <= k <= min(nr - (self_offset >= 0), KNN_MAX_K).
  */
 knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
@@ -179,22 +179,31 @@ knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t n
                            const knn_options_t *opt);
 
 /*
- * Bytes of device workspace a call with these sizes and default options needs;
- * 0 if the sizes are invalid.  `symmetric` != 0 asks
- * for knn_build (nq is ignored, nr = n), 0 for knn_search.  The workspace must be
- * 256-byte aligned; its contents need not be initialised and are garbage after.
- * Where the default plan writes the distance matrix out this is its size and more
- * (up to 72 GiB; 35 GB for the two blocks of a larger one); a caller who cannot
- * spare that asks for variant 3 through
- * knn_workspace_bytes_ex and the _ex entry points (copies of the inputs and the
- * lists only: about 4 n d + 8 n kcap bytes).
+ * Bytes of device workspace the PREFERRED plan of a call with these sizes and default
+ * options wants; 0 if the sizes are invalid.  `symmetric` != 0 asks for knn_build (nq is
+ * ignored, nr = n), 0 for knn_search.
  */
 size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
                            int32_t symmetric);
 
-/* Same, for a given option block (a forced r_splits changes the partial-list area). */
+/* Same, for a given option block; 0 also if an option is out of range. */
 size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
                               int32_t symmetric, const knn_options_t *opt);
+
+/* The smallest workspace with which a call with default options succeeds (the fused plan's:
+   scaled copies of the inputs and the lists). */
+size_t knn_workspace_bytes_min(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                               int32_t symmetric);
+
+/*
+ * The plan a call with these sizes and options would take if given a workspace of
+ * `workspace_bytes` (SIZE_MAX: no limit), without running anything: `out` is a HOST
+ * pointer.  KNN_ENOMEM if no plan fits, otherwise the status the call itself would
+ * return for these sizes and options.
+ */
+knn_status_t knn_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                      int32_t symmetric, const knn_options_t *opt, size_t workspace_bytes,
+                      knn_plan_info_t *out);
 
 /*
  * Batched partial sort of a matrix that already exists in memory: the paper's Phase 2 as

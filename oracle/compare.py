@@ -14,6 +14,12 @@ queries.  The rule:
   exchanged for other references inside that same band (fp32 cannot resolve
   them); the number of rows that needed this exemption is reported.
 
+``band_atol`` (default: ``atol``) is an absolute floor for the tie band ALONE, for distances
+that can be zero or negative while their terms are not (Kullback-Leibler on un-normalised
+rows): there a band relative to the k-th distance is meaningless, and the floor is derived
+from the size of the terms summed (see the test that passes it).  It never loosens the check
+of the reported distances.
+
 ``strict_ties=True`` drops the exemptions and demands the oracle's exact index
 lists (used where the arithmetic is exact and ties go to the lower index).
 """
@@ -33,10 +39,12 @@ class Report:
     max_rel_err: float = 0.0
     rows_set_exempt: int = 0      # rows whose set differs only inside the tie band
     rows_order_exempt: int = 0    # rows listing a near-tie pair in the other order
+    rows_failed: int = 0          # failures counted (the messages kept are capped)
     failures: list = field(default_factory=list)
 
     def fail(self, msg: str) -> None:
         self.ok = False
+        self.rows_failed += 1
         if len(self.failures) < 20:
             self.failures.append(msg)
 
@@ -47,7 +55,8 @@ class Report:
 
 
 def check(Q, R, metric, o_idx, o_dist, o_next, g_idx, g_dist, self_idx=None,
-          rtol: float = 1e-5, atol: float = 0.0, strict_ties: bool = False) -> Report:
+          rtol: float = 1e-5, atol: float = 0.0, strict_ties: bool = False,
+          band_atol=None) -> Report:
     """Compare a candidate answer (g_*) with the oracle's (o_*) row by row."""
     o_idx = np.asarray(o_idx)
     o_dist = np.asarray(o_dist, dtype=np.float64)
@@ -55,6 +64,8 @@ def check(Q, R, metric, o_idx, o_dist, o_next, g_idx, g_dist, self_idx=None,
     g_dist = np.asarray(g_dist, dtype=np.float64)
     nq, k = o_idx.shape
     rep = Report(rows=nq)
+    if band_atol is None:
+        band_atol = atol
     if g_idx.shape != (nq, k) or g_dist.shape != (nq, k):
         rep.fail(f"shape mismatch: got {g_idx.shape}/{g_dist.shape}, want {(nq, k)}")
         return rep
@@ -71,7 +82,7 @@ def check(Q, R, metric, o_idx, o_dist, o_next, g_idx, g_dist, self_idx=None,
         rel = np.where(true_d != 0, err / np.abs(true_d), 0.0)
     rep.max_rel_err = float(np.max(np.where(err <= atol, 0.0, rel))) if rel.size else 0.0
     bad = np.argwhere(~(err <= tol))
-    for b in bad[:5]:
+    for b in bad:
         rep.fail(f"row {b[0]} rank {b[1]} idx {g_idx[tuple(b)]}: dist {g_dist[tuple(b)]!r} "
                  f"vs oracle {true_d[tuple(b)]!r}")
 
@@ -91,11 +102,11 @@ def check(Q, R, metric, o_idx, o_dist, o_next, g_idx, g_dist, self_idx=None,
             continue
         td = true_d[i]
         dk = o_dist[i, k - 1]
-        band = rtol * abs(dk) + atol
+        band = rtol * abs(dk) + band_atol
         # order: true distances non-decreasing up to the tolerance
         steps = td[1:] - td[:-1]
-        if np.any(steps < -(rtol * np.abs(td[:-1]) + atol)):
-            r = int(np.argmax(steps < -(rtol * np.abs(td[:-1]) + atol)))
+        if np.any(steps < -(rtol * np.abs(td[:-1]) + band_atol)):
+            r = int(np.argmax(steps < -(rtol * np.abs(td[:-1]) + band_atol)))
             rep.fail(f"row {i}: order broken at rank {r}: {td[r]!r} then {td[r + 1]!r}")
             continue
         if np.any(steps < 0):

@@ -28,8 +28,12 @@ KNN_MAX_K = 128
 METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KNN_HELLINGER,
            "l1": KNN_L1, "linf": KNN_LINF, "kl": KNN_KL}
 
+PLAN_AUTO, PLAN_FUSED_STREAMING, PLAN_FUSED, PLAN_TWO_PHASE = 0, 1, 3, 4
+NO_LIMIT = ctypes.c_size_t(-1).value      # knn_plan: "whatever workspace the preferred plan wants"
+
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
-           "knn_workspace_bytes_ex", "knn_select", "knn_select_workspace_bytes",
+           "knn_workspace_bytes_ex", "knn_workspace_bytes_min", "knn_plan", "knn_select",
+           "knn_select_workspace_bytes",
            "knn_mfma_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
            "knn_last_device_error"]
 
@@ -47,6 +51,17 @@ class KnnOptions(ctypes.Structure):
                 ("r_splits", ctypes.c_int32), ("variant", ctypes.c_int32),
                 ("block_rows", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("profile", ctypes.POINTER(KnnProfile))]
+
+
+class KnnPlanInfo(ctypes.Structure):
+    _fields_ = [("plan", ctypes.c_int32), ("symmetric", ctypes.c_int32), ("two_phase", ctypes.c_int32),
+                ("main_launches", ctypes.c_int32), ("workspace_bytes", ctypes.c_uint64),
+                ("kernel", ctypes.c_char * 32)]
+
+    def __repr__(self) -> str:
+        return (f"KnnPlanInfo(plan={self.plan}, symmetric={self.symmetric}, two_phase={self.two_phase}, "
+                f"main_launches={self.main_launches}, workspace_bytes={self.workspace_bytes}, "
+                f"kernel={self.kernel.decode()!r})")
 
 
 class KnnError(RuntimeError):
@@ -82,6 +97,10 @@ def load_library() -> ctypes.CDLL:
     lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
     lib.knn_workspace_bytes_ex.restype = sz
     lib.knn_workspace_bytes_ex.argtypes = [i64, i64, i32, i32, i32, i32, optp]
+    lib.knn_workspace_bytes_min.restype = sz
+    lib.knn_workspace_bytes_min.argtypes = [i64, i64, i32, i32, i32, i32]
+    lib.knn_plan.restype = i32
+    lib.knn_plan.argtypes = [i64, i64, i32, i32, i32, i32, optp, sz, ctypes.POINTER(KnnPlanInfo)]
     lib.knn_select.restype = i32
     lib.knn_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
     lib.knn_select_workspace_bytes.restype = sz
@@ -145,19 +164,44 @@ def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
                                           ctypes.byref(opt)))
 
 
+def knn_workspace_bytes_min(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
+                            symmetric: bool = False) -> int:
+    """Smallest workspace with which a call with default options succeeds (the fused plan's)."""
+    return int(load_library().knn_workspace_bytes_min(nq, nr, d, k, _metric(metric), int(symmetric)))
+
+
+def knn_plan(nq: int, nr: int, d: int, k: int, metric="sqeuclidean", symmetric: bool = False, *,
+             workspace_bytes: int = NO_LIMIT, r_splits: int = 0, variant: int = 0, schedule: int = 0,
+             block_rows: int = 0) -> KnnPlanInfo:
+    """What knn_build (symmetric=True) or knn_search with these sizes and options would do if
+    given a workspace of `workspace_bytes`; see knn_plan in knn.h."""
+    lib = load_library()
+    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows)
+    info = KnnPlanInfo()
+    _check(lib.knn_plan(nq, nr, d, k, _metric(metric), int(symmetric), ctypes.byref(opt), workspace_bytes,
+                        ctypes.byref(info)))
+    return info
+
+
 def _own_workspace(lib, opt, nq, nr, d, k, metric, self_flag, device) -> torch.Tensor:
-    """Workspace for a call that brought none.  The default plan may want the whole distance
-    matrix (up to 72 GiB); if the device cannot spare that, the fused plan, which needs none, is
-    requested instead (opt.variant is changed accordingly)."""
+    """Workspace for a call that brought none: what the preferred plan wants (it may hold
+    distances, up to 72 GiB) or, if the device cannot spare that, what the fused plan needs.
+    The library takes its plan from the size it is handed; KnnResult.plan says which ran."""
     nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), self_flag, ctypes.byref(opt)))
     try:
         return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
     except torch.cuda.OutOfMemoryError:
         if opt.variant != 0:
             raise
-        opt.variant = 3
-        nbytes = int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), self_flag, ctypes.byref(opt)))
+        nbytes = int(lib.knn_workspace_bytes_min(nq, nr, d, k, _metric(metric), self_flag))
         return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _plan_of(lib, opt, nq, nr, d, k, metric, self_flag, workspace) -> KnnPlanInfo:
+    info = KnnPlanInfo()
+    _check(lib.knn_plan(nq, nr, d, k, _metric(metric), self_flag, ctypes.byref(opt), workspace.numel(),
+                        ctypes.byref(info)))
+    return info
 
 
 @dataclass
@@ -165,6 +209,7 @@ class KnnResult:
     idx: torch.Tensor                 # [nq, k] int32
     dist: torch.Tensor                # [nq, k] fp32, ascending
     profile: Optional[KnnProfile] = None
+    plan: Optional[KnnPlanInfo] = None  # the plan the library took for this call
 
 
 def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int = 0,
@@ -186,7 +231,8 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
         _check(lib.knn_build_ex(X.data_ptr(), n, d, k, _metric(metric), idx.data_ptr(),
                                 dist.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                 stream, ctypes.byref(opt)))
-    return KnnResult(idx, dist, prof)
+        plan = _plan_of(lib, opt, n, n, d, k, metric, 1, workspace)
+    return KnnResult(idx, dist, prof, plan)
 
 
 def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
@@ -213,7 +259,8 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
                                  self_offset, idx.data_ptr(), dist.data_ptr(),
                                  workspace.data_ptr(), workspace.numel(), stream,
                                  ctypes.byref(opt)))
-    return KnnResult(idx, dist, prof)
+        plan = _plan_of(lib, opt, nq, nr, d, k, metric, 0, workspace)
+    return KnnResult(idx, dist, prof, plan)
 
 
 def knn_select(A: torch.Tensor, k: int, *, workspace: Optional[torch.Tensor] = None,

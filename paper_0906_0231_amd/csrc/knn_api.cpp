@@ -33,13 +33,9 @@ struct Plan {
     int64_t nq_pad, n_cpad;
     bool self;      // knn_build: one matrix serves as queries and references
     bool rcopy;     // references need a scaled / padded copy
-    bool qres;      // query tile resident in LDS (knn_tiles_qres): two lists per slice
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
-    bool warm;      // symmetric schedule whose lists start from the pairs inside super-blocks, evaluated
-                    // in two-phase form; the tournament then plays pairs of different super-blocks only
-    int32_t sb, nsbp; // ... blocks per super-block, number of super-blocks rounded up to even
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     bool matrix;    // two-phase organisation: distance matrix written out (knn_dist_qreg), then select_rows
     bool msym;      // ... computing each unordered pair of rows once
@@ -153,13 +149,11 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.blocked = false;
     p.mstream = false;
     p.P = 0;
-    p.warm = false;
-    p.sb = p.nsbp = 0;
     if (p.fold) {
         // lane = query, 64 per wave; the reference range is cut so that the device has
         // several thousand waves to run
         p.dpad = (int32_t)align_up((size_t)d, 4);
-        p.qreg = p.qres = p.tri = false;
+        p.qreg = p.tri = false;
         p.rcopy = true;
         p.kcap = list_capacity(k);
         p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
@@ -246,14 +240,13 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     }
     p.dpad = (int32_t)align_up((size_t)d, KNN_DC);
     const int32_t dpad32 = (int32_t)align_up((size_t)d, 32);
-    p.qreg = (variant == 0 || variant == 3 || variant == 5) && dpad32 <= KNN_QRES_MAX_D;
+    p.qreg = (variant == 0 || variant == 3) && dpad32 <= KNN_QRES_MAX_D;
     if (p.qreg) p.dpad = dpad32;
     p.kcap = list_capacity(k);
     p.n_qtiles = (int32_t)((nq + KNN_TILE - 1) / KNN_TILE);
     p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
     p.nq_pad = (int64_t)p.n_qtiles * KNN_TILE;
     p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
-    p.qres = variant == 2 && p.dpad <= KNN_QRES_MAX_D;
     // symmetric schedule: only for knn_build, only with the register-resident kernel;
     // by default only where the cost model puts it below the full square
     p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr, p.kcap);
@@ -289,7 +282,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     if (p.matrix) {
         p.mstream = dpad32 > KNN_QRES_MAX_D;       // p.dpad stays d rounded up to KNN_DC then
         if (!p.mstream) p.dpad = dpad32;
-        p.qreg = p.qres = p.tri = false;
+        p.qreg = p.tri = false;
         p.msym = msym;
         const int32_t tr = p.mstream ? KNN_TILE : 64;              // reference rows per tile of the distance kernel
         p.n_rt64 = (int32_t)((nr + tr - 1) / tr);
@@ -336,8 +329,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.total = o;
         return true;
     }
-    const int32_t per_slice = p.qres ? 2 : 1;
-    int32_t smax = KNN_FIN_MAX / (p.kcap * per_slice);
+    int32_t smax = KNN_FIN_MAX / p.kcap;
     if (smax > p.n_rtiles) smax = p.n_rtiles;
     int32_t S = r_splits;
     if (S <= 0) {
@@ -367,33 +359,9 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     if (S > smax) S = smax;
     if (S < 1) S = 1;
     if (p.tri) S = 1;
-    // Warm start of the symmetric schedule: on request only (variant 5; r_splits then gives the
-    // blocks per super-block).  Measured at n = 2^20, d = 256: 2487 -> 2474 ms for k = 10, 3193 ->
-    // 3044 ms for k = 100 -- the rounds stay slower than their floor long after the lists hold the
-    // best of 65 536 candidates -- which does not pay for 17.7 GB more workspace by default.
-    if (p.tri && variant == 5) {
-        int32_t sb = variant == 5 && r_splits > 0 ? r_splits : 65536 / p.B;
-        if (sb < 1) sb = 1;
-        const int32_t nsb = (p.NB + sb - 1) / sb;
-        if (nsb >= 2) {
-            p.warm = true;
-            p.sb = sb;
-            p.nsbp = nsb + (nsb & 1);
-            p.blocked = true;                     // run_two_phase walks panels of p.P rows
-            p.msym = true;
-            p.P = (int64_t)sb * p.B;
-            p.ldd = p.P + 64;
-            p.ldm = (p.ldd / 32 + 15) / 16 * 16;
-            const int64_t tiles = (p.P / KNN_TILE) * (p.P / 64) / 2;
-            int64_t chunk = (tiles + 1023) / 1024;
-            if (chunk < 4) chunk = 4;
-            if (chunk > 64) chunk = 64;
-            p.chunk = (int32_t)chunk;
-        }
-    }
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
-    p.nlists = p.S * per_slice;
+    p.nlists = p.S;
     p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
 
     size_t o = 0;
@@ -407,12 +375,6 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;   // + one scalar (max c_j)
     p.off_bound = o;                                 // one word per query: bound shared by the slices
     o = align_up(o + (size_t)nq * sizeof(uint32_t), 256);
-    if (p.warm) {
-        p.off_D = p.off_D2 = o;
-        o = align_up(o + (size_t)p.P * p.ldd * sizeof(float), 256);
-        p.off_M = p.off_M2 = o;
-        o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
-    }
     p.off_lists = o;
     o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
@@ -431,6 +393,52 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
     if (d > (1 << 20)) return KNN_EUNSUPPORTED;
     if (k > KNN_MAX_K) return KNN_EUNSUPPORTED;
     return KNN_OK;
+}
+
+
+knn_status_t check_options(const knn_options_t &o)
+{
+    if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
+        o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
+        return KNN_EINVAL;
+    if (o.variant != KNN_PLAN_AUTO && o.variant != KNN_PLAN_FUSED_STREAMING && o.variant != KNN_PLAN_FUSED &&
+        o.variant != KNN_PLAN_TWO_PHASE)
+        return KNN_EINVAL;
+    return KNN_OK;
+}
+
+// The plan of a call.  A plan named in the options is taken as such.  KNN_PLAN_AUTO takes the
+// preferred plan (make_plan's choice, which may keep distances in the workspace) if it fits in
+// `budget` bytes, else the fused plan, which needs only copies of the inputs and the lists.
+// KNN_ENOMEM if even that does not fit.  Sizes and options are assumed validated.
+knn_status_t choose_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
+                         const knn_options_t &o, size_t budget, Plan &p)
+{
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
+    if (p.total <= budget) return KNN_OK;
+    if (o.variant != KNN_PLAN_AUTO || !p.matrix) return KNN_ENOMEM;
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, KNN_PLAN_FUSED, o.symmetric, o.block_rows, p);
+    return p.total <= budget ? KNN_OK : KNN_ENOMEM;
+}
+
+// kernel launches of the distance + selection stage
+int32_t plan_launches(const Plan &p, int64_t nr)
+{
+    if (p.matrix && p.blocked) {
+        const int64_t G = (nr + p.P - 1) / p.P;
+        return (int32_t)(G * (G + 1) / 2 + G * G);          // one block per panel pair, one selection per block and side
+    }
+    if (p.matrix) return 2;
+    if (p.tri) return p.NBp;                                // the diagonal blocks, then NBp - 1 rounds
+    return 1;
+}
+
+const char *plan_kernel(const Plan &p)
+{
+    if (p.fold) return p.matrix ? "knn_fold_dist" : "knn_fold";
+    if (p.matrix) return p.mstream ? "knn_dist_stream" : "knn_dist_qreg";
+    if (p.tri) return "knn_pairs_qreg";
+    return p.qreg ? "knn_tiles_qreg" : "knn_tiles";
 }
 
 struct Events {
@@ -481,12 +489,11 @@ struct Events {
 // (all of it, or the triangle mirrored) and one of select_rows.  Blocked (the matrix would not
 // fit): the rows are cut into panels of p.P; for every unordered pair of panels (a, b) the block
 // D[a][b] is written once, together with its transpose if a != b, and select_rows continues the
-// lists of the rows of a (and of b) with the columns of that block.  diag_only: only the blocks
-// (a, a) -- the warm start of the fused symmetric schedule.
+// lists of the rows of a (and of b) with the columns of that block.
 knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
                            int32_t k, knn_metric_t metric, int64_t self_offset, float *qp, float *rp, float *cr,
                            u64 *lists, char *ws, hipStream_t stream, Events &ev, int32_t &launches,
-                           int64_t &pairs_computed, bool diag_only = false)
+                           int64_t &pairs_computed)
 {
     (void)Q;
     float *D0 = (float *)(ws + p.off_D);
@@ -601,10 +608,10 @@ knn_status_t run_two_phase(const Plan &p, const float *Q, int64_t nq, const floa
     const int64_t seg = (p.P + 1023) / 1024 * 1024;
     for (int64_t a = 0; a < G; ++a) {
         const int64_t q0 = a * p.P, mq = nr - q0 < p.P ? nr - q0 : p.P;
-        for (int64_t b = a; b < (diag_only ? a + 1 : G); ++b) {
+        for (int64_t b = a; b < G; ++b) {
             const int64_t r0 = b * p.P, mr = nr - r0 < p.P ? nr - r0 : p.P;
             // rows of panel a were first seen in block (0, a) (mirrored) or, for a = 0, right here
-            const bool seen_a = !diag_only && !(a == 0 && b == 0), seen_b = !diag_only && a != 0;
+            const bool seen_a = !(a == 0 && b == 0), seen_b = a != 0;
             ev.bracket(stream);
             e = dist(q0, mq, r0, mr, a == b ? DIST_TRIANGLE : DIST_RECT_MIRROR, a == b ? 0 : -1, seen_a, seen_b);
             ev.bracket(stream);
@@ -633,14 +640,13 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     knn_options_t o;
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
-    if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
-        o.variant < 0 || o.variant > 5 || o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
-        return KNN_EINVAL;
+    st = check_options(o);
+    if (st != KNN_OK) return st;
+    if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
 
     Plan p;
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
-    if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
-    if (workspace_bytes < p.total) return KNN_ENOMEM;
+    st = choose_plan(nq, nr, d, k, metric, self, o, workspace_bytes, p);
+    if (st != KNN_OK) return st;
 
     hipStream_t stream = (hipStream_t)stream_v;
     char *ws = (char *)workspace;
@@ -732,36 +738,15 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pa.B = p.B;
         pa.NB = p.NB;
         pa.NBp = p.NBp;
-        pa.sb_blocks = 0;
-        pa.nsbp = 0;
-        if (p.warm) {
-            // the pairs inside each super-block first, in two-phase form: every list starts the
-            // tournament with the k best of p.P candidates instead of the B of its own block
-            int32_t l0 = 0;
-            int64_t pc0 = 0;
-            st = run_two_phase(p, Q, nq, R, nr, d, k, metric, self_offset, qp, rp, cr, lists, ws, stream, ev, l0,
-                               pc0, true);
-            if (st != KNN_OK) return st;
-            pa.sb_blocks = p.sb;
-            pa.nsbp = p.nsbp;
-            for (int32_t s = 0; s + 1 < p.nsbp; ++s)
-                for (int32_t r = 0; r < p.sb; ++r) {
-                    pa.round = s * p.sb + r;
-                    e = launch_pairs_qreg(pa, (p.nsbp / 2) * p.sb, stream);
-                    if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
-                }
-            launches = l0 + (p.nsbp - 1) * p.sb;
-        } else {
-            pa.round = -1;
-            e = launch_pairs_qreg(pa, p.NB, stream);
-            if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
-            for (int32_t r = 0; r + 1 < p.NBp; ++r) {
-                pa.round = r;
-                e = launch_pairs_qreg(pa, p.NBp / 2, stream);
-                if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
-            }
-            launches = p.NBp;
+        pa.round = -1;
+        e = launch_pairs_qreg(pa, p.NB, stream);
+        if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
+        for (int32_t r = 0; r + 1 < p.NBp; ++r) {
+            pa.round = r;
+            e = launch_pairs_qreg(pa, p.NBp / 2, stream);
+            if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
         }
+        launches = p.NBp;
         // padded rows actually contracted: queries in tiles of 128, references in tiles of 64
         const int64_t last = nr - (int64_t)(p.NB - 1) * p.B;
         const int64_t lq = (last + KNN_TILE - 1) / KNN_TILE * KNN_TILE, lr = (last + 63) / 64 * 64;
@@ -791,9 +776,9 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         t.n_rtiles = p.n_rtiles;
         t.S = p.S;
         t.rt_per_split = p.rt_per_split;
-        e = p.qreg ? launch_tiles_qreg(t, stream) : p.qres ? launch_tiles_qres(t, stream) : launch_tiles(t, stream);
+        e = p.qreg ? launch_tiles_qreg(t, stream) : launch_tiles(t, stream);
         if (e != hipSuccess) {
-            set_error(p.qreg ? "knn_tiles_qreg" : p.qres ? "knn_tiles_qres" : "knn_tiles", e);
+            set_error(p.qreg ? "knn_tiles_qreg" : "knn_tiles", e);
             return KNN_EDEVICE;
         }
     }
@@ -950,10 +935,51 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     if (symmetric) nq = nr;
     if (symmetric && nr < 2) return 0;
     if (check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1) != KNN_OK) return 0;
+    knn_options_t o;
+    memset(&o, 0, sizeof(o));
+    if (opt) o = *opt;
+    if (check_options(o) != KNN_OK) return 0;
     Plan p;
-    make_plan(nq, nr, d, k, metric, symmetric != 0, opt ? opt->r_splits : 0, opt ? opt->variant : 0,
-              opt ? opt->symmetric : 0, opt ? opt->block_rows : 0, p);
+    make_plan(nq, nr, d, k, metric, symmetric != 0, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
     return p.total;
+}
+
+size_t knn_workspace_bytes_min(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
+                               int32_t symmetric)
+{
+    knn_options_t o;
+    memset(&o, 0, sizeof(o));
+    o.variant = KNN_PLAN_FUSED;
+    return knn_workspace_bytes_ex(nq, nr, d, k, metric, symmetric, &o);
+}
+
+knn_status_t knn_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, int32_t symmetric,
+                      const knn_options_t *opt, size_t workspace_bytes, knn_plan_info_t *out)
+{
+    if (!out) return KNN_EINVAL;
+    if (symmetric) nq = nr;
+    if (symmetric && nr < 2) return KNN_EINVAL;
+    knn_status_t st = check_sizes(nq, nr, d, k, metric, symmetric ? 0 : -1);
+    if (st != KNN_OK) return st;
+    knn_options_t o;
+    memset(&o, 0, sizeof(o));
+    if (opt) o = *opt;
+    st = check_options(o);
+    if (st != KNN_OK) return st;
+    Plan p;
+    st = choose_plan(nq, nr, d, k, metric, symmetric != 0, o, workspace_bytes, p);
+    if (st != KNN_OK) return st;
+    memset(out, 0, sizeof(*out));
+    out->plan = p.matrix ? KNN_PLAN_TWO_PHASE : (p.qreg || p.fold) ? KNN_PLAN_FUSED : KNN_PLAN_FUSED_STREAMING;
+    out->symmetric = (p.tri || p.msym) ? 1 : 0;
+    out->two_phase = p.matrix ? (p.blocked ? 2 : 1) : 0;
+    out->main_launches = plan_launches(p, nr);
+    out->workspace_bytes = p.total;
+    const char *name = plan_kernel(p);
+    size_t i = 0;
+    for (; name[i] && i + 1 < sizeof(out->kernel); ++i) out->kernel[i] = name[i];
+    out->kernel[i] = 0;
+    return KNN_OK;
 }
 
 size_t knn_workspace_bytes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,

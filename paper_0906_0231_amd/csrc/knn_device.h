@@ -11,7 +11,7 @@
 #endif
 #define KNN_MAX_KCAP 128   // largest list capacity (>= KNN_MAX_K of the ABI)
 #define KNN_FIN_MAX 2048   // most keys per query finalize_rows can merge (S * kcap)
-#define KNN_QRES_MAX_D 256 // largest padded d whose query tile is kept resident in LDS
+#define KNN_QRES_MAX_D 256 // largest padded d whose query operands are kept resident in registers
 #define KNN_TILE 128       // queries per workgroup tile == references per tile
 #ifndef KNN_FOLD_NR
 #define KNN_FOLD_NR 64      // fold kernel: references per tile (accumulators per lane), multiple of 16
@@ -130,10 +130,7 @@ struct PairArgs {
     int32_t B;         // rows per block, multiple of 128
     int32_t NB;        // number of blocks
     int32_t NBp;       // NB rounded up to even
-    int32_t round;     // 0 .. NBp-2, or -1; with sb_blocks > 0: super-round * sb_blocks + shift
-    int32_t sb_blocks; // 0: every pair of blocks is played.  > 0: blocks per super-block; only pairs of
-                       // blocks from different super-blocks are played (see knn_pairs_qreg)
-    int32_t nsbp;      // number of super-blocks rounded up to even
+    int32_t round;     // 0 .. NBp-2, or -1
 };
 
 enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3, FIN_SELECT = 4, FIN_RESCORE_HEL = 5,
@@ -175,7 +172,6 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
-hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream);   // writes 2*S lists per query
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*
 hipError_t launch_dist_stream(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);    // any dpad (multiple of KNN_DC); n_rt, chunk in tiles of 128 rows   // dpad: multiple of 32, <= 256

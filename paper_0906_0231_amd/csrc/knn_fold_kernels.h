@@ -86,7 +86,6 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(64 * FOL
     st.Lw = Lw;
     st.cq = &s_cq[w][0][0];
     st.cnt = &s_cnt[w][0];
-    st.shared_tau = nullptr;
     st.mine = 0;
 
     const int64_t j_begin = (int64_t)split * a.refs_per_split;

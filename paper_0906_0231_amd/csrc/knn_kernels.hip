@@ -91,30 +91,6 @@ hipError_t launch_tiles(const TileArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-size_t qres_lds_bytes(int dpad)
-{
-    return (size_t)TQ * (dpad + 4) * 4 + 4 * QR_RBUF * 4 + 4 * QR_HALF * 4 + 8 * 32 * QR_QCAP * 8 +
-           4 * 32 * 8 + 8 * 32 * 4 + 16;
-}
-
-hipError_t launch_tiles_qres(const TileArgs &a, hipStream_t stream)
-{
-    static thread_local int configured_dev = -1;
-    size_t lds = qres_lds_bytes(a.dpad);
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (configured_dev != dev) {
-        e = hipFuncSetAttribute((const void *)knn_tiles_qres, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)qres_lds_bytes(KNN_QRES_MAX_D));
-        if (e != hipSuccess) return e;
-        configured_dev = dev;
-    }
-    int64_t blocks = (int64_t)a.n_qtiles * a.S;
-    hipLaunchKernelGGL(knn_tiles_qres, dim3((unsigned)blocks), dim3(512), lds, stream, a);
-    return hipGetLastError();
-}
-
 template <bool SHARE>
 static hipError_t launch_tiles_qreg_t(const TileArgs &a, hipStream_t stream)
 {

@@ -81,26 +81,6 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
     const bool diag = a.round < 0;
     if (diag) {
         ba = bb = blockIdx.x;
-    } else if (a.sb_blocks > 0) {
-        // Pairs of blocks from DIFFERENT super-blocks only (the pairs inside a super-block were
-        // evaluated beforehand, see the host).  The super-blocks play a round-robin tournament
-        // (circle method over a.nsbp of them); a launch is one super-round s and one shift r:
-        // super-pair (SA, SB) contributes the pairs (SA*sb + i, SB*sb + (i + r) mod sb),
-        // i < sb, which are disjoint, and r = 0 .. sb-1 covers every cross pair once.
-        const int sb = a.sb_blocks;
-        const int s = a.round / sb, r = a.round - s * sb;
-        const int sp = blockIdx.x / sb, i = blockIdx.x - sp * sb;
-        const int M = a.nsbp;
-        int SA, SB;
-        if (sp == 0) {
-            SA = M - 1;
-            SB = s;
-        } else {
-            SA = (s + sp) % (M - 1);
-            SB = (s - sp + (M - 1)) % (M - 1);
-        }
-        ba = SA * sb + i;
-        bb = SB * sb + (i + r) % sb;
     } else {
         const int M = a.NBp, p = blockIdx.x;       // circle method: M even, rounds 0..M-2
         if (p == 0) {
@@ -182,7 +162,6 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
             st.Lw = a.lists + (qbase + 32 * w) * a.kcap;
             st.cq = &sm.cq[w][0][0];
             st.cnt = &sm.cnt[w][0];
-            st.shared_tau = nullptr;
             st.mine = 0;
             return st;
         };

@@ -185,7 +185,6 @@ struct SelState {
     u64 *Lw;          // the wave's 32 lists in global memory, kcap entries each
     u64 *cq;          // the wave's candidate queues in LDS: [32][QCAP]
     uint32_t *cnt;    // their fill counts: [32]
-    u64 *shared_tau;  // LDS [32]: bound shared with the other waves serving the same queries, or null
     uint32_t mine;    // QPW == 64 only: fill count of the lane's own queue (no other lane appends to it)
 };
 
@@ -227,7 +226,6 @@ __device__ __forceinline__ void merge_queues(SelState &st, int kcap, int k, int 
         if (due) st.mine = 0;
     } else if (lane < 32) {
         if ((pend >> lane) & 1ull) st.cnt[lane] = 0;
-        if (st.shared_tau) atomicMin(&st.shared_tau[lane], st.tau_key);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }

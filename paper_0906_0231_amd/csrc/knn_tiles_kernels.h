@@ -1,6 +1,6 @@
 // The fused distance + selection kernels of the full-square schedule on the fp32 matrix cores
-// (paper Sect. 5 and 6 in one pass): knn_tiles (streaming, any d), knn_tiles_qres (query tile in
-// LDS), knn_tiles_qreg (query operands in registers).  Included by knn_kernels.hip only.
+// (paper Sect. 5 and 6 in one pass): knn_tiles (streaming, any d) and knn_tiles_qreg (query
+// operands in registers, d <= 256).  Included by knn_kernels.hip only.
 #ifndef KNN_TILES_KERNELS_H_
 #define KNN_TILES_KERNELS_H_
 
@@ -74,7 +74,6 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
     st.Lw = Lw;
     st.cq = &sm.cq[w][0][0];
     st.cnt = &sm.cnt[w][0];
-    st.shared_tau = nullptr;
     st.mine = 0;
 
     // staging: thread -> (row, 16-byte column) of the DC-wide chunk
@@ -181,205 +180,6 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// knn_tiles_qres: the fused kernel with the query tile stationary in LDS
-// (d padded <= 256).
-//
-// The streaming kernel above re-reads its 128 x d query tile for every reference
-// tile; with 64 workgroups per XCD those tiles do not fit the 4 MB L2 and evict the
-// shared reference stream as well, so every tile load misses.  Here the scaled query
-// tile is loaded into LDS once per sweep (128 rows x (d+4) floats <= 130 KB of the
-// 160 KB) and only reference rows stream.  One workgroup of 8 waves per CU:
-//   wave = (query group i of 32 queries) x (reference half g of 64 rows of the tile),
-//   two 32x32 accumulator blocks per wave.
-// The two halves are independent pipelines: each stages only its own 64 reference rows
-// (own LDS buffers) and synchronises only its own 4 waves, through a counter in LDS, so
-// that a half waiting for its slowest wave (or walking a rare path) leaves the matrix
-// pipe of every SIMD to the wave of the other half.  s_barrier would couple all 8.
-// Each wave keeps its own partial list per query (its half of every reference tile);
-// the two halves share the tighter of their two thresholds through LDS.
-// ---------------------------------------------------------------------------
-constexpr int QR_QCAP = 4;
-constexpr int QR_HALF = 64;                       // reference rows per half tile
-constexpr int QR_RBUF = QR_HALF * DC;             // floats per staging buffer
-
-// R staging layout: 64-byte rows, 16-byte units XOR-swizzled so that both the
-// row-contiguous stores and the 16-rows-same-unit fragment reads are conflict free.
-__device__ __forceinline__ int qr_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
-
-__device__ __forceinline__ void group_sync(uint32_t *bar, uint32_t target, int lane)
-{
-    // LDS operations of a wave complete in order, so once this wave's counter update is
-    // performed its staging stores are visible.  No global-memory wait: loads issued for
-    // later steps stay in flight.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    if (lane == 0) atomicAdd(bar, 1u);
-    while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
-        __builtin_amdgcn_s_sleep(1);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__global__ __launch_bounds__(512) void knn_tiles_qres(TileArgs a)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    const int qstr = a.dpad + 4;                  // odd number of 16-byte units per row
-    float *sQ = (float *)smem_raw;                // [128][qstr]
-    float *sR = sQ + TQ * qstr;                   // [2 halves][2 buffers][QR_RBUF]
-    float *sC = sR + 4 * QR_RBUF;                 // [2][2][64]
-    u64 *sCq = (u64 *)(sC + 4 * QR_HALF);         // [8 waves][32][QR_QCAP]
-    u64 *sTau = sCq + 8 * 32 * QR_QCAP;           // [4 query groups][32]
-    uint32_t *sCnt = (uint32_t *)(sTau + 4 * 32); // [8][32]
-    uint32_t *sBar = sCnt + 8 * 32;               // [2]
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int w = tid >> 6;
-    const int g = w >> 2;                         // reference half
-    const int qi = w & 3;                         // query group
-    const int gt = tid & 255;                     // thread index inside the half
-    const int h = lane >> 5;
-    const int ql = lane & 31;
-
-    const int qt = blockIdx.x / a.S;
-    const int split = blockIdx.x - qt * a.S;
-    const int64_t qbase = (int64_t)qt * TQ;
-    const int rt0 = split * a.rt_per_split;
-    const int rt1 = min(rt0 + a.rt_per_split, a.n_rtiles);
-    const int nk = a.dpad / DC;
-
-    u64 *Lw = a.lists + ((int64_t)(split * 2 + g) * a.nq_pad + qbase + 32 * qi) * a.kcap;
-    for (int i = lane; i < 32 * a.kcap; i += 64) Lw[i] = KEY_INF;
-    const int64_t myq = qbase + 32 * qi + ql;
-    const bool qvalid = myq < a.nq;
-    if (lane < 32) {
-        sCnt[w * 32 + lane] = 0;
-        if (g == 0) sTau[qi * 32 + lane] = qvalid ? KEY_INF : 0ull;
-    }
-    if (tid < 2) sBar[tid] = 0;
-
-    SelState st;
-    st.tau_key = qvalid ? KEY_INF : 0ull;
-    st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
-    st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
-    st.Lw = Lw;
-    st.cq = sCq + w * 32 * QR_QCAP;
-    st.cnt = sCnt + w * 32;
-    st.shared_tau = sTau + qi * 32;
-    st.mine = 0;
-
-    // query tile -> LDS, once
-    {
-        const int upr = a.dpad >> 2;              // 16-byte units per row
-        for (int u = tid; u < TQ * upr; u += 512) {
-            int row = u / upr, c4 = u - row * upr;
-            int64_t grow = min(qbase + row, a.nq - 1);
-            *(f32x4 *)&sQ[row * qstr + c4 * 4] = *(const f32x4 *)(a.Qp + grow * a.ldq + c4 * 4);
-        }
-    }
-    __syncthreads();
-
-    // staging of this half's 64 reference rows: thread -> (row, 16-byte unit)
-    const int lrow = gt >> 2, lunit = gt & 3;
-    float *myR = sR + g * 2 * QR_RBUF;
-    float *myC = sC + g * 2 * QR_HALF;
-    uint32_t *myBar = sBar + g;
-    const int st_off = lrow * DC + ((lunit ^ qr_swz(lrow)) << 2);
-    f32x4 pre[2];
-    float prec[2] = {0.f, 0.f};
-    int irt = rt0, ikc = 0;                       // (tile, chunk) of the next load to issue
-
-    auto issue = [&](int slot) {
-        int64_t row = min((int64_t)irt * TR + g * QR_HALF + lrow, a.nr - 1);
-        pre[slot] = *(const f32x4 *)(a.Rp + row * a.ldr + ikc * DC + lunit * 4);
-        // every thread, every step: a fixed number of loads in flight lets the compiler
-        // wait for exactly the older pair instead of draining the queue
-        prec[slot] = a.cR[(int64_t)irt * TR + g * QR_HALF + (gt & (QR_HALF - 1))];
-        if (++ikc == nk) { ikc = 0; ++irt; }
-    };
-    auto stash = [&](int slot, int buf, bool first_chunk) {
-        *(f32x4 *)&myR[buf * QR_RBUF + st_off] = pre[slot];
-        if (first_chunk && gt < QR_HALF) myC[buf * QR_HALF + gt] = prec[slot];
-    };
-
-    const int total = (rt1 - rt0) * nk;
-    uint32_t epoch = 0;
-    if (total > 0) {
-        issue(0);
-        if (total > 1) issue(1);
-        stash(0, 0, true);
-    }
-    epoch += 4;
-    group_sync(myBar, epoch, lane);
-
-    f32x16 acc[2];
-    const float *qp = sQ + (32 * qi + ql) * qstr + h * 4;
-    // fragment read offsets of the two 32-row blocks of this half (swizzled units)
-    int roff[2][NSLAB];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int s = 0; s < NSLAB; ++s) {
-            int row = t * 32 + ql;
-            roff[t][s] = row * DC + (((2 * s + h) ^ qr_swz(row)) << 2);
-        }
-
-    int rt = rt0, kc = 0;
-    auto step = [&](int it, int slot) {
-        // slot == it & 1: registers that held step `it` are free again, refill for it+2
-        if (it + 2 < total) issue(slot);
-        const int buf = it & 1;
-        if (kc == 0) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    f32x4 cv = *(const f32x4 *)&myC[buf * QR_HALF + t * 32 + gg * 8 + h * 4];
-                    acc[t][4 * gg + 0] = cv[0];
-                    acc[t][4 * gg + 1] = cv[1];
-                    acc[t][4 * gg + 2] = cv[2];
-                    acc[t][4 * gg + 3] = cv[3];
-                }
-        }
-        const float *rb = myR + buf * QR_RBUF;
-        const float *qk = qp + kc * DC;
-#pragma unroll
-        for (int s = 0; s < NSLAB; ++s) {
-            f32x4 qf = *(const f32x4 *)(qk + s * 8);
-            f32x4 rf0 = *(const f32x4 *)(rb + roff[0][s]);
-            f32x4 rf1 = *(const f32x4 *)(rb + roff[1][s]);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc[1], 0, 0, 0);
-            }
-        }
-        if (kc == nk - 1) {
-            u64 sh = st.shared_tau[ql];            // the other half may have tightened the bound
-            if (sh < st.tau_key) {
-                st.tau_key = sh;
-                st.tau_p = ord2f((uint32_t)(sh >> 32));
-            }
-            float m2 = fminf(min16(acc[0]), min16(acc[1]));
-            if (__ballot(m2 <= st.tau_p)) {
-                f32x16 blocks[2] = {acc[0], acc[1]};
-                select_rare<2, QR_QCAP>(blocks, rt * TR + g * QR_HALF + 4 * h, a.nr, a.kcap, a.k, st, lane);
-            }
-        }
-        int nkc = kc + 1, nrt = rt;
-        if (nkc == nk) { nkc = 0; nrt = rt + 1; }
-        if (it + 1 < total) stash(slot ^ 1, buf ^ 1, nkc == 0);
-        epoch += 4;
-        group_sync(myBar, epoch, lane);
-        rt = nrt;
-        kc = nkc;
-    };
-    for (int it = 0; it < total; it += 2) {
-        step(it, 0);
-        if (it + 1 < total) step(it + 1, 1);
-    }
-    merge_queues<QR_QCAP>(st, a.kcap, a.k, lane);
-}
-
-// ---------------------------------------------------------------------------
 // knn_tiles_qreg<DPAD>: the fused kernel with the query tile stationary in REGISTERS.
 //
 // Same ownership as knn_tiles (4 waves, wave = 32 queries, two independent workgroups
@@ -457,7 +257,6 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     st.Lw = Lw;
     st.cq = &sm.cq[w][0][0];
     st.cnt = &sm.cnt[w][0];
-    st.shared_tau = nullptr;
     st.mine = 0;
     uint32_t *mybound = SHARE ? a.bound + min(myq, a.nq - 1) : nullptr;
     uint32_t seen = 0xffffffffu;

@@ -46,6 +46,10 @@ def _check_rows(R, rows, self_offset, k, metric, g_idx, g_dist, strict=False, at
 def _sample_rows(n, count, seed):
     rng = np.random.default_rng(seed)
     fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, n // 2 - 1, n // 2, n - 129, n - 128, n - 2, n - 1]
+    # the panel walk cuts the rows into panels of 65 536: borders of the first, a middle and the last panel
+    P = 65536
+    mid = (n // P // 2) * P
+    fixed += [P - 1, P, P + 1, mid - 1, mid, mid + P - 1, mid + P, n - P - 1, n - P, n - P + 1]
     fixed = [r for r in fixed if 0 <= r < n]
     extra = rng.choice(n, size=max(0, min(count, n) - len(fixed)), replace=False).tolist()
     return np.array(sorted(set(fixed + extra)), dtype=np.int64)
@@ -65,7 +69,7 @@ def _sample_rows(n, count, seed):
     (2, 5, 1, "sqeuclidean"),
     (70, 3, 69, "cosine"),
 ])
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_build_small(n, d, k, metric, variant):
     _say(f"  build n={n} d={d} k={k} {metric} variant={variant}")
     X = workloads.gaussian(n, d, seed=1000 + n + d)
@@ -74,7 +78,7 @@ def test_build_small(n, d, k, metric, variant):
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 @pytest.mark.parametrize("splits", [1, 3, 16])
 @pytest.mark.parametrize("rescore", [1, 2])
 def test_split_reference_range_and_rescore(splits, rescore, variant):
@@ -96,7 +100,7 @@ def test_split_reference_range_and_rescore(splits, rescore, variant):
     (1, 513, 512, "cosine"),
     (640, 200, -1, "sqeuclidean"),
 ])
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_search_small(nq, nr, off, metric, variant):
     d, k = 24, 9
     _say(f"  search nq={nq} nr={nr} self_offset={off} {metric}")
@@ -210,28 +214,6 @@ def test_two_phase_by_panel_pairs(n, d, k, metric, panel):
     assert torch.equal(whole.idx, res.idx) and torch.equal(whole.dist, res.dist)
 
 
-@pytest.mark.parametrize("n,d,k,metric,block,sb", [
-    (1500, 40, 10, "sqeuclidean", 128, 2),     # 12 blocks in 6 super-blocks
-    (1500, 40, 10, "sqeuclidean", 128, 5),     # 3 super-blocks (odd: one dummy), the last one short
-    (3000, 96, 33, "cosine", 256, 3),
-    (2049, 64, 100, "hellinger", 128, 4),      # last block of a single row
-    (900, 256, 16, "sqeuclidean", 128, 1),     # super-block = block: every pair is a cross pair
-])
-def test_symmetric_schedule_with_warm_start(n, d, k, metric, block, sb):
-    """The triangle schedule whose lists start from the pairs inside super-blocks (two-phase
-    form) and whose rounds play pairs of different super-blocks only: every pair exactly once."""
-    _say(f"  warm-started triangle n={n} d={d} k={k} {metric} block={block} super-block={sb} blocks")
-    gen = workloads.uniform_rows if metric == "hellinger" else workloads.gaussian
-    X = gen(n, d, seed=9500 + n + d)
-    res = knn_build(X.cuda(), k, metric, symmetric=1, variant=5, block_rows=block, r_splits=sb, profile=True)
-    torch.cuda.synchronize()
-    assert res.profile.symmetric == 1 and res.profile.two_phase == 0
-    nb = -(-n // block)
-    nsb = -(-nb // sb)
-    assert res.profile.main_launches == 2 * nsb + (nsb + (nsb & 1) - 1) * sb
-    _check_rows(X.numpy(), np.arange(n), 0, k, metric, res.idx.cpu().numpy(), res.dist.cpu().numpy())
-
-
 def test_symmetric_exact_ties():
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
@@ -314,7 +296,7 @@ def test_search_equals_build():
 # ---------------------------------------------------------------------------
 # exact cases: ties must go to the lower index, bit-exact distances
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_lattice_exact(variant):
     n, k = 2000, 6
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
@@ -328,7 +310,7 @@ def test_lattice_exact(variant):
 
 @pytest.mark.parametrize("kw", [
     dict(variant=4, block_rows=512),                        # two-phase by pairs of row panels
-    dict(variant=5, symmetric=1, block_rows=128, r_splits=4),   # warm-started triangle
+    dict(symmetric=1, block_rows=128),                      # fused tournament of block pairs
 ])
 def test_ties_across_panels(kw):
     """Ties across block boundaries: a lattice on a line (every distance tied between the two
@@ -370,7 +352,7 @@ def test_panel_pairs_when_the_neighbours_come_late(n, d, k, panel):
     assert (res.idx[:third, 0].cpu() == torch.arange(third) + (n - third)).all()
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 @pytest.mark.parametrize("metric", ["sqeuclidean", "cosine"])
 def test_all_equidistant(metric, variant):
     n, k = 200, 17
@@ -384,7 +366,7 @@ def test_all_equidistant(metric, variant):
     _check_rows(X.numpy(), np.arange(n), 0, k, metric, gi, gd, strict=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_duplicate_rows(variant):
     base = workloads.gaussian(300, 20, seed=9)
     X = base.repeat_interleave(2, dim=0).contiguous()
@@ -398,7 +380,7 @@ def test_duplicate_rows(variant):
     _check_rows(X.numpy(), np.arange(600), 0, 4, "sqeuclidean", gi, gd, atol=1e-30)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_deterministic(variant):
     X = workloads.mixture(3000, 64, 16, seed=4).cuda()
     a = knn_build(X, 10, variant=variant)
@@ -458,7 +440,7 @@ def test_device_error_paths():
 # the benchmark configurations at full size (oracle on sampled rows where the full
 # oracle would take hours)
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 3, 4])
 def test_config1_full(variant):
     w = workloads.config(1)
     _say(f"  {w.name} variant={variant}")
@@ -468,7 +450,7 @@ def test_config1_full(variant):
                 res.dist.cpu().numpy())
 
 
-def _full_size(which, sample, variant=0, two_phase=None, symmetric=0):
+def _full_size(which, sample, variant=0, two_phase=None, symmetric=0, kernel=None):
     w = workloads.config(which)
     _say(f"  {w.name}: generated (variant {variant}, symmetric {symmetric})")
     Rd = w.R.cuda()
@@ -478,8 +460,10 @@ def _full_size(which, sample, variant=0, two_phase=None, symmetric=0):
         res = knn_search(Rd[:w.nq], Rd, w.k, w.metric, self_offset=0, variant=variant, profile=True)
     torch.cuda.synchronize()
     if two_phase is not None:
-        assert res.profile.two_phase == two_phase
-    _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms fused kernel")
+        assert res.profile.two_phase == two_phase and res.plan.two_phase == two_phase
+    if kernel is not None:
+        assert res.plan.kernel.decode() == kernel
+    _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms main stage, {res.plan}")
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     del Rd
     rows = _sample_rows(w.nq, sample, seed=which)
@@ -492,28 +476,129 @@ def _full_size(which, sample, variant=0, two_phase=None, symmetric=0):
     assert np.all(s[:, 1:] != s[:, :-1])
 
 
+# Oracle samples at full size: 1024 query rows for configs 2-4 and the Table-1 shape, 256 for
+# config 5 (8.4 million references each), always with rows at tile borders and at the borders of
+# the first, a middle and the last row panel.
 @pytest.mark.parametrize("variant,two_phase", [(0, 1), (3, 0)])
 def test_config2_full(variant, two_phase):
     _full_size(2, 1024, variant, two_phase)      # by default the two-phase form (d = 128, matrix of 16 GiB)
 
 
-@pytest.mark.parametrize("symmetric,two_phase", [(0, 2), (1, 0)])
-def test_config3_full(symmetric, two_phase):
+@pytest.mark.parametrize("symmetric,two_phase,kernel", [(0, 2, "knn_dist_qreg"), (1, 0, "knn_pairs_qreg")])
+def test_config3_full(symmetric, two_phase, kernel):
     """The headline workload in the plan bench.py times (by pairs of row panels, stores filtered
     by the lists' thresholds) and in the fused symmetric schedule."""
-    _full_size(3, 256, two_phase=two_phase, symmetric=symmetric)
+    _full_size(3, 1024, two_phase=two_phase, symmetric=symmetric, kernel=kernel)
 
 
-def test_config4_full():
-    _full_size(4, 128)
+@pytest.mark.parametrize("variant,two_phase,kernel", [(0, 2, "knn_dist_stream"), (3, 0, "knn_tiles")])
+def test_config4_full(variant, two_phase, kernel):
+    """d = 1024: by default the streaming distance kernel by pairs of row panels; on request the
+    fused streaming kernel (the register-resident one stops at d = 256)."""
+    _full_size(4, 1024, variant, two_phase, symmetric=2 if variant == 3 else 0, kernel=kernel)
 
 
 def test_config5_full():
-    _full_size(5, 48)
+    _full_size(5, 256, kernel="knn_tiles_qreg")
+
+
+def test_search_full_size_with_self_offset():
+    """A query block from the middle of a large reference set: queries = rows [2^19, 2^19 + 65 536)
+    of a 2^20 x 128 mixture, each excluding itself by its offset row number."""
+    nr, nq, d, k, off = 1 << 20, 65536, 128, 16, 1 << 19
+    R = workloads.mixture(nr, d, 256, seed=workloads.BASE_SEED + 55)
+    Rd = R.cuda()
+    res = knn_search(Rd[off:off + nq], Rd, k, "sqeuclidean", self_offset=off, profile=True)
+    torch.cuda.synchronize()
+    _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.plan}")
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    del Rd
+    assert not np.any(gi == (np.arange(nq, dtype=np.int64) + off)[:, None])
+    rng = np.random.default_rng(55)
+    rows = np.unique(np.concatenate([rng.choice(nq, 500, replace=False), [0, 127, 128, nq // 2, nq - 1]]))
+    Rh = R.numpy()
+    o_idx, o_dist, o_next = oracle.search(Rh[rows + off], Rh, k, "sqeuclidean", self_idx=rows + off)
+    rep = compare.check(Rh[rows + off], Rh, "sqeuclidean", o_idx, o_dist, o_next, gi[rows], gd[rows],
+                        self_idx=rows + off, rtol=RTOL)
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)
 
 
 @pytest.mark.parametrize("variant,two_phase", [(0, 1), (3, 0)])
 def test_paper_table1_shape_full(variant, two_phase):
     """n = 80 000, d = 256, k = 100, Hellinger (the largest row of the paper's Table 1): the
     two-phase form by default, the fused kernel on request."""
-    _full_size(6, 256, variant, two_phase)
+    _full_size(6, 1024, variant, two_phase)
+
+
+# ---------------------------------------------------------------------------
+# the plan follows the workspace; both sides of every rule of the default choice
+# ---------------------------------------------------------------------------
+def test_plan_follows_the_workspace():
+    """With default options the library takes the preferred plan when the workspace holds it and
+    the fused plan when it does not -- no error -- and says which; both answers meet the rule."""
+    n, d, k = 20000, 128, 10
+    X = workloads.mixture(n, d, 16, seed=4242)
+    Xd = X.cuda()
+    big = api.knn_workspace_bytes(n, n, d, k, symmetric=True)
+    small = api.knn_workspace_bytes_min(n, n, d, k, symmetric=True)
+    assert small < big // 8
+    rows = _sample_rows(n, 200, seed=5)
+    for nbytes, two_phase, kernel in ((big, 1, "knn_dist_qreg"), (small, 0, "knn_tiles_qreg"), (big - 256, 0, "knn_tiles_qreg")):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        res = knn_build(Xd, k, workspace=ws, profile=True)
+        torch.cuda.synchronize()
+        assert res.plan.two_phase == two_phase == res.profile.two_phase
+        assert res.plan.kernel.decode() == kernel and res.plan.workspace_bytes <= nbytes
+        _check_rows(X.numpy(), rows, 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+        del ws
+    with pytest.raises(api.KnnError) as e:
+        knn_build(Xd, k, workspace=torch.empty(small - 256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.KNN_ENOMEM
+    with pytest.raises(api.KnnError) as e:          # a plan asked for by name is not replaced
+        knn_build(Xd, k, variant=4, workspace=torch.empty(small, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.KNN_ENOMEM
+
+
+@pytest.mark.parametrize("n,d,k,two_phase,sym", [
+    (30000, 64, 32, 1, 1),        # k = 32 / 33: lists of 32 / 64 entries; long lists always take the two-phase form
+    (60000, 64, 32, 0, 0),
+    (60000, 64, 33, 1, 1),
+    (60000, 96, 10, 0, 0),        # d = 96 / 97 (padded to 96 / 128): from 128 on computing each pair once pays
+    (60000, 97, 10, 1, 1),
+    (49152, 64, 10, 1, 1),        # d = 64: two-phase up to 49 152 rows
+    (49152 + 128, 64, 10, 0, 0),
+    (138880, 128, 10, 1, 1),      # the matrix whole up to 72 GiB ...
+    (139008, 128, 10, 2, 1),      # ... one tile more: by pairs of row panels
+])
+def test_both_sides_of_the_plan_rules(n, d, k, two_phase, sym):
+    """One case on each side of every threshold of the default plan choice, each checked against
+    the oracle on sampled rows (not only for the plan it takes)."""
+    _say(f"  plan rule n={n} d={d} k={k}")
+    X = workloads.mixture(n, d, 32, seed=n % 1000 + d)
+    res = knn_build(X.cuda(), k)
+    torch.cuda.synchronize()
+    _say(f"    {res.plan}")
+    assert res.plan.two_phase == two_phase and res.plan.symmetric == sym
+    rows = _sample_rows(n, 96, seed=n % 89)
+    _check_rows(X.numpy(), rows, 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
+
+
+@pytest.mark.parametrize("nr,two_phase", [(130944, 1), (131072, 0)])
+def test_search_plan_rule_at_4_gib(nr, two_phase):
+    """Queries against a separate reference set: the matrix is written out while it is at most
+    4 GiB (8192 x (130944 + 64) x 4 bytes is just below, 8192 x (131072 + 64) x 4 just above)."""
+    nq, d, k = 8192, 64, 16
+    R = workloads.mixture(nr, d, 32, seed=nr % 1000)
+    Q = workloads.mixture(nq, d, 32, seed=7)
+    res = knn_search(Q.cuda(), R.cuda(), k)
+    torch.cuda.synchronize()
+    _say(f"    {res.plan}")
+    assert res.plan.two_phase == two_phase
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([rng.choice(nq, 96, replace=False), [0, nq - 1]]))
+    o_idx, o_dist, o_next = oracle.search(Q.numpy()[rows], R.numpy(), k, "sqeuclidean")
+    rep = compare.check(Q.numpy()[rows], R.numpy(), "sqeuclidean", o_idx, o_dist, o_next,
+                        res.idx.cpu().numpy()[rows], res.dist.cpu().numpy()[rows], rtol=RTOL)
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)

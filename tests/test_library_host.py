@@ -93,6 +93,53 @@ def test_workspace_of_the_two_phase_form(lib):
     assert f(65536, 131072, 128, 16) < 65536 * 131072 * 4 // 8
 
 
+def test_plan_follows_the_workspace_size(lib):
+    """With default options the plan is taken from the workspace the caller brings: the
+    preferred one if it fits, else the fused one, never an error while the fused one fits."""
+    n, d, k = 1 << 20, 256, 10
+    pref = api.knn_workspace_bytes(n, n, d, k, symmetric=True)
+    least = api.knn_workspace_bytes_min(n, n, d, k, symmetric=True)
+    assert least == api.knn_workspace_bytes(n, n, d, k, symmetric=True, variant=3) < pref // 16
+    p = api.knn_plan(n, n, d, k, symmetric=True)
+    assert (p.plan, p.two_phase, p.symmetric, p.workspace_bytes) == (api.PLAN_TWO_PHASE, 2, 1, pref)
+    assert p.kernel == b"knn_dist_qreg" and p.main_launches == 136 + 256
+    for nbytes in (least, pref - 1, 4 << 30):
+        q = api.knn_plan(n, n, d, k, symmetric=True, workspace_bytes=nbytes)
+        assert (q.plan, q.two_phase, q.symmetric) == (api.PLAN_FUSED, 0, 1)
+        assert q.kernel == b"knn_pairs_qreg" and q.workspace_bytes == least and q.main_launches == 1024
+    with pytest.raises(api.KnnError) as e:
+        api.knn_plan(n, n, d, k, symmetric=True, workspace_bytes=least - 1)
+    assert e.value.status == api.KNN_ENOMEM
+    with pytest.raises(api.KnnError) as e:      # a plan asked for by name is not replaced by another
+        api.knn_plan(n, n, d, k, symmetric=True, workspace_bytes=least, variant=4)
+    assert e.value.status == api.KNN_ENOMEM
+    # the same through the entry point itself: sizes are checked before anything touches a device
+    one, ws = ctypes.c_void_p(256), ctypes.c_void_p(4096)
+    assert lib.knn_build(one, n, d, k, 0, one, one, ws, least - 1, None) == api.KNN_ENOMEM
+    # other shapes: d > 256 falls back to the streaming fused kernel, the fold to its fused form
+    q = api.knn_plan(1 << 18, 1 << 18, 1024, 100, "cosine", symmetric=True, workspace_bytes=3 << 30)
+    assert (q.plan, q.kernel) == (api.PLAN_FUSED_STREAMING, b"knn_tiles")
+    q = api.knn_plan(65536, 65536, 128, 32, "l1", symmetric=True, workspace_bytes=1 << 30)
+    assert (q.plan, q.kernel, q.two_phase) == (api.PLAN_FUSED, b"knn_fold", 0)
+    assert api.knn_plan(65536, 65536, 128, 32, "l1", symmetric=True).kernel == b"knn_fold_dist"
+
+
+def test_options_are_validated_everywhere(lib):
+    """Out-of-range options: KNN_EINVAL from the entry points and from knn_plan, 0 from
+    knn_workspace_bytes_ex.  Plans 2 and 5 do not exist."""
+    one, ws = ctypes.c_void_p(256), ctypes.c_void_p(4096)
+    for field, value in (("variant", 2), ("variant", 5), ("variant", 7), ("variant", -1), ("symmetric", 3),
+                         ("rescore", 3), ("r_splits", -1), ("block_rows", -5), ("block_rows", (1 << 20) + 1),
+                         ("reserved", 1)):
+        opt = api.KnnOptions()
+        setattr(opt, field, value)
+        assert lib.knn_workspace_bytes_ex(100, 100, 8, 3, 0, 1, ctypes.byref(opt)) == 0, (field, value)
+        assert lib.knn_build_ex(one, 100, 8, 3, 0, one, one, ws, 1 << 30, None, ctypes.byref(opt)) == api.KNN_EINVAL
+        info = api.KnnPlanInfo()
+        assert lib.knn_plan(100, 100, 8, 3, 0, 1, ctypes.byref(opt), 1 << 30, ctypes.byref(info)) == api.KNN_EINVAL
+    assert lib.knn_plan(100, 100, 8, 3, 0, 1, None, 1 << 30, None) == api.KNN_EINVAL
+
+
 def test_bad_arguments_are_rejected_on_the_host(lib):
     one = ctypes.c_void_p(256)                  # never dereferenced: checks fail first
     ws = ctypes.c_void_p(4096)
