@@ -179,6 +179,23 @@ knn_status_t knn_search_ex(const float *Q, int64_t nq, const float *R, int64_t n
                            const knn_options_t *opt);
 
 /*
+ * knn_search for callers that cannot allocate device memory and have no workspace to
+ * bring: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and results as knn_search with default options, but the
+ * workspace is a static device array of KNN_STATIC_SCRATCH_BYTES inside the library
+ * (one per GPU, held until the process ends); the call itself allocates nothing.
+ * Sizes whose smallest plan needs more than that are refused with KNN_ENOMEM and
+ * nothing is enqueued (roughly: 4 d (nq + nr) + 8 kcap S nq bytes must fit, kcap = k
+ * rounded up to 16/32/64/128, S the number of reference slices, 16 for small nq).
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams or threads) race; calls on one stream are safe back to back.
+ */
+#define KNN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+knn_status_t knn_search_static(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d,
+                               int32_t k, knn_metric_t metric, int64_t self_offset,
+                               int32_t *idx, float *dist, void *stream);
+
+/*
  * Bytes of device workspace the PREFERRED plan of a call with these sizes and default
  * options wants; 0 if the sizes are invalid.  `symmetric` != 0 asks for knn_build (nq is
  * ignored, nr = n), 0 for knn_search.

@@ -31,7 +31,9 @@ METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KN
 PLAN_AUTO, PLAN_FUSED_STREAMING, PLAN_FUSED, PLAN_TWO_PHASE = 0, 1, 3, 4
 NO_LIMIT = ctypes.c_size_t(-1).value      # knn_plan: "whatever workspace the preferred plan wants"
 
-EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_workspace_bytes",
+STATIC_SCRATCH_BYTES = 64 << 20
+
+EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_search_static", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_workspace_bytes_min", "knn_plan", "knn_select",
            "knn_select_workspace_bytes",
            "knn_mfma_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
@@ -93,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, i64, vp, vp, vp, sz, vp]
     lib.knn_search_ex.restype = i32
     lib.knn_search_ex.argtypes = [vp, i64, vp, i64, i32, i32, i32, i64, vp, vp, vp, sz, vp, optp]
+    lib.knn_search_static.restype = i32
+    lib.knn_search_static.argtypes = [vp, i64, vp, i64, i32, i32, i32, i64, vp, vp, vp]
     lib.knn_workspace_bytes.restype = sz
     lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
     lib.knn_workspace_bytes_ex.restype = sz
@@ -261,6 +265,29 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
                                  ctypes.byref(opt)))
         plan = _plan_of(lib, opt, nq, nr, d, k, metric, 0, workspace)
     return KnnResult(idx, dist, prof, plan)
+
+
+def knn_search_static(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean", self_offset: int = -1, *,
+                      out: Tuple[torch.Tensor, torch.Tensor]) -> KnnResult:
+    """knn_search on the library's static scratch array: no workspace, and this binding allocates
+    nothing either -- the caller brings the outputs (`out` = (idx int32 [nq,k], dist fp32 [nq,k])).
+    See knn_search_static in knn.h; sizes beyond the array raise KnnError(KNN_ENOMEM)."""
+    lib = load_library()
+    Q = _dev_matrix(Q, "Q")
+    R = _dev_matrix(R, "R")
+    if Q.shape[1] != R.shape[1] or Q.device != R.device:
+        raise ValueError("Q and R must share dimension and device")
+    nq, d = Q.shape
+    nr = R.shape[0]
+    idx, dist = out
+    if idx.shape != (nq, k) or dist.shape != (nq, k) or idx.dtype != torch.int32 or dist.dtype != torch.float32 \
+            or not idx.is_contiguous() or not dist.is_contiguous() or idx.device != Q.device or dist.device != Q.device:
+        raise ValueError("out must be contiguous device tensors (int32 [nq,k], fp32 [nq,k])")
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+        _check(lib.knn_search_static(Q.data_ptr(), nq, R.data_ptr(), nr, d, k, _metric(metric), self_offset,
+                                     idx.data_ptr(), dist.data_ptr(), stream))
+    return KnnResult(idx, dist)
 
 
 def knn_select(A: torch.Tensor, k: int, *, workspace: Optional[torch.Tensor] = None,

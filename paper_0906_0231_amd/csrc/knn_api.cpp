@@ -2,16 +2,45 @@
 // layout, launch sequence.  No computation happens here.
 #include "knn.h"
 
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "knn_device.h"
 
+// Workspace of knn_search_static: one array per GPU the library is loaded on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address
+// of a device's copy is looked up once per device (static_scratch()) and that pointer is what
+// the kernels receive, exactly as they receive a caller's workspace.
+static __device__ __align__(256) unsigned char scratch[KNN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace knn;
+
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`; nullptr (and the HIP error in *err) on failure.
+void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= MAX_DEVICES)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) { *err = e; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));     // the copy of the device that is current
+        if (e != hipSuccess || !ptr) { *err = e != hipSuccess ? e : hipErrorInvalidSymbol; return nullptr; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *err = hipSuccess;
+    return g_scratch_ptr[dev];
+}
 
 thread_local char g_last_error[256] = "";
 
@@ -869,6 +898,27 @@ knn_status_t knn_search(const float *Q, int64_t nq, const float *R, int64_t nr, 
 {
     return knn_search_ex(Q, nq, R, nr, d, k, metric, self_offset, idx, dist, workspace,
                          workspace_bytes, stream, nullptr);
+}
+
+knn_status_t knn_search_static(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t d, int32_t k,
+                               knn_metric_t metric, int64_t self_offset, int32_t *idx, float *dist, void *stream)
+{
+    g_last_error[0] = 0;
+    if (!Q || !R || !idx || !dist) return KNN_EINVAL;
+    // sizes first, so that a call too large for the array is refused before anything else happens
+    knn_status_t st = check_sizes(nq, nr, d, k, metric, self_offset);
+    if (st != KNN_OK) return st;
+    knn_options_t o;
+    memset(&o, 0, sizeof(o));
+    Plan p;
+    st = choose_plan(nq, nr, d, k, metric, false, o, KNN_STATIC_SCRATCH_BYTES, p);
+    if (st != KNN_OK) return st;                     // KNN_ENOMEM: beyond what the static array holds
+    hipError_t e;
+    void *ws = static_scratch(&e);
+    if (!ws) { set_error("hipGetSymbolAddress(scratch)", e); return KNN_EDEVICE; }
+    // no profile record: run() then creates no event and allocates nothing, on host or device
+    return run(Q, nq, R, nr, d, k, metric, self_offset, false, idx, dist, ws, KNN_STATIC_SCRATCH_BYTES, stream,
+               nullptr);
 }
 
 size_t knn_select_workspace_bytes(int64_t m, int64_t n, int32_t k)
