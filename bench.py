@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0    # ... and the dense bf16 one (the split-precision experiment's instruction)
 # Vector-ALU ceiling for the fold kernel: its arithmetic is one subtract and one add (or max)
 # per coordinate and pair -- single-flop instructions that cannot fuse into FMAs.  The published
 # 157.3 TFLOP/s fp32 vector figure is 256 CUs x 4 SIMDs x 32 lanes per clock x 2 flop (FMA) x
@@ -52,7 +53,8 @@ def main() -> int:
                          "8 = Kullback-Leibler)")
     ap.add_argument("--n", type=int, default=None, help="shrink the workload (testing only)")
     ap.add_argument("--symmetric", type=int, default=0, help="0 auto, 1 triangle, 2 full square")
-    ap.add_argument("--variant", type=int, default=0, help="plan: 0 auto, 1 fused streaming, 3 fused with the query operands in registers, 4 two-phase")
+    ap.add_argument("--variant", type=int, default=0, help="plan: 0 auto, 1 fused streaming, 3 fused with the query operands in registers, 4 two-phase, "
+                         "6 the split-precision (bf16 pieces) experiment")
     ap.add_argument("--no-fused-legs", dest="fused_legs", action="store_false",
                     help="skip the extra timing of the fused plans when the default plan is two-phase")
     ap.add_argument("--block-rows", type=int, default=0, help="symmetric schedule: rows per block")
@@ -130,6 +132,8 @@ def main() -> int:
             launches = max(1, plan.main_launches)
             kern_ms = prof.ms_main / launches
         work_per_launch = 2.0 * d * prof.pairs_computed / launches      # flop (matrix path) or lane operations (fold)
+        if plan.plan == 6:
+            work_per_launch *= 3.0                                      # three bf16 products per pair and coordinate
         achieved = work_per_launch / (kern_ms * 1e-3) / 1e12
         del ws
         return {"ms_per_step": ms_per_step, "kernel": kernel, "launches": launches, "kern_ms": kern_ms,
@@ -198,6 +202,23 @@ def main() -> int:
         out["roofline"]["traffic_source"] = ("bytes per launch, FETCH_SIZE + WRITE_SIZE, measured offline "
                                              "(not by this run): " + source)
 
+    if args.variant == 6:
+        out["dtype"] = "bf16 pieces of f32 data (2 per operand, 3 products), f32 accumulation, f64 re-pricing"
+        out["roofline"].update({"peak": MFMA_BF16_PEAK_TFLOPS, "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                                "counts": "every bf16 piece product executed: 3 x 2 d flop per pair"})
+        for key in ("measured_peak", "frac_of_measured_peak"):
+            out["roofline"].pop(key, None)
+    if args.fused_legs and args.variant == 0 and w.metric == "sqeuclidean" and d <= 256 and k <= 112:
+        # The split-precision experiment (never the default, never `value`): the fused full square on
+        # bf16 matrix instructions, used as a filter; fraction of the bf16 peak, every product counted.
+        f = time_plan(0, 6, 0, 2, 1)
+        out["split_precision_experiment"] = {
+            "kernel": f["kernel"], "ms_per_step": f["ms_per_step"], "value": pairs_served / (f["ms_per_step"] * 1e-3),
+            "steps": 2, "warmup": 1, "kernel_ms_per_launch": f["kern_ms"], "achieved": f["achieved"],
+            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": f["achieved"] / MFMA_BF16_PEAK_TFLOPS,
+            "counts": "3 bf16 products per pair and coordinate", "workspace_bytes": f["workspace_bytes"]}
+        if not two_phase:
+            time_plan(args.symmetric, args.variant, args.block_rows, 1, 0)   # the default plan's answer back in idx / dist
     if args.fused_legs and two_phase and w.symmetric and w.metric not in ("l1", "linf"):
         # The default plan keeps distances in the workspace between its two phases.  The fused plans
         # (selection inside the distance kernel, nothing of the matrix stored) under the same clock:

@@ -84,11 +84,15 @@ typedef enum {
     KNN_PLAN_FUSED_STREAMING = 1, /* fused; both operands staged through LDS; any d */
     KNN_PLAN_FUSED = 3,           /* fused; query operands resident in registers (d <= 256,
                                      else as 1).  Workspace about 4 n d + 8 n kcap bytes */
-    KNN_PLAN_TWO_PHASE = 4        /* distances written to the workspace, then selected from:
+    KNN_PLAN_TWO_PHASE = 4,       /* distances written to the workspace, then selected from:
                                      the whole matrix, or (knn_build, symmetric distance) two
                                      blocks of block_rows^2 at a time, walked by pairs of row
                                      panels; chunks of distances that can no longer enter a
                                      row's list are then not stored */
+    KNN_PLAN_SPLIT_BF16 = 6       /* experiment, never taken by AUTO: fused, operands split into
+                                     two bf16 pieces, three bf16 matrix products per pair;
+                                     see knn_options_t.uncertified.  KNN_SQEUCLIDEAN,
+                                     d <= 256 and k <= 112 only */
 } knn_plan_t;
 
 /* Time spent by one call, filled in when knn_options_t.profile points here. */
@@ -121,6 +125,10 @@ typedef struct {
     int32_t reserved;   /* must be 0 */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its kernels with
                            events, waits for them and fills this in */
+    int32_t *uncertified;   /* DEVICE pointer or NULL; KNN_PLAN_SPLIT_BF16 only: receives the number
+                           of query rows whose answer could not be proven equal to the exact one
+                           from the error bound of the split products (such rows are still
+                           answered, from the candidates kept) */
 } knn_options_t;
 
 /* What a call with these sizes, options and workspace size would do; see knn_plan(). */

@@ -28,7 +28,7 @@ KNN_MAX_K = 128
 METRICS = {"sqeuclidean": KNN_SQEUCLIDEAN, "cosine": KNN_COSINE, "hellinger": KNN_HELLINGER,
            "l1": KNN_L1, "linf": KNN_LINF, "kl": KNN_KL}
 
-PLAN_AUTO, PLAN_FUSED_STREAMING, PLAN_FUSED, PLAN_TWO_PHASE = 0, 1, 3, 4
+PLAN_AUTO, PLAN_FUSED_STREAMING, PLAN_FUSED, PLAN_TWO_PHASE, PLAN_SPLIT_BF16 = 0, 1, 3, 4, 6
 NO_LIMIT = ctypes.c_size_t(-1).value      # knn_plan: "whatever workspace the preferred plan wants"
 
 STATIC_SCRATCH_BYTES = 64 << 20
@@ -52,7 +52,7 @@ class KnnOptions(ctypes.Structure):
     _fields_ = [("symmetric", ctypes.c_int32), ("rescore", ctypes.c_int32),
                 ("r_splits", ctypes.c_int32), ("variant", ctypes.c_int32),
                 ("block_rows", ctypes.c_int32), ("reserved", ctypes.c_int32),
-                ("profile", ctypes.POINTER(KnnProfile))]
+                ("profile", ctypes.POINTER(KnnProfile)), ("uncertified", ctypes.c_void_p)]
 
 
 class KnnPlanInfo(ctypes.Structure):
@@ -137,10 +137,14 @@ def _metric(metric) -> int:
 
 
 def _options(symmetric: int, rescore: int, r_splits: int, profile: bool, variant: int = 0,
-             block_rows: int = 0):
+             block_rows: int = 0, uncertified: Optional[torch.Tensor] = None):
     opt = KnnOptions()
     opt.symmetric, opt.rescore, opt.r_splits, opt.variant = symmetric, rescore, r_splits, variant
     opt.block_rows = block_rows
+    if uncertified is not None:
+        if not uncertified.is_cuda or uncertified.dtype != torch.int32 or uncertified.numel() < 1:
+            raise ValueError("uncertified must be an int32 tensor on the GPU")
+        opt.uncertified = uncertified.data_ptr()
     prof = KnnProfile() if profile else None
     if prof is not None:
         opt.profile = ctypes.pointer(prof)
@@ -219,8 +223,10 @@ class KnnResult:
 def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int = 0,
               rescore: int = 0, r_splits: int = 0, variant: int = 0, block_rows: int = 0,
               profile: bool = False, workspace: Optional[torch.Tensor] = None,
-              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
-    """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h."""
+              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+              uncertified: Optional[torch.Tensor] = None) -> KnnResult:
+    """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h.
+    `uncertified`: int32 device tensor that receives knn_options_t.uncertified (plan 6 only)."""
     lib = load_library()
     X = _dev_matrix(X, "X")
     n, d = X.shape
@@ -228,7 +234,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
         idx, dist = out if out is not None else (
             torch.empty((n, k), dtype=torch.int32, device=X.device),
             torch.empty((n, k), dtype=torch.float32, device=X.device))
-        opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows)
+        opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows, uncertified)
         if workspace is None:
             workspace = _own_workspace(lib, opt, n, n, d, k, metric, 1, X.device)
         stream = torch.cuda.current_stream(X.device).cuda_stream
@@ -242,7 +248,8 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
 def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
                self_offset: int = -1, *, rescore: int = 0, r_splits: int = 0, variant: int = 0,
                profile: bool = False, workspace: Optional[torch.Tensor] = None,
-               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> KnnResult:
+               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+               uncertified: Optional[torch.Tensor] = None) -> KnnResult:
     """Neighbours of every row of Q among the rows of R; see knn_search in knn.h."""
     lib = load_library()
     Q = _dev_matrix(Q, "Q")
@@ -255,7 +262,7 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
         idx, dist = out if out is not None else (
             torch.empty((nq, k), dtype=torch.int32, device=Q.device),
             torch.empty((nq, k), dtype=torch.float32, device=Q.device))
-        opt, prof = _options(0, rescore, r_splits, profile, variant)
+        opt, prof = _options(0, rescore, r_splits, profile, variant, 0, uncertified)
         if workspace is None:
             workspace = _own_workspace(lib, opt, nq, nr, d, k, metric, 0, Q.device)
         stream = torch.cuda.current_stream(Q.device).cuda_stream

@@ -65,6 +65,8 @@ struct Plan {
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
+    bool split;     // split-precision experiment: bf16 pieces, lists of kcap > k entries by approximate value
+    int32_t split_waves; // ... waves per workgroup of knn_tiles_split (32 queries each)
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     bool matrix;    // two-phase organisation: distance matrix written out (knn_dist_qreg), then select_rows
     bool msym;      // ... computing each unordered pair of rows once
@@ -92,6 +94,12 @@ int32_t list_capacity(int32_t k)
     while (c < k) c <<= 1;
     return c;
 }
+
+// Split-precision experiment: the lists are kept by approximate value, so they hold more than k
+// entries -- a margin of at least two, an eighth of k for long lists -- for the exact re-pricing
+// to choose from.
+constexpr int32_t KNN_SPLIT_MAX_K = 112;
+int32_t split_list_capacity(int32_t k) { return list_capacity(k + (k / 8 > 2 ? k / 8 : 2)); }
 
 // Symmetric schedule: rows per block, and what the schedule costs next to the full square.
 // A round is one launch of NBp/2 workgroups, one block pair each, on 512 workgroup slots
@@ -164,6 +172,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
                int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, Plan &p)
 {
     p.self = self;
+    p.split = false;
+    p.split_waves = 0;
     p.fold = metric == KNN_L1 || metric == KNN_LINF;
     p.refs_per_split = 0;
     p.matrix = p.msym = false;
@@ -262,6 +272,57 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o = align_up(o + (size_t)p.nq_pad * sizeof(uint32_t), 256);
         p.off_sq = o;
         p.off_bound = o;
+        p.off_lists = o;
+        o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
+        p.total = o;
+        return true;
+    }
+    if (variant == KNN_PLAN_SPLIT_BF16) {
+        // fused full square on the bf16 matrix instructions; the caller has checked metric, d and k
+        p.split = true;
+        p.split_waves = 8;
+        const int32_t tq = 32 * p.split_waves;
+        p.dpad = (int32_t)align_up((size_t)d, 32);
+        p.qreg = true;
+        p.tri = false;
+        p.rcopy = true;
+        p.kcap = split_list_capacity(k);
+        p.n_qtiles = (int32_t)((nq + tq - 1) / tq);
+        p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
+        p.nq_pad = (int64_t)p.n_qtiles * tq;
+        p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
+        p.B = p.NB = p.NBp = 0;
+        // one workgroup of 8 waves per CU: 256 slots; slices of the reference range as for the fp32 kernel
+        int32_t smax = KNN_FIN_MAX / p.kcap;
+        if (smax > p.n_rtiles) smax = p.n_rtiles;
+        int32_t S = r_splits;
+        if (S <= 0) {
+            const int32_t cap = (p.n_qtiles >= 256 && p.kcap > 32) ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
+            double best = -1.0;
+            S = 1;
+            for (int32_t s = 1; s <= cap && s <= smax; ++s) {
+                const int64_t wg = (int64_t)p.n_qtiles * s;
+                const double eff = (double)wg / (double)((wg + 255) / 256 * 256);
+                if (eff >= 0.9) { S = s; break; }
+                if (eff > best + 1e-9) { best = eff; S = s; }
+            }
+        }
+        if (S > smax) S = smax;
+        if (S < 1) S = 1;
+        p.rt_per_split = (p.n_rtiles + S - 1) / S;
+        p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
+        p.nlists = p.S;
+        size_t o = 0;
+        p.off_qp = o;
+        o = align_up(o + (size_t)nq * p.dpad * sizeof(float), 256);
+        p.off_rp = o;
+        o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
+        p.off_c = o;
+        o = align_up(o + (size_t)p.n_cpad * sizeof(float), 256);
+        p.off_sq = o;
+        o = align_up(o + (size_t)nq * sizeof(float), 256) + 256;   // + one scalar (max c_j)
+        p.off_bound = o;
+        o = align_up(o + (size_t)nq * sizeof(uint32_t), 256);
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
         p.total = o;
@@ -431,8 +492,16 @@ knn_status_t check_options(const knn_options_t &o)
         o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
         return KNN_EINVAL;
     if (o.variant != KNN_PLAN_AUTO && o.variant != KNN_PLAN_FUSED_STREAMING && o.variant != KNN_PLAN_FUSED &&
-        o.variant != KNN_PLAN_TWO_PHASE)
+        o.variant != KNN_PLAN_TWO_PHASE && o.variant != KNN_PLAN_SPLIT_BF16)
         return KNN_EINVAL;
+    return KNN_OK;
+}
+
+// what the split-precision plan can serve
+knn_status_t check_split(const knn_options_t &o, int32_t d, int32_t k, knn_metric_t metric)
+{
+    if (o.variant != KNN_PLAN_SPLIT_BF16) return KNN_OK;
+    if (metric != KNN_SQEUCLIDEAN || d > KNN_QRES_MAX_D || k > KNN_SPLIT_MAX_K) return KNN_EUNSUPPORTED;
     return KNN_OK;
 }
 
@@ -464,6 +533,7 @@ int32_t plan_launches(const Plan &p, int64_t nr)
 
 const char *plan_kernel(const Plan &p)
 {
+    if (p.split) return "knn_tiles_split";
     if (p.fold) return p.matrix ? "knn_fold_dist" : "knn_fold";
     if (p.matrix) return p.mstream ? "knn_dist_stream" : "knn_dist_qreg";
     if (p.tri) return "knn_pairs_qreg";
@@ -670,6 +740,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
     st = check_options(o);
+    if (st == KNN_OK) st = check_split(o, d, k, metric);
     if (st != KNN_OK) return st;
     if (!workspace || ((uintptr_t)workspace & 255)) return KNN_EINVAL;
 
@@ -684,7 +755,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     float *cr = (float *)(ws + p.off_c);
     float *sq = (float *)(ws + p.off_sq);
     u64 *lists = (u64 *)(ws + p.off_lists);
-    uint32_t *bound = (!p.fold && p.qreg && !p.tri && p.S > 1) ? (uint32_t *)(ws + p.off_bound) : nullptr;
+    uint32_t *bound = (!p.fold && p.qreg && !p.tri && p.S > 1) ? (uint32_t *)(ws + p.off_bound) : nullptr;   // qreg: also the split plan
 
     Events ev;
     if (o.profile) {
@@ -698,7 +769,20 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     ev.record(0, stream);
 
     // ---- prologue: norms and scaled copies ----
-    if (p.fold) {
+    if (p.split) {
+        SplitPrepArgs aq = {Q, nq, d, p.dpad, -2.f, (uint32_t *)qp, nullptr, 0, sq, bound};
+        e = launch_prep_split(aq, stream);
+        if (e != hipSuccess) { set_error("prep_split(Q)", e); return KNN_EDEVICE; }
+        SplitPrepArgs ar = {R, nr, d, p.dpad, 1.f, (uint32_t *)rp, cr, p.n_cpad, nullptr, nullptr};
+        e = launch_prep_split(ar, stream);
+        if (e != hipSuccess) { set_error("prep_split(R)", e); return KNN_EDEVICE; }
+        e = launch_reduce_max(cr, nr, (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256)), stream);
+        if (e != hipSuccess) { set_error("reduce_max", e); return KNN_EDEVICE; }
+        if (o.uncertified) {
+            e = launch_zero_word(o.uncertified, stream);
+            if (e != hipSuccess) { set_error("zero_word", e); return KNN_EDEVICE; }
+        }
+    } else if (p.fold) {
         PackArgs pq = {Q, qp, nq, d, p.dpad, 64, p.matrix ? nullptr : (uint32_t *)cr};
         e = launch_pack(pq, stream);
         if (e != hipSuccess) { set_error("pack_tiles(Q)", e); return KNN_EDEVICE; }
@@ -805,9 +889,12 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         t.n_rtiles = p.n_rtiles;
         t.S = p.S;
         t.rt_per_split = p.rt_per_split;
-        e = p.qreg ? launch_tiles_qreg(t, stream) : launch_tiles(t, stream);
+        // the split plan keeps every entry of its lists live: as many as the lists hold, or as there are references
+        const int64_t avail = nr - (self_offset >= 0 ? 1 : 0);
+        if (p.split) t.k = (int32_t)(avail < p.kcap ? avail : p.kcap);
+        e = p.split ? launch_tiles_split(t, p.split_waves, stream) : p.qreg ? launch_tiles_qreg(t, stream) : launch_tiles(t, stream);
         if (e != hipSuccess) {
-            set_error(p.qreg ? "knn_tiles_qreg" : "knn_tiles", e);
+            set_error(p.split ? "knn_tiles_split" : p.qreg ? "knn_tiles_qreg" : "knn_tiles", e);
             return KNN_EDEVICE;
         }
     }
@@ -841,6 +928,31 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     else
         f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_SQ;
     f.vec4 = (d % 4 == 0) ? 1 : 0;
+    f.krs = 0;
+    f.all_kept = 0;
+    f.cmax = nullptr;
+    f.err_a = f.err_b = 0.0;
+    f.uncert = nullptr;
+    if (p.split) {
+        // Error of the value the split kernel selects on, p~ = fl(c_j + sum of 3 dpad bf16 products),
+        // against p = |r|^2 - 2 q.r, with Q' = -2q and every fp32 value v = hi + lo + e, |e| <= 2^-16 |v|,
+        // |lo| <= 2^-8 (1 + 2^-8) |v|:
+        //   left out per coordinate: lo*lo + e_q R + Q' e_r     <= 3.02 * 2^-16 |Q'_c| |R_c|
+        //   summed (Cauchy-Schwarz):                            <= alpha |Q'| |r|,  alpha = 3.02 * 2^-16
+        //   fp32 accumulation of 3 dpad + 1 terms, any order, taken at 2^-22 per term (four times the
+        //   unit roundoff of round-to-nearest, since the matrix unit's internal rounding is not
+        //   specified):                                         <= beta (c_j + 1.02 |Q'| |r|)
+        //   c_j = fl(|r|^2):                                    <= 2^-24 |r|^2
+        // With |Q'| = 2 |q| and |r|^2 <= cmax:  E <= err_a |q| sqrt(cmax) + err_b cmax.
+        const double alpha = 3.02 / 65536.0, beta = (3.0 * p.dpad + 2.0) / 4194304.0;
+        f.mode = FIN_RESCORE_SQ;                   // the refinement IS the re-pricing: always on
+        f.krs = (int32_t)(nr - (self_offset >= 0 ? 1 : 0) < p.kcap ? nr - (self_offset >= 0 ? 1 : 0) : p.kcap);
+        f.all_kept = nr - (self_offset >= 0 ? 1 : 0) <= p.kcap ? 1 : 0;
+        f.cmax = (const float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
+        f.err_a = 2.0 * (alpha + 1.02 * beta);
+        f.err_b = beta + 1.0 / 8388608.0;
+        f.uncert = o.uncertified;
+    }
     e = launch_finalize(f, stream);
     if (e != hipSuccess) { set_error("finalize_rows", e); return KNN_EDEVICE; }
     ev.record(3, stream);
@@ -988,7 +1100,7 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     knn_options_t o;
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
-    if (check_options(o) != KNN_OK) return 0;
+    if (check_options(o) != KNN_OK || check_split(o, d, k, metric) != KNN_OK) return 0;
     Plan p;
     make_plan(nq, nr, d, k, metric, symmetric != 0, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
     return p.total;
@@ -1015,12 +1127,15 @@ knn_status_t knn_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t
     memset(&o, 0, sizeof(o));
     if (opt) o = *opt;
     st = check_options(o);
+    if (st == KNN_OK) st = check_split(o, d, k, metric);
     if (st != KNN_OK) return st;
     Plan p;
     st = choose_plan(nq, nr, d, k, metric, symmetric != 0, o, workspace_bytes, p);
     if (st != KNN_OK) return st;
     memset(out, 0, sizeof(*out));
-    out->plan = p.matrix ? KNN_PLAN_TWO_PHASE : (p.qreg || p.fold) ? KNN_PLAN_FUSED : KNN_PLAN_FUSED_STREAMING;
+    out->plan = p.split ? KNN_PLAN_SPLIT_BF16 : p.matrix ? KNN_PLAN_TWO_PHASE
+                : (p.qreg || p.fold)                         ? KNN_PLAN_FUSED
+                                                             : KNN_PLAN_FUSED_STREAMING;
     out->symmetric = (p.tri || p.msym) ? 1 : 0;
     out->two_phase = p.matrix ? (p.blocked ? 2 : 1) : 0;
     out->main_launches = plan_launches(p, nr);

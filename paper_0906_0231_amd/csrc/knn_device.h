@@ -34,6 +34,19 @@ struct PrepArgs {
     uint32_t *b_out;   // [n] per-query bound shared by the slices of the reference range: set to "none yet", or null
 };
 
+// split-precision experiment: a row as two bf16 pieces (see prep_split)
+struct SplitPrepArgs {
+    const float *X;    // [n, d]
+    int64_t n;
+    int32_t d, dpad;
+    float scale;       // a power of two (-2: query side, 1: reference side)
+    uint32_t *out;     // [n, dpad] words: per chunk of 32 coordinates 32 hi pieces, then 32 lo pieces
+    float *c_out;      // [n_cpad] |x|^2, +inf beyond n, or null
+    int64_t n_cpad;
+    float *s_out;      // [n] |x|^2, or null
+    uint32_t *b_out;   // [n] per-query bound shared by the slices: set to "none yet", or null
+};
+
 struct TileArgs {
     const float *Qp;   // [nq, ldq]
     const float *Rp;   // [nr, ldr]
@@ -146,6 +159,16 @@ struct FinArgs {
     int64_t nq, nq_pad;
     int64_t nr;        // number of reference rows (indices outside [0, nr) are never dereferenced)
     int32_t d, k, kcap, S, mode, vec4;
+    // Filter-and-refine (split-precision experiment; FIN_RESCORE_SQ only): the lists were selected on
+    // approximate values p~ with |p~ - p| <= err_a |q| + err_b for every reference.  The first
+    // `krs` (> k) entries are priced exactly and the k best of them reported; the row is CERTIFIED
+    // when the bound proves that no reference outside those krs can be among the true k nearest,
+    // and counted in *uncert otherwise.  krs == 0: none of this.
+    int32_t krs;
+    int32_t all_kept;  // 1: there are no more than krs references in all, nothing was left out
+    const float *cmax; // device scalar max_j |r_j|^2 (err_a, err_b are relative to its root / to it)
+    double err_a, err_b;
+    int32_t *uncert;   // device counter of rows not certified, or null
 };
 
 // batched partial sort of a materialised matrix
@@ -171,6 +194,9 @@ hipError_t launch_fold_dist(const FoldDistArgs &a, int mode, hipStream_t stream)
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
+hipError_t launch_prep_split(const SplitPrepArgs &a, hipStream_t stream);
+hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream);   // dpad: multiple of 32, <= 256; n_qtiles in tiles of 32 * waves queries
+hipError_t launch_zero_word(int32_t *word, hipStream_t stream);
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*

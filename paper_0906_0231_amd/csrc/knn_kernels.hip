@@ -10,6 +10,8 @@
 //   knn_matrix_kernel.h  Phase 1 on its own: the distance matrix written out (Sect. 5), for the
 //                        problems where selecting from it afterwards (select_rows) is cheaper
 //   knn_fold_kernels.h   folds that are not inner products, on the vector ALUs; calibration
+//   knn_split_kernels.h  experiment: the fused kernel on bf16 matrix instructions, operands
+//                        split into two pieces, used as a filter with a proven error bound
 //   this file            launchers called from the C ABI (knn_api.cpp)
 //
 // On the matrix path distances are evaluated in the expanded form
@@ -43,6 +45,7 @@ typedef __attribute__((address_space(3))) void *lds_ptr;
 #include "knn_pairs_kernel.h"
 #include "knn_matrix_kernel.h"
 #include "knn_fold_kernels.h"
+#include "knn_split_kernels.h"
 
 namespace knn {
 
@@ -238,11 +241,58 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_prep_split(const SplitPrepArgs &a, hipStream_t stream)
+{
+    int64_t blocks = (a.n + 3) / 4;
+    int64_t pad_blocks = a.c_out ? (a.n_cpad - a.n + 255) / 256 : 0;
+    if (blocks > 262144) blocks = 262144;
+    if (blocks < pad_blocks) blocks = pad_blocks;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(prep_split, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int WAVES, bool SHARE>
+static hipError_t launch_tiles_split_t(const TileArgs &a, hipStream_t stream)
+{
+    int64_t blocks = (int64_t)a.n_qtiles * a.S;
+    dim3 grid((unsigned)blocks), block(64 * WAVES);
+    switch (a.dpad) {
+    case 32: hipLaunchKernelGGL((knn_tiles_split<32, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_tiles_split<64, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_tiles_split<96, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_tiles_split<128, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_tiles_split<160, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_tiles_split<192, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_tiles_split<224, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((knn_tiles_split<256, WAVES, SHARE>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream)
+{
+    const bool share = a.bound != nullptr && a.S > 1;
+    if (waves == 8) return share ? launch_tiles_split_t<8, true>(a, stream) : launch_tiles_split_t<8, false>(a, stream);
+    if (waves == 4) return share ? launch_tiles_split_t<4, true>(a, stream) : launch_tiles_split_t<4, false>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+__global__ void zero_word(int32_t *w) { *w = 0; }
+
+// a one-thread fill kernel rather than hipMemsetAsync, so that a caller may capture the call in a graph
+hipError_t launch_zero_word(int32_t *word, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_word, dim3(1), dim3(1), 0, stream, word);
+    return hipGetLastError();
+}
+
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream)
 {
     int npow = 1, kpow = 1;
     while (npow < a.S * a.kcap) npow <<= 1;
-    while (kpow < a.k) kpow <<= 1;
+    while (kpow < (a.krs > a.k ? a.krs : a.k)) kpow <<= 1;
     if (npow > KNN_FIN_MAX || kpow > KNN_MAX_KCAP) return hipErrorInvalidValue;
     const size_t lds = (size_t)(npow + kpow) * sizeof(u64);
     hipLaunchKernelGGL(finalize_rows, dim3((unsigned)a.nq), dim3(64), lds, stream, a);

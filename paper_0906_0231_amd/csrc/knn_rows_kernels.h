@@ -455,8 +455,10 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     __syncthreads();
     if (a.S > 1) bitonic_sort_lds(keys, npow, lane);
 
+    // entries that are priced again below: the k winners, or (filter-and-refine) the first krs > k
+    const int kr = a.krs > 0 ? a.krs : a.k;
     int kpow = 1;
-    while (kpow < a.k) kpow <<= 1;
+    while (kpow < kr) kpow <<= 1;
     for (int i = lane; i < kpow; i += 64) outk[i] = KEY_INF;
     __syncthreads();
 
@@ -508,9 +510,9 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                 for (int e = 0; e < 4; ++e) xs[i][e] = sqrt_of_float(u[e]);
             }
         }
-        for (int r0 = 0; r0 < a.k; r0 += 4) {
+        for (int r0 = 0; r0 < kr; r0 += 4) {
             const int r = r0 + g16;
-            const int32_t j = r < a.k ? (int32_t)(uint32_t)keys[r] : -1;
+            const int32_t j = r < kr ? (int32_t)(uint32_t)keys[r] : -1;
             const bool ok = j >= 0 && j < a.nr;
             const float *y = a.R + (int64_t)(ok ? j : 0) * a.d;
             double s = 0.0, uu = 0.0, vv = 0.0;
@@ -563,7 +565,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
                 s = (uu == 0.0 || vv == 0.0) ? 1.0 : 1.0 - s / (sqrt(uu) * sqrt(vv));
                 if (s < 0.0) s = 0.0;
             }
-            if (gl == 0 && r < a.k) outk[r] = ok ? make_key((float)s, j) : KEY_INF;
+            if (gl == 0 && r < kr) outk[r] = ok ? make_key((float)s, j) : KEY_INF;
         }
     } else if (a.mode == FIN_SELECT) {
         for (int r = lane; r < a.k; r += 64) outk[r] = keys[r];   // keys are (value, column) already
@@ -582,6 +584,30 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
         u64 key = outk[r];
         a.idx[q * a.k + r] = (int32_t)(uint32_t)key;
         a.dist[q * a.k + r] = ord2f((uint32_t)(key >> 32));
+    }
+    if (a.krs > 0 && a.uncert != nullptr) {
+        // Certificate of the filter.  The lists hold, by approximate value p~, the krs smallest of
+        // ALL references, so a reference j outside them has p~_j >= t~ (the krs-th kept value)
+        // and a true value p_j >= t~ - E, where E = err_a |q| sqrt(cmax) + err_b cmax bounds
+        // |p~ - p| for this query.  The k-th smallest TRUE value among the kept ones is
+        // p_k = delta_k - |q|^2.  If p_k < t~ - E, every reference left out is strictly farther
+        // than the k reported: they are the exact answer, ties included.  With no more than krs
+        // references in all, nothing was left out.
+        const u64 last = keys[kr - 1];
+        bool certified = a.all_kept != 0 || last == KEY_INF;
+        if (!certified) {
+            const float *x = a.Q + q * (int64_t)a.d;
+            double qq = 0.0;
+            for (int c = lane; c < a.d; c += 64) qq = fma((double)x[c], (double)x[c], qq);
+            qq = wave_sum_f64(qq);
+            const double cm = (double)*a.cmax;
+            const double E = a.err_a * sqrt(qq * cm) + a.err_b * cm;
+            const double tt = (double)ord2f((uint32_t)(last >> 32));
+            // the reported distance is the double sum rounded to fp32: at most 2^-24 below it
+            const double dk = (double)ord2f((uint32_t)(outk[a.k - 1] >> 32)) * (1.0 + 1.2e-7);
+            certified = dk - qq < tt - E;
+        }
+        if (!certified && lane == 0) atomicAdd(a.uncert, 1);
     }
 }
 
