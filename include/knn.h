@@ -89,10 +89,12 @@ typedef enum {
                                      blocks of block_rows^2 at a time, walked by pairs of row
                                      panels; chunks of distances that can no longer enter a
                                      row's list are then not stored */
-    KNN_PLAN_SPLIT_BF16 = 6       /* experiment, never taken by AUTO: fused, operands split into
-                                     two bf16 pieces, three bf16 matrix products per pair;
-                                     see knn_options_t.uncertified.  KNN_SQEUCLIDEAN,
-                                     d <= 256 and k <= 112 only */
+    KNN_PLAN_SPLIT_BF16 = 6       /* experiment, never taken by AUTO: fused; operands split into two
+                                     bf16 pieces, three bf16 matrix products per pair pick K' > k
+                                     candidates per query, which are then priced exactly; rows the
+                                     error bound of the split cannot prove right are answered
+                                     again by the fp32 kernel (at most 4096 rows).
+                                     KNN_SQEUCLIDEAN, d <= 256 and k <= 112 only */
 } knn_plan_t;
 
 /* Time spent by one call, filled in when knn_options_t.profile points here. */
@@ -126,9 +128,10 @@ typedef struct {
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its kernels with
                            events, waits for them and fills this in */
     int32_t *uncertified;   /* DEVICE pointer or NULL; KNN_PLAN_SPLIT_BF16 only: receives the number
-                           of query rows whose answer could not be proven equal to the exact one
-                           from the error bound of the split products (such rows are still
-                           answered, from the candidates kept) */
+                           of query rows whose answer is neither proven exact by the error bound of
+                           the split products nor recomputed by the fp32 kernel, i.e. those beyond
+                           the 4096 the second pass takes (such rows are still answered, from the
+                           candidates kept) */
 } knn_options_t;
 
 /* What a call with these sizes, options and workspace size would do; see knn_plan(). */

@@ -67,6 +67,9 @@ struct Plan {
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
     bool split;     // split-precision experiment: bf16 pieces, lists of kcap > k entries by approximate value
     int32_t split_waves; // ... waves per workgroup of knn_tiles_split (32 queries each)
+    int32_t fb_cap, fb_S, fb_kcap, fb_rt_per_split;   // ... second pass (fp32 kernel) over the rows the filter could
+                         //     not certify: most rows it takes, slices, list capacity
+    size_t off_fb_q, off_fb_self, off_fb_bound, off_fb_rows, off_fb_words, off_fb_lists, off_r32;
     int64_t refs_per_split; // fold kernel: references per slice, multiple of KNN_FOLD_NR
     bool matrix;    // two-phase organisation: distance matrix written out (knn_dist_qreg), then select_rows
     bool msym;      // ... computing each unordered pair of rows once
@@ -325,6 +328,27 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o = align_up(o + (size_t)nq * sizeof(uint32_t), 256);
         p.off_lists = o;
         o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
+        // second pass: at most 4096 rows, the reference range in as many slices as finalize can merge
+        p.fb_cap = (int32_t)(nq < 4096 ? (nq + KNN_TILE - 1) / KNN_TILE * KNN_TILE : 4096);
+        p.fb_kcap = list_capacity(k);
+        int32_t s2 = KNN_FIN_MAX / p.fb_kcap;
+        if (s2 > p.n_rtiles) s2 = p.n_rtiles;
+        p.fb_rt_per_split = (p.n_rtiles + s2 - 1) / s2;
+        p.fb_S = (p.n_rtiles + p.fb_rt_per_split - 1) / p.fb_rt_per_split;
+        p.off_fb_q = o;
+        o = align_up(o + (size_t)p.fb_cap * p.dpad * sizeof(float), 256);
+        p.off_fb_self = o;
+        o = align_up(o + (size_t)p.fb_cap * sizeof(int32_t), 256);
+        p.off_fb_bound = o;
+        o = align_up(o + (size_t)p.fb_cap * sizeof(uint32_t), 256);
+        p.off_fb_rows = o;
+        o = align_up(o + (size_t)p.fb_cap * sizeof(int32_t), 256);
+        p.off_fb_words = o;                        // [0] rows not certified by the first pass, [1] rows in the second
+        o += 256;
+        p.off_fb_lists = o;
+        o = align_up(o + (size_t)p.fb_S * p.fb_cap * p.fb_kcap * sizeof(u64), 256);
+        p.off_r32 = o;                             // fp32 reference rows padded to dpad, if d is ragged
+        if (p.dpad != d) o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
         p.total = o;
         return true;
     }
@@ -778,9 +802,13 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         if (e != hipSuccess) { set_error("prep_split(R)", e); return KNN_EDEVICE; }
         e = launch_reduce_max(cr, nr, (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256)), stream);
         if (e != hipSuccess) { set_error("reduce_max", e); return KNN_EDEVICE; }
-        if (o.uncertified) {
-            e = launch_zero_word(o.uncertified, stream);
-            if (e != hipSuccess) { set_error("zero_word", e); return KNN_EDEVICE; }
+        e = launch_zero_word((int32_t *)(ws + p.off_fb_words), stream);
+        if (e != hipSuccess) { set_error("zero_word", e); return KNN_EDEVICE; }
+        if (p.dpad != d) {
+            // the second pass reads fp32 reference rows of dpad coordinates
+            PrepArgs a32 = {R, nr, d, p.dpad, (int32_t)KNN_SQEUCLIDEAN, nullptr, (float *)(ws + p.off_r32), nullptr, nr, nullptr, nullptr};
+            e = launch_prep(a32, stream);
+            if (e != hipSuccess) { set_error("prep_rows(R, fp32)", e); return KNN_EDEVICE; }
         }
     } else if (p.fold) {
         PackArgs pq = {Q, qp, nq, d, p.dpad, 64, p.matrix ? nullptr : (uint32_t *)cr};
@@ -889,6 +917,8 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         t.n_rtiles = p.n_rtiles;
         t.S = p.S;
         t.rt_per_split = p.rt_per_split;
+        t.nq_dev = nullptr;
+        t.self_rows = nullptr;
         // the split plan keeps every entry of its lists live: as many as the lists hold, or as there are references
         const int64_t avail = nr - (self_offset >= 0 ? 1 : 0);
         if (p.split) t.k = (int32_t)(avail < p.kcap ? avail : p.kcap);
@@ -930,6 +960,10 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     f.vec4 = (d % 4 == 0) ? 1 : 0;
     f.krs = 0;
     f.all_kept = 0;
+    f.unc_rows = nullptr;
+    f.unc_cap = 0;
+    f.row_map = nullptr;
+    f.nq_dev = nullptr;
     f.cmax = nullptr;
     f.err_a = f.err_b = 0.0;
     f.uncert = nullptr;
@@ -951,10 +985,70 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         f.cmax = (const float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
         f.err_a = 2.0 * (alpha + 1.02 * beta);
         f.err_b = beta + 1.0 / 8388608.0;
-        f.uncert = o.uncertified;
+        f.uncert = (int32_t *)(ws + p.off_fb_words);
+        f.unc_rows = (int32_t *)(ws + p.off_fb_rows);
+        f.unc_cap = p.fb_cap;
     }
     e = launch_finalize(f, stream);
     if (e != hipSuccess) { set_error("finalize_rows", e); return KNN_EDEVICE; }
+    if (p.split) {
+        // Second pass: the rows the bound could not certify (up to fb_cap of them) are answered again
+        // by the fp32 kernel over all references, as the fused fp32 plan would answer them.  The
+        // number of such rows is only known on the device: the launches have room for fb_cap rows
+        // and their workgroups beyond the count leave at once.
+        int32_t *words = (int32_t *)(ws + p.off_fb_words);
+        GatherArgs g;
+        g.Q = Q;
+        g.rows = (const int32_t *)(ws + p.off_fb_rows);
+        g.count = words;
+        g.q_out = (float *)(ws + p.off_fb_q);
+        g.self_out = (int32_t *)(ws + p.off_fb_self);
+        g.b_out = (uint32_t *)(ws + p.off_fb_bound);
+        g.n_out = words + 1;
+        g.left_out = o.uncertified;
+        g.self_offset = self_offset;
+        g.d = d;
+        g.dpad = p.dpad;
+        g.cap = p.fb_cap;
+        e = launch_gather_rows(g, stream);
+        if (e != hipSuccess) { set_error("gather_rows", e); return KNN_EDEVICE; }
+        TileArgs t;
+        t.Qp = g.q_out;
+        t.Rp = p.dpad != d ? (const float *)(ws + p.off_r32) : R;
+        t.cR = cr;
+        t.lists = (u64 *)(ws + p.off_fb_lists);
+        t.bound = g.b_out;
+        t.ldq = p.dpad;
+        t.ldr = p.dpad;
+        t.nq = p.fb_cap;
+        t.nr = nr;
+        t.nq_pad = p.fb_cap;
+        t.self_offset = -1;
+        t.dpad = p.dpad;
+        t.k = k;
+        t.kcap = p.fb_kcap;
+        t.n_qtiles = p.fb_cap / KNN_TILE;
+        t.n_rtiles = p.n_rtiles;
+        t.S = p.fb_S;
+        t.rt_per_split = p.fb_rt_per_split;
+        t.nq_dev = words + 1;
+        t.self_rows = g.self_out;
+        e = launch_tiles_qreg_subset(t, stream);
+        if (e != hipSuccess) { set_error("knn_tiles_qreg(second pass)", e); return KNN_EDEVICE; }
+        FinArgs f2 = f;
+        f2.lists = t.lists;
+        f2.nq = p.fb_cap;
+        f2.nq_pad = p.fb_cap;
+        f2.kcap = p.fb_kcap;
+        f2.S = p.fb_S;
+        f2.krs = 0;
+        f2.uncert = nullptr;
+        f2.unc_rows = nullptr;
+        f2.row_map = g.rows;
+        f2.nq_dev = words + 1;
+        e = launch_finalize(f2, stream);
+        if (e != hipSuccess) { set_error("finalize_rows(second pass)", e); return KNN_EDEVICE; }
+    }
     ev.record(3, stream);
 
     if (o.profile) {

@@ -58,6 +58,8 @@ struct TileArgs {
     int64_t self_offset;
     int32_t dpad, k, kcap;
     int32_t n_qtiles, n_rtiles, S, rt_per_split;
+    const int32_t *nq_dev;    // knn_tiles_qreg<.., SUBSET> only: device word holding the number of queries (<= nq)
+    const int32_t *self_rows; // ... and per query the reference index that is the query itself, or -1
 };
 
 // fold kernel (distances that are not inner products): lane = query, references from
@@ -169,6 +171,27 @@ struct FinArgs {
     const float *cmax; // device scalar max_j |r_j|^2 (err_a, err_b are relative to its root / to it)
     double err_a, err_b;
     int32_t *uncert;   // device counter of rows not certified, or null
+    int32_t *unc_rows; // [unc_cap] the first unc_cap of them, in order of arrival, or null
+    int32_t unc_cap;
+    // Second pass over a compacted subset of the queries (the rows listed in unc_rows by an earlier
+    // call): block q serves query row row_map[q] and leaves if q >= *nq_dev.  null: block q is row q.
+    const int32_t *row_map;
+    const int32_t *nq_dev;
+};
+
+// split-precision plan, between its two passes: the rows the filter could not certify, scaled and
+// padded for the fp32 kernel
+struct GatherArgs {
+    const float *Q;         // [nq, d] original query rows
+    const int32_t *rows;    // [cap] uncertified rows (the first min(*count, cap) are valid)
+    const int32_t *count;   // device word: rows not certified by the first pass
+    float *q_out;           // [cap, dpad] = -2 Q[rows[i]], zero padded
+    int32_t *self_out;      // [cap] self_offset + rows[i], or -1
+    uint32_t *b_out;        // [cap] shared bound of the slices: "none yet"
+    int32_t *n_out;         // device word: min(*count, cap), the size of the subset
+    int32_t *left_out;      // device word or null: rows still unproven after the second pass, max(0, *count - cap)
+    int64_t self_offset;
+    int32_t d, dpad, cap;
 };
 
 // batched partial sort of a materialised matrix
@@ -197,6 +220,8 @@ hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_prep_split(const SplitPrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream);   // dpad: multiple of 32, <= 256; n_qtiles in tiles of 32 * waves queries
 hipError_t launch_zero_word(int32_t *word, hipStream_t stream);
+hipError_t launch_gather_rows(const GatherArgs &a, hipStream_t stream);
+hipError_t launch_tiles_qreg_subset(const TileArgs &a, hipStream_t stream);   // nq = capacity of the subset; S > 1 needs bound
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qreg(const TileArgs &a, hipStream_t stream);   // dpad: multiple of 32, <= 256
 hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);      // mode: see DIST_*

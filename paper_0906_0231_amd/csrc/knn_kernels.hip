@@ -279,6 +279,31 @@ hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream)
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_gather_rows(const GatherArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(gather_rows, dim3((unsigned)((a.cap + 3) / 4)), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_qreg_subset(const TileArgs &a, hipStream_t stream)
+{
+    if (a.nq_dev == nullptr || a.self_rows == nullptr || (a.S > 1 && a.bound == nullptr)) return hipErrorInvalidValue;
+    int64_t blocks = (int64_t)a.n_qtiles * a.S;
+    dim3 grid((unsigned)blocks), block(256);
+    switch (a.dpad) {
+    case 32: hipLaunchKernelGGL((knn_tiles_qreg<32, true, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_tiles_qreg<64, true, true>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_tiles_qreg<96, true, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_tiles_qreg<128, true, true>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_tiles_qreg<160, true, true>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_tiles_qreg<192, true, true>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_tiles_qreg<224, true, true>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((knn_tiles_qreg<256, true, true>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 __global__ void zero_word(int32_t *w) { *w = 0; }
 
 // a one-thread fill kernel rather than hipMemsetAsync, so that a caller may capture the call in a graph

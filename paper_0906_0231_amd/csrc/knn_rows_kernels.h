@@ -437,7 +437,11 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     // times as many queries in flight per CU for the row gathers below
     extern __shared__ u64 fin_lds[];
     const int lane = threadIdx.x;
-    const int64_t q = blockIdx.x;
+    // lq: position of the query's lists; q: the query's row (they differ in the second pass over a
+    // compacted subset of the rows)
+    const int64_t lq = blockIdx.x;
+    if (a.nq_dev != nullptr && lq >= *a.nq_dev) return;
+    const int64_t q = a.row_map != nullptr ? a.row_map[lq] : lq;
 
     const int nin = a.S * a.kcap;
     int npow = 1;
@@ -448,7 +452,7 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
         u64 v = KEY_INF;
         if (i < nin) {
             int s = i / a.kcap, e = i - s * a.kcap;
-            v = a.lists[((int64_t)s * a.nq_pad + q) * a.kcap + e];
+            v = a.lists[((int64_t)s * a.nq_pad + lq) * a.kcap + e];
         }
         keys[i] = v;
     }
@@ -607,10 +611,34 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
             const double dk = (double)ord2f((uint32_t)(outk[a.k - 1] >> 32)) * (1.0 + 1.2e-7);
             certified = dk - qq < tt - E;
         }
-        if (!certified && lane == 0) atomicAdd(a.uncert, 1);
+        if (!certified && lane == 0) {
+            const int slot = atomicAdd(a.uncert, 1);
+            if (a.unc_rows != nullptr && slot < a.unc_cap) a.unc_rows[slot] = (int32_t)q;
+        }
     }
 }
 
+
+// The rows a filter pass could not certify, made ready for the fp32 kernel: one wave per row.
+__global__ __launch_bounds__(256) void gather_rows(GatherArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int n = min(*a.count, a.cap);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *a.n_out = n;
+        if (a.left_out) *a.left_out = *a.count - n;
+    }
+    if (i >= n) return;
+    const int32_t row = a.rows[i];
+    const float *x = a.Q + (int64_t)row * a.d;
+    float *o = a.q_out + (int64_t)i * a.dpad;
+    for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? -2.f * x[c] : 0.f;
+    if (lane == 0) {
+        a.self_out[i] = a.self_offset >= 0 ? (int32_t)(a.self_offset + row) : -1;
+        a.b_out[i] = 0xffffffffu;
+    }
+}
 
 // largest c_j (squared norm) of the data set: scale of the mirror slack
 __global__ __launch_bounds__(1024) void reduce_max(const float *c, int64_t n, float *out)

@@ -225,7 +225,11 @@ struct __attribute__((aligned(16))) QregSmem {
 // slices publish theirs (atomic minimum on one word per query) and test against the smallest
 // published so far; a stale read is merely looser.  Matters when n is small against k (the
 // shape of the paper's Table 1: without it 40 % of all pairs entered a queue at n = 10 000).
-template <int DPAD, bool SHARE>
+// SUBSET: the queries are a compacted subset whose size is only known on the device (a.nq_dev;
+// a.nq is its capacity) and whose self indices come from a table (a.self_rows): the second pass
+// of the split-precision plan over the rows its filter could not certify.  Workgroups beyond the
+// subset leave at once.
+template <int DPAD, bool SHARE, bool SUBSET = false>
 __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
 {
     constexpr int NK = DPAD / QG_DC;
@@ -240,6 +244,10 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     const int qt = blockIdx.x / a.S;
     const int split = blockIdx.x - qt * a.S;
     const int64_t qbase = (int64_t)qt * TQ;
+    if (SUBSET) {
+        a.nq = min(a.nq, (int64_t)*a.nq_dev);
+        if (qbase >= a.nq) return;                // the whole workgroup, before any barrier
+    }
     // slices are cut in units of 128 reference rows; this kernel walks them 64 at a time
     const int rt0 = split * a.rt_per_split * 2;
     const int rt1 = min(rt0 + a.rt_per_split * 2, (int)((a.nr + QG_TR - 1) / QG_TR));
@@ -254,6 +262,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles_qreg(TileArgs a)
     st.tau_key = qvalid ? KEY_INF : 0ull;
     st.tau_p = qvalid ? __builtin_inff() : -__builtin_inff();
     st.selfj = (a.self_offset >= 0 && qvalid) ? (int32_t)(a.self_offset + myq) : -1;
+    if (SUBSET) st.selfj = qvalid ? a.self_rows[myq] : -1;
     st.Lw = Lw;
     st.cq = &sm.cq[w][0][0];
     st.cnt = &sm.cnt[w][0];

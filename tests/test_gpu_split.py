@@ -2,8 +2,8 @@
 bf16 matrix products per pair, used as a filter whose survivors are priced exactly.  Its answers
 are held to the same rule against the CPU oracle as every other plan's; where the arithmetic is
 exact (small integers survive the split) the index lists must match bit for bit.  The number of
-rows the error bound could not certify is printed; it does not enter the verdict -- the
-comparison with the oracle does."""
+rows left unproven (neither certified by the error bound nor taken by the fp32 second pass) is
+printed; it does not enter the verdict -- the comparison with the oracle does."""
 import numpy as np
 import pytest
 import torch
@@ -64,7 +64,7 @@ def test_split_build_small(n, d, k, splits):
     _say(f"  split build n={n} d={d} k={k} splits={splits}")
     X = workloads.gaussian(n, d, seed=7000 + n + d)
     res, n_unc = _build(X, k, r_splits=splits)
-    _say(f"    rows not certified: {n_unc} of {n}")
+    _say(f"    rows left unproven: {n_unc} of {n}")
     _check(X.numpy(), X.numpy(), np.arange(n), k, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
@@ -92,7 +92,8 @@ def test_split_exact_ties():
     assert gi[1000].tolist() == [999, 1001, 998, 1002, 997, 1003] and gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
     E = torch.eye(256, dtype=torch.float32)
     res, n_unc = _build(E, 17)
-    _say(f"    one-hot rows not certified: {n_unc} of 256 (every pair ties: the bound cannot separate them)")
+    _say(f"    one-hot rows left unproven: {n_unc} of 256 (every pair ties: all 256 go through the second pass)")
+    assert n_unc == 0
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     for i in (0, 1, 16, 17, 18, 127, 128, 255):
         assert gi[i].tolist() == [j for j in range(256) if j != i][:17]
@@ -103,6 +104,24 @@ def test_split_exact_ties():
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     assert np.array_equal(gi[:, 0], np.arange(600) ^ 1) and np.all(gd[:, 0] == 0.0)
     _check(D.numpy(), D.numpy(), np.arange(600), 4, gi, gd, atol=1e-30)
+
+
+def test_split_second_pass_and_its_overflow():
+    """Totally tied data (50 distinct small-integer points, each repeated n/50 times: every row has
+    more than K' references at distance 0, all values exact in every plan): the bound can certify
+    nothing, so the fp32 second pass answers up to 4096 rows and the rest keep the filter's answer
+    -- all of them the oracle's lists bit for bit.  With 3000 rows everything fits the second pass,
+    with 6000 rows 1904 are left over and counted."""
+    rng = np.random.default_rng(21)
+    base = rng.integers(0, 3, size=(50, 8)).astype(np.float32)
+    for n, left_some in ((3000, False), (6000, True)):
+        X = torch.from_numpy(base[np.arange(n) % 50].copy())
+        res, left = _build(X, 9)
+        _say(f"    n={n}: rows left unproven after the second pass: {left}")
+        assert left == (n - 4096 if left_some else 0)
+        o_idx, o_dist, _ = oracle.build_knn(X.numpy(), 9)
+        assert np.array_equal(res.idx.cpu().numpy(), o_idx)
+        assert np.array_equal(res.dist.cpu().numpy().astype(np.float64), o_dist)
 
 
 def test_split_deterministic_and_agrees_with_fp32_plan():
@@ -144,7 +163,8 @@ def test_split_configs_full(which, sample):
     res = knn_build(w.R.cuda(), w.k, w.metric, variant=SPLIT, profile=True, uncertified=unc)
     torch.cuda.synchronize()
     _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms main stage; "
-         f"rows not certified: {int(unc.item())} of {w.n}")
+         f"rows left unproven: {int(unc.item())} of {w.n}")
+    assert int(unc.item()) == 0
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     rng = np.random.default_rng(which)
     rows = np.unique(np.concatenate([rng.choice(w.n, min(sample, w.n), replace=False),
