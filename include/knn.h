@@ -266,6 +266,15 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
                                   size_t sink_bytes, int64_t *total_waves, void *stream);
 
 /*
+ * The same for v_mfma_f32_32x32x16_bf16, the instruction of KNN_PLAN_SPLIT_BF16: one launch
+ * executes waves * mfma_per_wave * 32768 flop.  `chains` is the number of independent
+ * accumulators per wave the instructions rotate over: 4, or 2 (the dependency pattern of that
+ * plan's kernel).  Other arguments and errors as for knn_mfma_calibration.
+ */
+knn_status_t knn_mfma_bf16_calibration(int64_t mfma_per_wave, int32_t waves_per_simd, int32_t chains,
+                                       float *sink, size_t sink_bytes, int64_t *total_waves, void *stream);
+
+/*
  * The same for the vector ALUs: every wave issues `pairs_per_wave` times the fold kernel's
  * instruction pair (v_sub_f32 with a scalar operand, v_add_f32 with the |.| modifier) on 32
  * independent accumulators.  One launch executes waves * pairs_per_wave * 2 * 64 lane

@@ -36,7 +36,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_search_static", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_workspace_bytes_min", "knn_plan", "knn_select",
            "knn_select_workspace_bytes",
-           "knn_mfma_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
+           "knn_mfma_calibration", "knn_mfma_bf16_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
            "knn_last_device_error"]
 
 
@@ -111,6 +111,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_select_workspace_bytes.argtypes = [i64, i64, i32]
     lib.knn_mfma_calibration.restype = i32
     lib.knn_mfma_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
+    lib.knn_mfma_bf16_calibration.restype = i32
+    lib.knn_mfma_bf16_calibration.argtypes = [i64, i32, i32, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_read_calibration.restype = i32
     lib.knn_read_calibration.argtypes = [vp, i64, i64, vp, sz, vp]
     lib.knn_valu_calibration.restype = i32
@@ -338,6 +340,27 @@ def knn_mfma_calibration(mfma_per_wave: int = 1 << 20, waves_per_simd: int = 2, 
         stop.synchronize()
         ms = start.elapsed_time(stop)
     return waves.value * mfma_per_wave * 4096.0 / (ms * 1e-3) / 1e12, ms
+
+
+def knn_mfma_bf16_calibration(mfma_per_wave: int = 1 << 21, waves_per_simd: int = 2, chains: int = 4,
+                              device=None) -> Tuple[float, float]:
+    """Time the library's bf16 matrix-instruction-only kernel; returns (TFLOP/s, ms).  See
+    knn_mfma_bf16_calibration in knn.h."""
+    lib = load_library()
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    with torch.cuda.device(dev):
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        sink = torch.empty(cus * waves_per_simd * 256, dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream(dev)
+        waves = ctypes.c_int64(0)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        _check(lib.knn_mfma_bf16_calibration(mfma_per_wave, waves_per_simd, chains, sink.data_ptr(), sink.numel() * 4,
+                                             ctypes.byref(waves), stream.cuda_stream))
+        stop.record(stream)
+        stop.synchronize()
+        ms = start.elapsed_time(stop)
+    return waves.value * mfma_per_wave * 32768.0 / (ms * 1e-3) / 1e12, ms
 
 
 def knn_valu_calibration(pairs_per_wave: int = 1 << 22, waves_per_simd: int = 4, device=None) -> Tuple[float, float]:

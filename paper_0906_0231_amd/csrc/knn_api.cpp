@@ -295,17 +295,18 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         p.nq_pad = (int64_t)p.n_qtiles * tq;
         p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
         p.B = p.NB = p.NBp = 0;
-        // one workgroup of 8 waves per CU: 256 slots; slices of the reference range as for the fp32 kernel
+        // slices of the reference range as for the fp32 kernel
         int32_t smax = KNN_FIN_MAX / p.kcap;
         if (smax > p.n_rtiles) smax = p.n_rtiles;
         int32_t S = r_splits;
         if (S <= 0) {
-            const int32_t cap = (p.n_qtiles >= 256 && p.kcap > 32) ? 1 : (1024 + p.n_qtiles - 1) / p.n_qtiles;
+            const int32_t slots = 2048 / p.split_waves;          // workgroups the device holds at once          // workgroups the device holds at once
+            const int32_t cap = (p.n_qtiles >= slots && p.kcap > 32) ? 1 : (4 * slots + p.n_qtiles - 1) / p.n_qtiles;
             double best = -1.0;
             S = 1;
             for (int32_t s = 1; s <= cap && s <= smax; ++s) {
                 const int64_t wg = (int64_t)p.n_qtiles * s;
-                const double eff = (double)wg / (double)((wg + 255) / 256 * 256);
+                const double eff = (double)wg / (double)((wg + slots - 1) / slots * slots);
                 if (eff >= 0.9) { S = s; break; }
                 if (eff > best + 1e-9) { best = eff; S = s; }
             }
@@ -1261,6 +1262,25 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
     if (sink_bytes < (size_t)blocks * 256 * sizeof(float)) return KNN_EINVAL;
     e = launch_mfma_calibration(mfma_per_wave, blocks, sink, (hipStream_t)stream);
     if (e != hipSuccess) { set_error("mfma_only", e); return KNN_EDEVICE; }
+    if (total_waves) *total_waves = (int64_t)blocks * 4;
+    return KNN_OK;
+}
+
+knn_status_t knn_mfma_bf16_calibration(int64_t mfma_per_wave, int32_t waves_per_simd, int32_t chains, float *sink,
+                                       size_t sink_bytes, int64_t *total_waves, void *stream)
+{
+    g_last_error[0] = 0;
+    if (mfma_per_wave < 16 || mfma_per_wave % 16 != 0 || waves_per_simd < 1 || waves_per_simd > 4 ||
+        (chains != 2 && chains != 4) || !sink)
+        return KNN_EINVAL;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { set_error("hipDeviceGetAttribute", e); return KNN_EDEVICE; }
+    const int blocks = cus * waves_per_simd;                 // 4 waves each: one per SIMD
+    if (sink_bytes < (size_t)blocks * 256 * sizeof(float)) return KNN_EINVAL;
+    e = launch_mfma_bf16_calibration(mfma_per_wave, blocks, chains, sink, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("mfma_bf16_only", e); return KNN_EDEVICE; }
     if (total_waves) *total_waves = (int64_t)blocks * 4;
     return KNN_OK;
 }

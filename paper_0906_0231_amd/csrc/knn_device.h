@@ -210,6 +210,7 @@ struct SelectArgs {
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
+hipError_t launch_mfma_bf16_calibration(int64_t mfma_per_wave, int blocks, int chains, float *sink, hipStream_t stream);   // chains: 4 or 2
 hipError_t launch_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
                                    hipStream_t stream);   // sizes: multiples of 2048 floats
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream);
@@ -218,7 +219,7 @@ hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
 hipError_t launch_prep_split(const SplitPrepArgs &a, hipStream_t stream);
-hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream);   // dpad: multiple of 32, <= 256; n_qtiles in tiles of 32 * waves queries
+hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream);   // dpad: multiple of 32, <= 256; waves = 8; n_qtiles in tiles of 32 * waves queries
 hipError_t launch_zero_word(int32_t *word, hipStream_t stream);
 hipError_t launch_gather_rows(const GatherArgs &a, hipStream_t stream);
 hipError_t launch_tiles_qreg_subset(const TileArgs &a, hipStream_t stream);   // nq = capacity of the subset; S > 1 needs bound

@@ -72,6 +72,17 @@ hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sin
     return hipGetLastError();
 }
 
+hipError_t launch_mfma_bf16_calibration(int64_t mfma_per_wave, int blocks, int chains, float *sink, hipStream_t stream)
+{
+    if (chains == 4)
+        hipLaunchKernelGGL(mfma_bf16_only<4>, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);
+    else if (chains == 2)
+        hipLaunchKernelGGL(mfma_bf16_only<2>, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 
 // ---------------------------------------------------------------------------
 // launchers (called from the C ABI in knn_api.cpp)
@@ -274,9 +285,8 @@ static hipError_t launch_tiles_split_t(const TileArgs &a, hipStream_t stream)
 hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream)
 {
     const bool share = a.bound != nullptr && a.S > 1;
-    if (waves == 8) return share ? launch_tiles_split_t<8, true>(a, stream) : launch_tiles_split_t<8, false>(a, stream);
-    if (waves == 4) return share ? launch_tiles_split_t<4, true>(a, stream) : launch_tiles_split_t<4, false>(a, stream);
-    return hipErrorInvalidValue;
+    if (waves != 8) return hipErrorInvalidValue;
+    return share ? launch_tiles_split_t<8, true>(a, stream) : launch_tiles_split_t<8, false>(a, stream);
 }
 
 hipError_t launch_gather_rows(const GatherArgs &a, hipStream_t stream)

@@ -414,6 +414,10 @@ def test_mfma_calibration_runs():
     sink = torch.empty(64, dtype=torch.float32, device="cuda")
     st = lib.knn_mfma_calibration(1024, 2, sink.data_ptr(), sink.numel() * 4, None, None)
     assert st == api.KNN_EINVAL
+    from paper_0906_0231_amd import knn_mfma_bf16_calibration
+    for chains in (4, 2):
+        tf, ms = knn_mfma_bf16_calibration(1 << 14, 2, chains)
+        assert ms > 0 and 10.0 < tf < 3000.0
     from paper_0906_0231_amd import knn_valu_calibration
     tops, ms = knn_valu_calibration(1 << 14, 2)
     assert ms > 0 and 1.0 < tops < 100.0

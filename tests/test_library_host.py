@@ -22,7 +22,7 @@ def lib():
 def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "knn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(knn_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(knn_[a-z0-9_]+)\s*\(", text))
     assert declared == set(api.EXPORTS), declared ^ set(api.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -168,6 +168,16 @@ def test_calibration_rejects_bad_arguments_on_the_host(lib):
     assert call(1024, 0, one, 1 << 30, None, None) == api.KNN_EINVAL     # waves per SIMD out of range
     assert call(1024, 5, one, 1 << 30, None, None) == api.KNN_EINVAL
     assert call(1024, 2, None, 1 << 30, None, None) == api.KNN_EINVAL    # no sink
+
+
+def test_bf16_calibration_rejects_bad_arguments_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    call = lib.knn_mfma_bf16_calibration
+    assert call(0, 2, 4, one, 1 << 30, None, None) == api.KNN_EINVAL
+    assert call(24, 2, 4, one, 1 << 30, None, None) == api.KNN_EINVAL      # not a multiple of 16
+    assert call(1024, 5, 4, one, 1 << 30, None, None) == api.KNN_EINVAL    # waves per SIMD out of range
+    assert call(1024, 2, 3, one, 1 << 30, None, None) == api.KNN_EINVAL    # chains: 2 or 4
+    assert call(1024, 2, 4, None, 1 << 30, None, None) == api.KNN_EINVAL   # no sink
 
 
 def test_valu_calibration_rejects_bad_arguments_on_the_host(lib):
