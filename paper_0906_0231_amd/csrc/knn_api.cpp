@@ -406,6 +406,16 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         int64_t chunk = (tiles + 1023) / 1024;
         if (chunk < (p.mstream ? 2 : 4)) chunk = p.mstream ? 2 : 4;
         if (chunk > (p.mstream ? 32 : 64)) chunk = p.mstream ? 32 : 64;
+        if (!p.mstream && !p.blocked && tiles >= 8192) {
+            // whole matrix, d <= 256, enough tiles to go round: about six workgroups per slot (512 slots) even out the unequal
+            // sweeps of the triangle, but no fewer than 8 tiles each, which is what a workgroup's
+            // start (query operands into registers) wants to be spread over.  Measured, ms of the
+            // distance kernel with 1024 workgroups in all -> this rule: n = 20 000, d = 256: 1.13 ->
+            // 0.99; 40 000: 4.09 -> 3.62; 80 000: 14.19 -> 14.04; 65 536, d = 128: 6.41 -> 6.20.
+            chunk = (tiles + 3071) / 3072;
+            if (chunk < 8) chunk = 8;
+            if (chunk > 48) chunk = 48;
+        }
         p.chunk = (int32_t)chunk;
         p.n_chunks = (p.n_rt64 + p.chunk - 1) / p.chunk;
         int32_t skcap;
