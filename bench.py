@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--oracle-rows", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-select", action="store_true", help="skip the stand-alone selection timing")
+    ap.add_argument("--calibrate-contraction", action="store_true",
+                    help="instead of a workload: time the contraction-only kernel for both fp32 matrix instructions "
+                         "and 16 / 32 / 64 coordinates per LDS step (the evidence behind those two design choices)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain elementwise copy of 1 GiB (for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -80,6 +83,19 @@ def main() -> int:
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.calibrate_contraction:
+        from paper_0906_0231_amd import knn_contraction_calibration
+        rows = []
+        for shape, name in ((0, "v_mfma_f32_32x32x2_f32"), (1, "v_mfma_f32_16x16x4_f32")):
+            for dc in (16, 32, 64):
+                knn_contraction_calibration(shape, dc, 256)
+                tf, ms = knn_contraction_calibration(shape, dc, 4096)
+                rows.append({"instruction": name, "coordinates_per_step": dc, "tflops": tf, "ms": ms,
+                             "frac": tf / MFMA_F32_PEAK_TFLOPS, "kernel": f"contract_only<{shape}, {dc}>"})
+        print(json.dumps({"contraction_calibration": rows, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "workload": "2 workgroups per CU x 4096 tiles of 128 queries x 64 references x 256 coordinates"}))
+        return 0
 
     t0 = time.time()
     w = workloads.config(args.config, n=args.n)

@@ -275,6 +275,22 @@ knn_status_t knn_mfma_bf16_calibration(int64_t mfma_per_wave, int32_t waves_per_
                                        float *sink, size_t sink_bytes, int64_t *total_waves, void *stream);
 
 /*
+ * Calibration of two design choices of the fp32 tile kernels: their contraction and nothing
+ * else -- a workgroup of 4 waves, 32 queries per wave resident in registers (d = 256), 64
+ * reference rows staged through swizzled LDS `dc` coordinates per step (16, 32 or 64; the
+ * kernels use 32), no selection -- on v_mfma_f32_32x32x2_f32 (`shape` 0, the kernels' choice) or
+ * v_mfma_f32_16x16x4_f32 (`shape` 1).  Two workgroups per compute unit, each contracting
+ * `tiles_per_workgroup` tiles of 128 queries x 64 references x 256 coordinates (4 194 304 flop).
+ *   rows   DEVICE, 16-byte aligned, [64, 256] fp32: the reference rows every tile re-reads
+ *   sink   DEVICE, at least 4 * 256 * 2 * (compute units) bytes
+ *   workgroups  HOST pointer or NULL: receives the number launched
+ * Asynchronous on `stream`.  Errors as for knn_mfma_calibration.
+ */
+knn_status_t knn_contraction_calibration(int32_t shape, int32_t dc, int64_t tiles_per_workgroup,
+                                         const float *rows, float *sink, size_t sink_bytes,
+                                         int64_t *workgroups, void *stream);
+
+/*
  * The same for the vector ALUs: every wave issues `pairs_per_wave` times the fold kernel's
  * instruction pair (v_sub_f32 with a scalar operand, v_add_f32 with the |.| modifier) on 32
  * independent accumulators.  One launch executes waves * pairs_per_wave * 2 * 64 lane

@@ -36,7 +36,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ["knn_build", "knn_build_ex", "knn_search", "knn_search_ex", "knn_search_static", "knn_workspace_bytes",
            "knn_workspace_bytes_ex", "knn_workspace_bytes_min", "knn_plan", "knn_select",
            "knn_select_workspace_bytes",
-           "knn_mfma_calibration", "knn_mfma_bf16_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
+           "knn_mfma_calibration", "knn_mfma_bf16_calibration", "knn_contraction_calibration", "knn_valu_calibration", "knn_read_calibration", "knn_status_string",
            "knn_last_device_error"]
 
 
@@ -113,6 +113,8 @@ def load_library() -> ctypes.CDLL:
     lib.knn_mfma_calibration.argtypes = [i64, i32, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_mfma_bf16_calibration.restype = i32
     lib.knn_mfma_bf16_calibration.argtypes = [i64, i32, i32, vp, sz, ctypes.POINTER(i64), vp]
+    lib.knn_contraction_calibration.restype = i32
+    lib.knn_contraction_calibration.argtypes = [i32, i32, i64, vp, vp, sz, ctypes.POINTER(i64), vp]
     lib.knn_read_calibration.restype = i32
     lib.knn_read_calibration.argtypes = [vp, i64, i64, vp, sz, vp]
     lib.knn_valu_calibration.restype = i32
@@ -361,6 +363,30 @@ def knn_mfma_bf16_calibration(mfma_per_wave: int = 1 << 21, waves_per_simd: int 
         stop.synchronize()
         ms = start.elapsed_time(stop)
     return waves.value * mfma_per_wave * 32768.0 / (ms * 1e-3) / 1e12, ms
+
+
+def knn_contraction_calibration(shape: int = 0, dc: int = 32, tiles_per_workgroup: int = 2048,
+                                device=None) -> Tuple[float, float]:
+    """Time the library's contraction-only kernel (see knn_contraction_calibration in knn.h):
+    `shape` 0 = 32x32x2, 1 = 16x16x4 fp32 matrix instruction, `dc` coordinates per LDS step.
+    Returns (TFLOP/s, ms)."""
+    lib = load_library()
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    with torch.cuda.device(dev):
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        g = torch.Generator(device="cpu").manual_seed(7)
+        rows = torch.randn(64, 256, generator=g, dtype=torch.float32).to(dev)
+        sink = torch.empty(2 * cus * 256, dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream(dev)
+        wgs = ctypes.c_int64(0)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        _check(lib.knn_contraction_calibration(shape, dc, tiles_per_workgroup, rows.data_ptr(), sink.data_ptr(),
+                                               sink.numel() * 4, ctypes.byref(wgs), stream.cuda_stream))
+        stop.record(stream)
+        stop.synchronize()
+        ms = start.elapsed_time(stop)
+    return wgs.value * tiles_per_workgroup * 4194304.0 / (ms * 1e-3) / 1e12, ms
 
 
 def knn_valu_calibration(pairs_per_wave: int = 1 << 22, waves_per_simd: int = 4, device=None) -> Tuple[float, float]:

@@ -969,6 +969,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     else
         f.mode = o.rescore == 2 ? FIN_ADD_SQ : FIN_RESCORE_SQ;
     f.vec4 = (d % 4 == 0) ? 1 : 0;
+    if (f.mode == FIN_SELECT) f.Q = nullptr;       // the fold's values are the distances: reported from the keys
     f.krs = 0;
     f.all_kept = 0;
     f.unc_rows = nullptr;
@@ -1183,6 +1184,8 @@ knn_status_t knn_select(const float *A, int64_t m, int64_t n, int64_t lda, int32
     FinArgs f;
     memset(&f, 0, sizeof(f));
     f.lists = (const u64 *)workspace;
+    f.Q = A;                                       // FIN_SELECT with a matrix: values are read back from it,
+    f.nr = lda;                                    // row pitch nr
     f.idx = idx;
     f.dist = val;
     f.nq = m;
@@ -1273,6 +1276,25 @@ knn_status_t knn_mfma_calibration(int64_t mfma_per_wave, int32_t waves_per_simd,
     e = launch_mfma_calibration(mfma_per_wave, blocks, sink, (hipStream_t)stream);
     if (e != hipSuccess) { set_error("mfma_only", e); return KNN_EDEVICE; }
     if (total_waves) *total_waves = (int64_t)blocks * 4;
+    return KNN_OK;
+}
+
+knn_status_t knn_contraction_calibration(int32_t shape, int32_t dc, int64_t tiles_per_workgroup, const float *rows,
+                                         float *sink, size_t sink_bytes, int64_t *workgroups, void *stream)
+{
+    g_last_error[0] = 0;
+    if ((shape != 0 && shape != 1) || (dc != 16 && dc != 32 && dc != 64) || tiles_per_workgroup < 1 || !rows ||
+        ((uintptr_t)rows & 15) || !sink)
+        return KNN_EINVAL;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { set_error("hipDeviceGetAttribute", e); return KNN_EDEVICE; }
+    const int blocks = 2 * cus;                              // two workgroups of 4 waves per CU, as the tile kernels run
+    if (sink_bytes < (size_t)blocks * 256 * sizeof(float)) return KNN_EINVAL;
+    e = launch_contraction_calibration(shape, dc, tiles_per_workgroup, blocks, rows, sink, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error("contract_only", e); return KNN_EDEVICE; }
+    if (workgroups) *workgroups = blocks;
     return KNN_OK;
 }
 

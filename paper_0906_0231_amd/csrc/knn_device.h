@@ -153,7 +153,7 @@ enum { FIN_RESCORE_SQ = 0, FIN_RESCORE_COS = 1, FIN_ADD_SQ = 2, FIN_ADD_ONE = 3,
 
 struct FinArgs {
     const u64 *lists;
-    const float *Q;    // original query rows  [nq, d]   (re-score)
+    const float *Q;    // original query rows  [nq, d]   (re-score); FIN_SELECT: the matrix, row pitch nr, or null
     const float *R;    // original references  [nr, d]
     const float *sq;   // [nq] squared norms of the queries
     int32_t *idx;      // [nq, k]
@@ -210,6 +210,8 @@ struct SelectArgs {
 
 hipError_t launch_valu_calibration(int64_t pairs_per_wave, int blocks, float *sink, hipStream_t stream);
 hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sink, hipStream_t stream);
+hipError_t launch_contraction_calibration(int shape, int dc, int64_t tiles, int blocks, const float *rows, float *sink,
+                                          hipStream_t stream);   // shape 0 / 1, dc 16 / 32 / 64; rows: [64, 256] floats
 hipError_t launch_mfma_bf16_calibration(int64_t mfma_per_wave, int blocks, int chains, float *sink, hipStream_t stream);   // chains: 4 or 2
 hipError_t launch_read_calibration(const float *buf, int64_t n_floats, int64_t floats_per_wave, float *sink,
                                    hipStream_t stream);   // sizes: multiples of 2048 floats

@@ -12,6 +12,7 @@
 //   knn_fold_kernels.h   folds that are not inner products, on the vector ALUs; calibration
 //   knn_split_kernels.h  experiment: the fused kernel on bf16 matrix instructions, operands
 //                        split into two pieces, used as a filter with a proven error bound
+//   knn_calibration_kernels.h  the fp32 contraction alone, by matrix instruction and LDS step width
 //   this file            launchers called from the C ABI (knn_api.cpp)
 //
 // On the matrix path distances are evaluated in the expanded form
@@ -46,6 +47,7 @@ typedef __attribute__((address_space(3))) void *lds_ptr;
 #include "knn_matrix_kernel.h"
 #include "knn_fold_kernels.h"
 #include "knn_split_kernels.h"
+#include "knn_calibration_kernels.h"
 
 namespace knn {
 
@@ -70,6 +72,25 @@ hipError_t launch_mfma_calibration(int64_t mfma_per_wave, int blocks, float *sin
 {
     hipLaunchKernelGGL(mfma_only, dim3((unsigned)blocks), dim3(256), 0, stream, mfma_per_wave / 16, sink);
     return hipGetLastError();
+}
+
+hipError_t launch_contraction_calibration(int shape, int dc, int64_t tiles, int blocks, const float *rows, float *sink,
+                                          hipStream_t stream)
+{
+    dim3 grid((unsigned)blocks), block(256);
+#define KNN_CONTRACT_CASE(S, C)                                                                      \
+    if (shape == S && dc == C) {                                                                     \
+        hipLaunchKernelGGL((contract_only<S, C>), grid, block, 0, stream, rows, tiles, sink);        \
+        return hipGetLastError();                                                                    \
+    }
+    KNN_CONTRACT_CASE(0, 16)
+    KNN_CONTRACT_CASE(0, 32)
+    KNN_CONTRACT_CASE(0, 64)
+    KNN_CONTRACT_CASE(1, 16)
+    KNN_CONTRACT_CASE(1, 32)
+    KNN_CONTRACT_CASE(1, 64)
+#undef KNN_CONTRACT_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_mfma_bf16_calibration(int64_t mfma_per_wave, int blocks, int chains, float *sink, hipStream_t stream)

@@ -586,8 +586,11 @@ __global__ __launch_bounds__(64) void finalize_rows(FinArgs a)
     bitonic_sort_lds(outk, kpow, lane);
     for (int r = lane; r < a.k; r += 64) {
         u64 key = outk[r];
-        a.idx[q * a.k + r] = (int32_t)(uint32_t)key;
-        a.dist[q * a.k + r] = ord2f((uint32_t)(key >> 32));
+        const int32_t j = (int32_t)(uint32_t)key;
+        a.idx[q * a.k + r] = j;
+        // knn_select returns copies of the matrix entries: taken from the matrix itself, since a
+        // key does not keep the sign of a zero (keys of -0 and +0 tie, as the values do)
+        a.dist[q * a.k + r] = (a.mode == FIN_SELECT && a.Q != nullptr) ? a.Q[q * a.nr + j] : ord2f((uint32_t)(key >> 32));
     }
     if (a.krs > 0 && a.uncert != nullptr) {
         // Certificate of the filter.  The lists hold, by approximate value p~, the krs smallest of

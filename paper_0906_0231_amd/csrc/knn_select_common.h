@@ -22,7 +22,8 @@ __device__ __forceinline__ float ord2f(uint32_t o)
 }
 __device__ __forceinline__ u64 make_key(float p, int32_t j)
 {
-    return ((u64)f2ord(p) << 32) | (u64)(uint32_t)j;
+    // p + 0 turns -0 into +0: the two are the same distance and must tie (lower index first)
+    return ((u64)f2ord(p + 0.f) << 32) | (u64)(uint32_t)j;
 }
 __device__ __forceinline__ u64 readlane64(u64 v, int src)
 {

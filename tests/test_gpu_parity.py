@@ -418,6 +418,11 @@ def test_mfma_calibration_runs():
     for chains in (4, 2):
         tf, ms = knn_mfma_bf16_calibration(1 << 14, 2, chains)
         assert ms > 0 and 10.0 < tf < 3000.0
+    from paper_0906_0231_amd import knn_contraction_calibration
+    for shape in (0, 1):
+        for dc in (16, 32, 64):
+            tf, ms = knn_contraction_calibration(shape, dc, 64)
+            assert ms > 0 and 1.0 < tf < 200.0
     from paper_0906_0231_amd import knn_valu_calibration
     tops, ms = knn_valu_calibration(1 << 14, 2)
     assert ms > 0 and 1.0 < tops < 100.0

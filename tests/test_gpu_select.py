@@ -46,6 +46,16 @@ def test_select_ties_and_order():
     _check(A, 20)
 
 
+def test_select_signed_zeros():
+    """-0 and +0 are the same value: they tie (lower column first) and each is returned with its
+    own sign, as a copy of the entry."""
+    rng = np.random.default_rng(3)
+    A = rng.integers(0, 3, size=(30, 5000)).astype(np.float32)
+    A[rng.random(A.shape) < 0.3] *= -1.0           # -0.0 where the entry was 0
+    assert np.signbit(A[A == 0]).any() and (~np.signbit(A[A == 0])).any()
+    _check(A, 40)
+
+
 def test_select_strided_and_unaligned_rows():
     rng = np.random.default_rng(2)
     big = rng.standard_normal((50, 9001)).astype(np.float32)

@@ -180,6 +180,17 @@ def test_bf16_calibration_rejects_bad_arguments_on_the_host(lib):
     assert call(1024, 2, 4, None, 1 << 30, None, None) == api.KNN_EINVAL   # no sink
 
 
+def test_contraction_calibration_rejects_bad_arguments_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    call = lib.knn_contraction_calibration
+    assert call(2, 32, 10, one, one, 1 << 30, None, None) == api.KNN_EINVAL     # shape: 0 or 1
+    assert call(0, 48, 10, one, one, 1 << 30, None, None) == api.KNN_EINVAL     # dc: 16, 32 or 64
+    assert call(0, 32, 0, one, one, 1 << 30, None, None) == api.KNN_EINVAL      # no work
+    assert call(0, 32, 10, None, one, 1 << 30, None, None) == api.KNN_EINVAL    # no rows
+    assert call(0, 32, 10, ctypes.c_void_p(260), one, 1 << 30, None, None) == api.KNN_EINVAL   # misaligned
+    assert call(0, 32, 10, one, None, 1 << 30, None, None) == api.KNN_EINVAL    # no sink
+
+
 def test_valu_calibration_rejects_bad_arguments_on_the_host(lib):
     one = ctypes.c_void_p(256)
     call = lib.knn_valu_calibration
