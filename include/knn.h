@@ -93,7 +93,8 @@ typedef enum {
                                      bf16 pieces, three bf16 matrix products per pair pick K' > k
                                      candidates per query, which are then priced exactly; rows the
                                      error bound of the split cannot prove right are answered
-                                     again by the fp32 kernel (at most 4096 rows).
+                                     again by the fp32 kernel (at most 4096 rows).  Full square
+                                     unless knn_build is asked for symmetric = 1.
                                      KNN_SQEUCLIDEAN, d <= 256 and k <= 112 only */
 } knn_plan_t;
 

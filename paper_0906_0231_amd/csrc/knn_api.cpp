@@ -284,23 +284,29 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         // fused full square on the bf16 matrix instructions; the caller has checked metric, d and k
         p.split = true;
         p.split_waves = 8;
-        const int32_t tq = 32 * p.split_waves;
         p.dpad = (int32_t)align_up((size_t)d, 32);
         p.qreg = true;
-        p.tri = false;
         p.rcopy = true;
         p.kcap = split_list_capacity(k);
+        // each pair once (the tournament of knn_pairs_qreg, which works on tiles of 128 queries): on
+        // request only.  With products this cheap the mirror update costs what the halved products
+        // save: n = 2^20, d = 256: 1421 ms against 1341 ms for the full square; n = 65 536, d = 128,
+        // k = 32: 24.7 against 9.8 ms.
+        p.B = block_rows > 0 ? (int32_t)align_up((size_t)block_rows, KNN_TILE) : pair_block_rows(nr, p.kcap);
+        p.tri = self && symmetric == 1;
+        p.NB = (int32_t)((nr + p.B - 1) / p.B);
+        p.NBp = p.NB + (p.NB & 1);
+        const int32_t tq = p.tri ? KNN_TILE : 32 * p.split_waves;
         p.n_qtiles = (int32_t)((nq + tq - 1) / tq);
         p.n_rtiles = (int32_t)((nr + KNN_TILE - 1) / KNN_TILE);
         p.nq_pad = (int64_t)p.n_qtiles * tq;
         p.n_cpad = (int64_t)p.n_rtiles * KNN_TILE;
-        p.B = p.NB = p.NBp = 0;
         // slices of the reference range as for the fp32 kernel
         int32_t smax = KNN_FIN_MAX / p.kcap;
         if (smax > p.n_rtiles) smax = p.n_rtiles;
         int32_t S = r_splits;
         if (S <= 0) {
-            const int32_t slots = 2048 / p.split_waves;          // workgroups the device holds at once          // workgroups the device holds at once
+            const int32_t slots = 2048 / p.split_waves;          // workgroups the device holds at once
             const int32_t cap = (p.n_qtiles >= slots && p.kcap > 32) ? 1 : (4 * slots + p.n_qtiles - 1) / p.n_qtiles;
             double best = -1.0;
             S = 1;
@@ -313,6 +319,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         }
         if (S > smax) S = smax;
         if (S < 1) S = 1;
+        if (p.tri) S = 1;
         p.rt_per_split = (p.n_rtiles + S - 1) / S;
         p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
         p.nlists = p.S;
@@ -568,7 +575,7 @@ int32_t plan_launches(const Plan &p, int64_t nr)
 
 const char *plan_kernel(const Plan &p)
 {
-    if (p.split) return "knn_tiles_split";
+    if (p.split) return p.tri ? "knn_pairs_qreg" : "knn_tiles_split";
     if (p.fold) return p.matrix ? "knn_fold_dist" : "knn_fold";
     if (p.matrix) return p.mstream ? "knn_dist_stream" : "knn_dist_qreg";
     if (p.tri) return "knn_pairs_qreg";
@@ -885,17 +892,18 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         pa.n = nr;
         pa.dpad = p.dpad;
         pa.k = k;
+        if (p.split) pa.k = (int32_t)(nr - 1 < p.kcap ? nr - 1 : p.kcap);   // every entry of the lists live
         pa.kcap = p.kcap;
         pa.metric = (int32_t)metric;
         pa.B = p.B;
         pa.NB = p.NB;
         pa.NBp = p.NBp;
         pa.round = -1;
-        e = launch_pairs_qreg(pa, p.NB, stream);
+        e = launch_pairs_qreg(pa, p.NB, p.split, stream);
         if (e != hipSuccess) { set_error("knn_pairs_qreg(diagonal)", e); return KNN_EDEVICE; }
         for (int32_t r = 0; r + 1 < p.NBp; ++r) {
             pa.round = r;
-            e = launch_pairs_qreg(pa, p.NBp / 2, stream);
+            e = launch_pairs_qreg(pa, p.NBp / 2, p.split, stream);
             if (e != hipSuccess) { set_error("knn_pairs_qreg", e); return KNN_EDEVICE; }
         }
         launches = p.NBp;
@@ -997,6 +1005,9 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         f.cmax = (const float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256));
         f.err_a = 2.0 * (alpha + 1.02 * beta);
         f.err_b = beta + 1.0 / 8388608.0;
+        // each pair once: a value may have reached its list as (p~ - c_j) + c_q, two more roundings of
+        // numbers below 4 cmax
+        if (p.tri) f.err_b += 1.0 / 2097152.0;
         f.uncert = (int32_t *)(ws + p.off_fb_words);
         f.unc_rows = (int32_t *)(ws + p.off_fb_rows);
         f.unc_cap = p.fb_cap;

@@ -231,7 +231,7 @@ hipError_t launch_dist_qreg(const DistArgs &a, int n_qtiles, int mode, hipStream
 hipError_t launch_dist_stream(const DistArgs &a, int n_qtiles, int mode, hipStream_t stream);    // any dpad (multiple of KNN_DC); n_rt, chunk in tiles of 128 rows   // dpad: multiple of 32, <= 256
 hipError_t launch_finalize(const FinArgs &a, hipStream_t stream);
 hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t stream);
-hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream);
+hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, bool split, hipStream_t stream);   // split: operands are bf16 pieces (prep_split)
 
 }  // namespace knn
 #endif

@@ -36,6 +36,7 @@ namespace knn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));   // one operand of v_mfma_f32_32x32x16_bf16
 typedef __attribute__((address_space(3))) void *lds_ptr;
 
 }  // namespace knn
@@ -197,28 +198,34 @@ hipError_t launch_reduce_max(const float *c, int64_t n, float *out, hipStream_t 
     return hipGetLastError();
 }
 
-hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, hipStream_t stream)
+template <bool SPLIT>
+static hipError_t launch_pairs_qreg_t(const PairArgs &a, int blocks, hipStream_t stream)
 {
     dim3 grid((unsigned)blocks), block(256);
     switch (a.dpad) {
-    case 32: hipLaunchKernelGGL((knn_pairs_qreg<32, true>), grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL((knn_pairs_qreg<64, true>), grid, block, 0, stream, a); break;
-    case 96: hipLaunchKernelGGL((knn_pairs_qreg<96, true>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((knn_pairs_qreg<128, true>), grid, block, 0, stream, a); break;
-    case 160: hipLaunchKernelGGL((knn_pairs_qreg<160, true>), grid, block, 0, stream, a); break;
-    case 192: hipLaunchKernelGGL((knn_pairs_qreg<192, true>), grid, block, 0, stream, a); break;
-    case 224: hipLaunchKernelGGL((knn_pairs_qreg<224, true>), grid, block, 0, stream, a); break;
+    case 32: hipLaunchKernelGGL((knn_pairs_qreg<32, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((knn_pairs_qreg<64, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 96: hipLaunchKernelGGL((knn_pairs_qreg<96, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((knn_pairs_qreg<128, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 160: hipLaunchKernelGGL((knn_pairs_qreg<160, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 192: hipLaunchKernelGGL((knn_pairs_qreg<192, true, SPLIT>), grid, block, 0, stream, a); break;
+    case 224: hipLaunchKernelGGL((knn_pairs_qreg<224, true, SPLIT>), grid, block, 0, stream, a); break;
     case 256:
         // at the register limit: the mask scan costs the matrix loop spills that only pay
         // while candidates are frequent, i.e. for the smaller problems
         if (a.n < (1 << 19))
-            hipLaunchKernelGGL((knn_pairs_qreg<256, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((knn_pairs_qreg<256, true, SPLIT>), grid, block, 0, stream, a);
         else
-            hipLaunchKernelGGL((knn_pairs_qreg<256, false>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((knn_pairs_qreg<256, false, SPLIT>), grid, block, 0, stream, a);
         break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_pairs_qreg(const PairArgs &a, int blocks, bool split, hipStream_t stream)
+{
+    return split ? launch_pairs_qreg_t<true>(a, blocks, stream) : launch_pairs_qreg_t<false>(a, blocks, stream);
 }
 
 hipError_t launch_fold(const FoldArgs &a, hipStream_t stream)

@@ -64,7 +64,14 @@ __device__ __forceinline__ float mirror_T(u64 tkey, float cj, float cmax, float 
 // while thresholds are loose (small n, early rounds), but at d = 256 its few extra live
 // registers push spills into the matrix loop (+4.7 % at n = 2^20, -5 % at n = 2^18): the host
 // picks the walk for d = 256 and large n.
-template <int DPAD, bool MASKSCAN>
+// SPLIT: the split-precision experiment's form of the same schedule.  Operand rows are two bf16
+// pieces per value in the layout of prep_split -- per chunk of 32 coordinates the 16-byte units
+// h, 2+h hold the hi pieces and 4+h, 6+h the lo pieces that lane half h needs, i.e. the very
+// units (2s+h, s = 0..3) the fp32 loop reads -- so staging, query registers, accumulator layout
+// and everything the selection does are shared and only the matrix instructions differ: three
+// v_mfma_f32_32x32x16_bf16 per 16 coordinates and block.  The lists then hold a.k = K' entries
+// by approximate value, mirrored values included (see finalize_rows).
+template <int DPAD, bool MASKSCAN, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
 {
     constexpr int NK = DPAD / QG_DC;
@@ -359,16 +366,35 @@ __global__ __launch_bounds__(256, 2) void knn_pairs_qreg(PairArgs a)
                 }
             }
             const float *rb = &sm.r[buf][0];
+            if constexpr (SPLIT) {
 #pragma unroll
-            for (int s = 0; s < QG_NSLAB; ++s) {
-                const int u = ((2 * s + h) ^ sw) << 2;
-                f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
-                f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
-                const f32x4 qf = qreg[kc * QG_NSLAB + s];
+                for (int s = 0; s < 2; ++s) {
+                    const int uh = ((2 * s + h) ^ sw) << 2, ul = ((4 + 2 * s + h) ^ sw) << 2;
+                    const bf16x8 rh0 = __builtin_bit_cast(bf16x8, *(const f32x4 *)(rb + rbase0 + uh));
+                    const bf16x8 rh1 = __builtin_bit_cast(bf16x8, *(const f32x4 *)(rb + rbase1 + uh));
+                    const bf16x8 xh = __builtin_bit_cast(bf16x8, qreg[kc * QG_NSLAB + s]);
+                    const bf16x8 xl = __builtin_bit_cast(bf16x8, qreg[kc * QG_NSLAB + 2 + s]);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh0, xh, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh1, xh, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh0, xl, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh1, xl, acc1, 0, 0, 0);
+                    const bf16x8 rl0 = __builtin_bit_cast(bf16x8, *(const f32x4 *)(rb + rbase0 + ul));
+                    const bf16x8 rl1 = __builtin_bit_cast(bf16x8, *(const f32x4 *)(rb + rbase1 + ul));
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl0, xh, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl1, xh, acc1, 0, 0, 0);
+                }
+            } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+                for (int s = 0; s < QG_NSLAB; ++s) {
+                    const int u = ((2 * s + h) ^ sw) << 2;
+                    f32x4 rf0 = *(const f32x4 *)(rb + rbase0 + u);
+                    f32x4 rf1 = *(const f32x4 *)(rb + rbase1 + u);
+                    const f32x4 qf = qreg[kc * QG_NSLAB + s];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf0[c], qf[c], acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
+                    }
                 }
             }
             if (last) {

@@ -11,8 +11,6 @@
 
 namespace knn {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
 // fp32 -> bf16, round to nearest even (inputs are finite)
 __device__ __forceinline__ uint32_t bf16_rne(float x)
 {

@@ -40,7 +40,8 @@ def _build(X, k, **kw):
     unc = torch.full((1,), -1, dtype=torch.int32, device="cuda")
     res = knn_build(X.cuda(), k, variant=SPLIT, uncertified=unc, **kw)
     torch.cuda.synchronize()
-    assert res.plan.plan == SPLIT and res.plan.kernel == b"knn_tiles_split"
+    assert res.plan.plan == SPLIT
+    assert res.plan.kernel == (b"knn_pairs_qreg" if res.plan.symmetric else b"knn_tiles_split")
     n_unc = int(unc.item())
     assert 0 <= n_unc <= X.shape[0]
     return res, n_unc
@@ -60,10 +61,12 @@ def _build(X, k, **kw):
     (2100, 256, 12, 7),
     (4100, 200, 14, 0),
 ])
-def test_split_build_small(n, d, k, splits):
-    _say(f"  split build n={n} d={d} k={k} splits={splits}")
+@pytest.mark.parametrize("symmetric", [2, 1])
+def test_split_build_small(n, d, k, splits, symmetric):
+    _say(f"  split build n={n} d={d} k={k} splits={splits} symmetric={symmetric}")
     X = workloads.gaussian(n, d, seed=7000 + n + d)
-    res, n_unc = _build(X, k, r_splits=splits)
+    res, n_unc = _build(X, k, r_splits=splits, symmetric=symmetric)
+    assert res.plan.symmetric == (1 if symmetric == 1 else 0)
     _say(f"    rows left unproven: {n_unc} of {n}")
     _check(X.numpy(), X.numpy(), np.arange(n), k, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
@@ -80,18 +83,22 @@ def test_split_search_small(nq, nr, off):
     _check(Q.numpy(), R.numpy(), self_idx, k, res.idx.cpu().numpy(), res.dist.cpu().numpy())
 
 
-def test_split_exact_ties():
+@pytest.mark.parametrize("symmetric", [2, 1])
+def test_split_exact_ties(symmetric):
     """Small integers are exact in two bf16 pieces (16 bits), their products and sums exact in
     fp32: a lattice on a line, one-hot rows (every pair equidistant) and duplicated rows must give
-    the oracle's index lists bit for bit, ties to the lower index."""
+    the oracle's index lists bit for bit, ties to the lower index -- in the full square and with
+    each pair evaluated once (blocks of 128 rows: ties across block borders and rounds)."""
     n, k = 2000, 6
+    def build(X, k):
+        return _build(X, k, symmetric=symmetric, block_rows=128 if symmetric == 1 else 0)
     X = torch.arange(n, dtype=torch.float32)[:, None].contiguous()
-    res, n_unc = _build(X, k)
+    res, n_unc = build(X, k)
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     _check(X.numpy(), X.numpy(), np.arange(n), k, gi, gd, strict=True)
     assert gi[1000].tolist() == [999, 1001, 998, 1002, 997, 1003] and gd[1000].tolist() == [1, 1, 4, 4, 9, 9]
     E = torch.eye(256, dtype=torch.float32)
-    res, n_unc = _build(E, 17)
+    res, n_unc = build(E, 17)
     _say(f"    one-hot rows left unproven: {n_unc} of 256 (every pair ties: all 256 go through the second pass)")
     assert n_unc == 0
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
@@ -100,7 +107,7 @@ def test_split_exact_ties():
     assert np.all(gd == 2.0)
     base = workloads.gaussian(300, 20, seed=9)
     D = base.repeat_interleave(2, dim=0).contiguous()
-    res, n_unc = _build(D, 4)
+    res, n_unc = build(D, 4)
     gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
     assert np.array_equal(gi[:, 0], np.arange(600) ^ 1) and np.all(gd[:, 0] == 0.0)
     _check(D.numpy(), D.numpy(), np.arange(600), 4, gi, gd, atol=1e-30)
@@ -114,9 +121,9 @@ def test_split_second_pass_and_its_overflow():
     with 6000 rows 1904 are left over and counted."""
     rng = np.random.default_rng(21)
     base = rng.integers(0, 3, size=(50, 8)).astype(np.float32)
-    for n, left_some in ((3000, False), (6000, True)):
+    for n, left_some, symmetric in ((3000, False, 2), (6000, True, 2), (3000, False, 1)):
         X = torch.from_numpy(base[np.arange(n) % 50].copy())
-        res, left = _build(X, 9)
+        res, left = _build(X, 9, symmetric=symmetric)
         _say(f"    n={n}: rows left unproven after the second pass: {left}")
         assert left == (n - 4096 if left_some else 0)
         o_idx, o_dist, _ = oracle.build_knn(X.numpy(), 9)
@@ -153,15 +160,17 @@ def test_split_refuses_what_it_cannot_serve():
     assert e.value.status == api.KNN_EUNSUPPORTED
 
 
-@pytest.mark.parametrize("which,sample", [(1, 4096), (2, 1024), (3, 1024)])
-def test_split_configs_full(which, sample):
-    """Configs 1-3 at full size: the same oracle samples and the same comparator as the fp32
-    plans, no exemption beyond theirs (0 rows)."""
+@pytest.mark.parametrize("which,sample,symmetric", [(1, 4096, 2), (1, 4096, 1), (2, 1024, 2), (2, 1024, 1), (3, 1024, 0),
+                                                    (3, 1024, 1)])
+def test_split_configs_full(which, sample, symmetric):
+    """Configs 1-3 at full size, what the plan takes by itself (the full square) and each pair once: the same oracle samples and the same comparator as the fp32 plans, no exemption
+    beyond theirs (0 rows)."""
     w = workloads.config(which)
-    _say(f"  {w.name} split-precision")
+    _say(f"  {w.name} split-precision symmetric={symmetric}")
     unc = torch.full((1,), -1, dtype=torch.int32, device="cuda")
-    res = knn_build(w.R.cuda(), w.k, w.metric, variant=SPLIT, profile=True, uncertified=unc)
+    res = knn_build(w.R.cuda(), w.k, w.metric, variant=SPLIT, symmetric=symmetric, profile=True, uncertified=unc)
     torch.cuda.synchronize()
+    _say(f"    {res.plan}")
     _say(f"    gpu: {res.profile.ms_total:.1f} ms total, {res.profile.ms_main:.1f} ms main stage; "
          f"rows left unproven: {int(unc.item())} of {w.n}")
     assert int(unc.item()) == 0
