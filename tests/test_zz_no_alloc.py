@@ -80,3 +80,37 @@ def test_static_scratch_refuses_what_does_not_fit():
     assert st == api.KNN_ENOMEM
     assert lib.knn_search_static(None, 10, one, 100, 8, 3, 0, -1, one, one, None) == api.KNN_EINVAL
     assert lib.knn_search_static(one, 10, one, 100, 8, 101, 0, -1, one, one, None) == api.KNN_EINVAL
+
+
+def test_static_scratch_under_graph_capture():
+    """A caller that cannot allocate because it is being captured into a HIP graph: the call is
+    recorded once and replayed on new inputs, with the program's own eager work and
+    synchronisations between the replays; every replay must give what the eager call gives.
+    (The library enqueues kernels only -- no memset or copy nodes.)"""
+    assert torch.cuda.is_available(), "this test needs the GPU"
+    from paper_0906_0231_amd import knn_search, knn_search_static
+    nq, nr, d, k = 1000, 5000, 40, 12
+    R = workloads.mixture(nr, d, 6, seed=900).cuda()
+    Q = torch.empty((nq, d), dtype=torch.float32, device="cuda")
+    idx = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    dist = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+    Q.copy_(workloads.gaussian(nq, d, seed=901).cuda())
+    knn_search_static(Q, R, k, out=(idx, dist))            # first use of the array on this device: outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        knn_search_static(Q, R, k, out=(idx, dist))
+    for rep in range(4):
+        Qh = workloads.gaussian(nq, d, seed=910 + rep) * (1.0 + rep)
+        Q.copy_(Qh.cuda())
+        idx.fill_(-7)
+        dist.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        eager = knn_search(Q, R, k)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, eager.idx) and torch.equal(dist, eager.dist), f"replay {rep} differs from the eager call"
+        o_idx, o_dist, o_next = oracle.search(Qh.numpy(), R.cpu().numpy(), k, "sqeuclidean")
+        rep_ = compare.check(Qh.numpy(), R.cpu().numpy(), "sqeuclidean", o_idx, o_dist, o_next, idx.cpu().numpy(),
+                             dist.cpu().numpy(), rtol=RTOL)
+        assert rep_.ok, str(rep_)
