@@ -35,8 +35,9 @@
  *     distances to a query differ by less than that may be ranked either way;
  *     for data far from the origin (all rows sharing a large offset) that band
  *     is wide relative to the distances themselves: centre such data first
- *     (subtracting one vector from every row changes no distance).  The
- *     distances REPORTED are recomputed from the original rows in double.
+ *     (subtracting one vector from every row changes no distance), or set
+ *     knn_options_t.center, which does so inside the call.  The distances
+ *     REPORTED are recomputed from the original rows in double.
  *   - NaN or infinite input values: behaviour undefined.
  */
 #ifndef KNN_H_
@@ -125,7 +126,13 @@ typedef struct {
     int32_t block_rows; /* 0 = auto.  Fused symmetric schedule: rows per block (multiple of 128).
                            KNN_PLAN_TWO_PHASE with knn_build: rows per panel (multiple of 256),
                            and the panel walk is used whatever the size */
-    int32_t reserved;   /* must be 0 */
+    int32_t center;     /* 0 = off.  1 = KNN_SQEUCLIDEAN: subtract the references' column means (summed
+                           in double, once per call) from every query and reference row before
+                           the expanded form is taken -- no squared Euclidean distance changes,
+                           and the error of the expanded form (see the conventions above) then scales with
+                           the spread of the data, not with its distance from the origin.  Costs
+                           one more pass over R, a copy of R where the plan had none, and
+                           12 * dpad bytes of workspace.  Ignored for the other distances */
     knn_profile_t *profile; /* HOST pointer or NULL.  If set, the call brackets its kernels with
                            events, waits for them and fills this in */
     int32_t *uncertified;   /* DEVICE pointer or NULL; KNN_PLAN_SPLIT_BF16 only: receives the number

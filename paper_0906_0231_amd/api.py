@@ -51,7 +51,7 @@ class KnnProfile(ctypes.Structure):
 class KnnOptions(ctypes.Structure):
     _fields_ = [("symmetric", ctypes.c_int32), ("rescore", ctypes.c_int32),
                 ("r_splits", ctypes.c_int32), ("variant", ctypes.c_int32),
-                ("block_rows", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("block_rows", ctypes.c_int32), ("center", ctypes.c_int32),
                 ("profile", ctypes.POINTER(KnnProfile)), ("uncertified", ctypes.c_void_p)]
 
 
@@ -141,10 +141,11 @@ def _metric(metric) -> int:
 
 
 def _options(symmetric: int, rescore: int, r_splits: int, profile: bool, variant: int = 0,
-             block_rows: int = 0, uncertified: Optional[torch.Tensor] = None):
+             block_rows: int = 0, uncertified: Optional[torch.Tensor] = None, center: bool = False):
     opt = KnnOptions()
     opt.symmetric, opt.rescore, opt.r_splits, opt.variant = symmetric, rescore, r_splits, variant
     opt.block_rows = block_rows
+    opt.center = int(center)
     if uncertified is not None:
         if not uncertified.is_cuda or uncertified.dtype != torch.int32 or uncertified.numel() < 1:
             raise ValueError("uncertified must be an int32 tensor on the GPU")
@@ -167,11 +168,11 @@ def _dev_matrix(x: torch.Tensor, name: str) -> torch.Tensor:
 
 def knn_workspace_bytes(nq: int, nr: int, d: int, k: int, metric="sqeuclidean",
                         symmetric: bool = False, r_splits: int = 0, variant: int = 0,
-                        schedule: int = 0, block_rows: int = 0) -> int:
+                        schedule: int = 0, block_rows: int = 0, center: bool = False) -> int:
     """Workspace of knn_build (symmetric=True) or knn_search for the same options; `schedule`
     is the value of their `symmetric` option (0 auto, 1 triangle, 2 full square)."""
     lib = load_library()
-    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows)
+    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows, None, center)
     return int(lib.knn_workspace_bytes_ex(nq, nr, d, k, _metric(metric), int(symmetric),
                                           ctypes.byref(opt)))
 
@@ -184,11 +185,11 @@ def knn_workspace_bytes_min(nq: int, nr: int, d: int, k: int, metric="sqeuclidea
 
 def knn_plan(nq: int, nr: int, d: int, k: int, metric="sqeuclidean", symmetric: bool = False, *,
              workspace_bytes: int = NO_LIMIT, r_splits: int = 0, variant: int = 0, schedule: int = 0,
-             block_rows: int = 0) -> KnnPlanInfo:
+             block_rows: int = 0, center: bool = False) -> KnnPlanInfo:
     """What knn_build (symmetric=True) or knn_search with these sizes and options would do if
     given a workspace of `workspace_bytes`; see knn_plan in knn.h."""
     lib = load_library()
-    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows)
+    opt, _ = _options(schedule, 0, r_splits, False, variant, block_rows, None, center)
     info = KnnPlanInfo()
     _check(lib.knn_plan(nq, nr, d, k, _metric(metric), int(symmetric), ctypes.byref(opt), workspace_bytes,
                         ctypes.byref(info)))
@@ -228,9 +229,10 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
               rescore: int = 0, r_splits: int = 0, variant: int = 0, block_rows: int = 0,
               profile: bool = False, workspace: Optional[torch.Tensor] = None,
               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-              uncertified: Optional[torch.Tensor] = None) -> KnnResult:
+              uncertified: Optional[torch.Tensor] = None, center: bool = False) -> KnnResult:
     """All-pairs self kNN of the rows of X (device tensor); see knn_build in knn.h.
-    `uncertified`: int32 device tensor that receives knn_options_t.uncertified (plan 6 only)."""
+    `uncertified`: int32 device tensor that receives knn_options_t.uncertified (plan 6 only);
+    `center`: knn_options_t.center (squared Euclidean: column means subtracted first)."""
     lib = load_library()
     X = _dev_matrix(X, "X")
     n, d = X.shape
@@ -238,7 +240,7 @@ def knn_build(X: torch.Tensor, k: int, metric="sqeuclidean", *, symmetric: int =
         idx, dist = out if out is not None else (
             torch.empty((n, k), dtype=torch.int32, device=X.device),
             torch.empty((n, k), dtype=torch.float32, device=X.device))
-        opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows, uncertified)
+        opt, prof = _options(symmetric, rescore, r_splits, profile, variant, block_rows, uncertified, center)
         if workspace is None:
             workspace = _own_workspace(lib, opt, n, n, d, k, metric, 1, X.device)
         stream = torch.cuda.current_stream(X.device).cuda_stream
@@ -253,7 +255,7 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
                self_offset: int = -1, *, rescore: int = 0, r_splits: int = 0, variant: int = 0,
                profile: bool = False, workspace: Optional[torch.Tensor] = None,
                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-               uncertified: Optional[torch.Tensor] = None) -> KnnResult:
+               uncertified: Optional[torch.Tensor] = None, center: bool = False) -> KnnResult:
     """Neighbours of every row of Q among the rows of R; see knn_search in knn.h."""
     lib = load_library()
     Q = _dev_matrix(Q, "Q")
@@ -266,7 +268,7 @@ def knn_search(Q: torch.Tensor, R: torch.Tensor, k: int, metric="sqeuclidean",
         idx, dist = out if out is not None else (
             torch.empty((nq, k), dtype=torch.int32, device=Q.device),
             torch.empty((nq, k), dtype=torch.float32, device=Q.device))
-        opt, prof = _options(0, rescore, r_splits, profile, variant, 0, uncertified)
+        opt, prof = _options(0, rescore, r_splits, profile, variant, 0, uncertified, center)
         if workspace is None:
             workspace = _own_workspace(lib, opt, nq, nr, d, k, metric, 0, Q.device)
         stream = torch.cuda.current_stream(Q.device).cuda_stream

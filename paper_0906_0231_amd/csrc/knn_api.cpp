@@ -65,6 +65,8 @@ struct Plan {
     bool qreg;      // query tile resident in registers (knn_tiles_qreg)
     bool tri;       // symmetric schedule: rounds of disjoint block pairs (knn_pairs_qreg)
     bool fold;      // distance is not an inner product: vector-ALU kernel (knn_fold)
+    bool center;    // squared Euclidean: the references' column means are subtracted from every row first
+    size_t off_mu;  // ... [dpad] floats, then [dpad] doubles (the sums they come from)
     bool split;     // split-precision experiment: bf16 pieces, lists of kcap > k entries by approximate value
     int32_t split_waves; // ... waves per workgroup of knn_tiles_split (32 queries each)
     int32_t fb_cap, fb_S, fb_kcap, fb_rt_per_split;   // ... second pass (fp32 kernel) over the rows the filter could
@@ -171,10 +173,11 @@ bool two_phase_layout(Plan &p, int64_t cpad128, double matrix_bytes, bool msym, 
 
 // Sizes are assumed validated.  r_splits == 0 picks the slice count of the reference range
 // (see below), block_rows == 0 and symmetric == 0 take the cost model above.
-bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
-               int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, Plan &p)
+bool make_plan_core(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
+                    int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, bool center, Plan &p)
 {
     p.self = self;
+    p.center = center;
     p.split = false;
     p.split_waves = 0;
     p.fold = metric == KNN_L1 || metric == KNN_LINF;
@@ -355,8 +358,8 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         o += 256;
         p.off_fb_lists = o;
         o = align_up(o + (size_t)p.fb_S * p.fb_cap * p.fb_kcap * sizeof(u64), 256);
-        p.off_r32 = o;                             // fp32 reference rows padded to dpad, if d is ragged
-        if (p.dpad != d) o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
+        p.off_r32 = o;                             // fp32 reference rows padded to dpad (and centred), if d is ragged (or centred)
+        if (p.dpad != d || p.center) o = align_up(o + (size_t)nr * p.dpad * sizeof(float), 256);
         p.total = o;
         return true;
     }
@@ -430,7 +433,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
         if (p.blocked) p.S = 1;                   // lists are continued from block to block: one per row
         p.nlists = p.S;
         p.rt_per_split = 0;
-        p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
+        p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d || p.center;
         size_t o = 0;
         p.off_qp = o;
         o = align_up(o + (size_t)nq * p.dpad * sizeof(float), 256);
@@ -494,7 +497,7 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     p.rt_per_split = (p.n_rtiles + S - 1) / S;
     p.S = (p.n_rtiles + p.rt_per_split - 1) / p.rt_per_split;
     p.nlists = p.S;
-    p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d;
+    p.rcopy = metric != KNN_SQEUCLIDEAN || p.dpad != d || p.center;
 
     size_t o = 0;
     p.off_qp = o;
@@ -511,6 +514,19 @@ bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric
     o = align_up(o + (size_t)p.nlists * p.nq_pad * p.kcap * sizeof(u64), 256);
     p.total = o;
     return true;
+}
+
+// knn_options_t.center applies to the squared Euclidean distance only (a translation changes the
+// cosine and correlation distances, and the others do not go through the expanded form); the
+// means and their sums follow whatever the plan itself needs.
+bool make_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
+               int32_t r_splits, int32_t variant, int32_t symmetric, int32_t block_rows, int32_t center, Plan &p)
+{
+    const bool ok = make_plan_core(nq, nr, d, k, metric, self, r_splits, variant, symmetric, block_rows,
+                                   center == 1 && metric == KNN_SQEUCLIDEAN, p);
+    p.off_mu = p.total;
+    if (p.center) p.total += align_up((size_t)p.dpad * sizeof(float), 256) + align_up((size_t)p.dpad * sizeof(double), 256);
+    return ok;
 }
 
 knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric,
@@ -531,7 +547,7 @@ knn_status_t check_sizes(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metri
 knn_status_t check_options(const knn_options_t &o)
 {
     if (o.symmetric < 0 || o.symmetric > 2 || o.rescore < 0 || o.rescore > 2 || o.r_splits < 0 ||
-        o.block_rows < 0 || o.block_rows > (1 << 20) || o.reserved != 0)
+        o.block_rows < 0 || o.block_rows > (1 << 20) || o.center < 0 || o.center > 1)
         return KNN_EINVAL;
     if (o.variant != KNN_PLAN_AUTO && o.variant != KNN_PLAN_FUSED_STREAMING && o.variant != KNN_PLAN_FUSED &&
         o.variant != KNN_PLAN_TWO_PHASE && o.variant != KNN_PLAN_SPLIT_BF16)
@@ -554,10 +570,10 @@ knn_status_t check_split(const knn_options_t &o, int32_t d, int32_t k, knn_metri
 knn_status_t choose_plan(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t metric, bool self,
                          const knn_options_t &o, size_t budget, Plan &p)
 {
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, o.variant, o.symmetric, o.block_rows, o.center, p);
     if (p.total <= budget) return KNN_OK;
     if (o.variant != KNN_PLAN_AUTO || !p.matrix) return KNN_ENOMEM;
-    make_plan(nq, nr, d, k, metric, self, o.r_splits, KNN_PLAN_FUSED, o.symmetric, o.block_rows, p);
+    make_plan(nq, nr, d, k, metric, self, o.r_splits, KNN_PLAN_FUSED, o.symmetric, o.block_rows, o.center, p);
     return p.total <= budget ? KNN_OK : KNN_ENOMEM;
 }
 
@@ -811,20 +827,27 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
     ev.record(0, stream);
 
     // ---- prologue: norms and scaled copies ----
+    const float *mu = nullptr;
+    if (p.center) {
+        float *m = (float *)(ws + p.off_mu);
+        e = launch_col_mean(R, nr, d, p.dpad, (double *)(ws + p.off_mu + align_up((size_t)p.dpad * sizeof(float), 256)), m, stream);
+        if (e != hipSuccess) { set_error("col_mean", e); return KNN_EDEVICE; }
+        mu = m;
+    }
     if (p.split) {
-        SplitPrepArgs aq = {Q, nq, d, p.dpad, -2.f, (uint32_t *)qp, nullptr, 0, sq, bound};
+        SplitPrepArgs aq = {Q, nq, d, p.dpad, -2.f, (uint32_t *)qp, nullptr, 0, sq, bound, mu};
         e = launch_prep_split(aq, stream);
         if (e != hipSuccess) { set_error("prep_split(Q)", e); return KNN_EDEVICE; }
-        SplitPrepArgs ar = {R, nr, d, p.dpad, 1.f, (uint32_t *)rp, cr, p.n_cpad, nullptr, nullptr};
+        SplitPrepArgs ar = {R, nr, d, p.dpad, 1.f, (uint32_t *)rp, cr, p.n_cpad, nullptr, nullptr, mu};
         e = launch_prep_split(ar, stream);
         if (e != hipSuccess) { set_error("prep_split(R)", e); return KNN_EDEVICE; }
         e = launch_reduce_max(cr, nr, (float *)(ws + p.off_sq + align_up((size_t)nq * sizeof(float), 256)), stream);
         if (e != hipSuccess) { set_error("reduce_max", e); return KNN_EDEVICE; }
         e = launch_zero_word((int32_t *)(ws + p.off_fb_words), stream);
         if (e != hipSuccess) { set_error("zero_word", e); return KNN_EDEVICE; }
-        if (p.dpad != d) {
+        if (p.dpad != d || p.center) {
             // the second pass reads fp32 reference rows of dpad coordinates
-            PrepArgs a32 = {R, nr, d, p.dpad, (int32_t)KNN_SQEUCLIDEAN, nullptr, (float *)(ws + p.off_r32), nullptr, nr, nullptr, nullptr};
+            PrepArgs a32 = {R, nr, d, p.dpad, (int32_t)KNN_SQEUCLIDEAN, nullptr, (float *)(ws + p.off_r32), nullptr, nr, nullptr, nullptr, mu};
             e = launch_prep(a32, stream);
             if (e != hipSuccess) { set_error("prep_rows(R, fp32)", e); return KNN_EDEVICE; }
         }
@@ -836,14 +859,14 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         e = launch_pack(pk, stream);
         if (e != hipSuccess) { set_error("pack_tiles(R)", e); return KNN_EDEVICE; }
     } else if (self) {
-        PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq, bound};
+        PrepArgs a = {R, nr, d, p.dpad, (int32_t)metric, qp, rp, cr, p.n_cpad, sq, bound, mu};
         e = launch_prep(a, stream);
         if (e != hipSuccess) { set_error("prep_rows", e); return KNN_EDEVICE; }
     } else {
-        PrepArgs aq = {Q, nq, d, p.dpad, (int32_t)metric, qp, nullptr, nullptr, nq, sq, bound};
+        PrepArgs aq = {Q, nq, d, p.dpad, (int32_t)metric, qp, nullptr, nullptr, nq, sq, bound, mu};
         e = launch_prep(aq, stream);
         if (e != hipSuccess) { set_error("prep_rows(Q)", e); return KNN_EDEVICE; }
-        PrepArgs ar = {R, nr, d, p.dpad, (int32_t)metric, nullptr, rp, cr, p.n_cpad, nullptr, nullptr};
+        PrepArgs ar = {R, nr, d, p.dpad, (int32_t)metric, nullptr, rp, cr, p.n_cpad, nullptr, nullptr, mu};
         e = launch_prep(ar, stream);
         if (e != hipSuccess) { set_error("prep_rows(R)", e); return KNN_EDEVICE; }
     }
@@ -1029,6 +1052,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         g.b_out = (uint32_t *)(ws + p.off_fb_bound);
         g.n_out = words + 1;
         g.left_out = o.uncertified;
+        g.mu = p.center ? (const float *)(ws + p.off_mu) : nullptr;
         g.self_offset = self_offset;
         g.d = d;
         g.dpad = p.dpad;
@@ -1037,7 +1061,7 @@ knn_status_t run(const float *Q, int64_t nq, const float *R, int64_t nr, int32_t
         if (e != hipSuccess) { set_error("gather_rows", e); return KNN_EDEVICE; }
         TileArgs t;
         t.Qp = g.q_out;
-        t.Rp = p.dpad != d ? (const float *)(ws + p.off_r32) : R;
+        t.Rp = (p.dpad != d || p.center) ? (const float *)(ws + p.off_r32) : R;
         t.cR = cr;
         t.lists = (u64 *)(ws + p.off_fb_lists);
         t.bound = g.b_out;
@@ -1221,7 +1245,7 @@ size_t knn_workspace_bytes_ex(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_
     if (opt) o = *opt;
     if (check_options(o) != KNN_OK || check_split(o, d, k, metric) != KNN_OK) return 0;
     Plan p;
-    make_plan(nq, nr, d, k, metric, symmetric != 0, o.r_splits, o.variant, o.symmetric, o.block_rows, p);
+    make_plan(nq, nr, d, k, metric, symmetric != 0, o.r_splits, o.variant, o.symmetric, o.block_rows, o.center, p);
     return p.total;
 }
 

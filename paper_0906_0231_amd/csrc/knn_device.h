@@ -32,6 +32,7 @@ struct PrepArgs {
     int64_t n_cpad;
     float *s_out;      // [n] squared norms, or null
     uint32_t *b_out;   // [n] per-query bound shared by the slices of the reference range: set to "none yet", or null
+    const float *mu;   // [dpad] or null: subtracted from every row first (squared Euclidean only: no distance changes)
 };
 
 // split-precision experiment: a row as two bf16 pieces (see prep_split)
@@ -45,6 +46,7 @@ struct SplitPrepArgs {
     int64_t n_cpad;
     float *s_out;      // [n] |x|^2, or null
     uint32_t *b_out;   // [n] per-query bound shared by the slices: set to "none yet", or null
+    const float *mu;   // [dpad] or null: subtracted from every row before the scaling
 };
 
 struct TileArgs {
@@ -190,6 +192,7 @@ struct GatherArgs {
     uint32_t *b_out;        // [cap] shared bound of the slices: "none yet"
     int32_t *n_out;         // device word: min(*count, cap), the size of the subset
     int32_t *left_out;      // device word or null: rows still unproven after the second pass, max(0, *count - cap)
+    const float *mu;        // [dpad] or null: subtracted from the row before the scaling
     int64_t self_offset;
     int32_t d, dpad, cap;
 };
@@ -220,6 +223,7 @@ hipError_t launch_fold_dist(const FoldDistArgs &a, int mode, hipStream_t stream)
 hipError_t launch_pack(const PackArgs &a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_prep(const PrepArgs &a, hipStream_t stream);
+hipError_t launch_col_mean(const float *X, int64_t n, int32_t d, int32_t dpad, double *sums, float *mu, hipStream_t stream);   // mu[dpad] = column means, 0 beyond d
 hipError_t launch_prep_split(const SplitPrepArgs &a, hipStream_t stream);
 hipError_t launch_tiles_split(const TileArgs &a, int waves, hipStream_t stream);   // dpad: multiple of 32, <= 256; waves = 8; n_qtiles in tiles of 32 * waves queries
 hipError_t launch_zero_word(int32_t *word, hipStream_t stream);

@@ -120,6 +120,18 @@ hipError_t launch_prep(const PrepArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_col_mean(const float *X, int64_t n, int32_t d, int32_t dpad, double *sums, float *mu, hipStream_t stream)
+{
+    const unsigned cb = (unsigned)((dpad + 255) / 256);
+    int64_t ry = (n + 63) / 64;                    // at least 64 rows per thread
+    if (ry > 1024) ry = 1024;
+    if (ry < 1) ry = 1;
+    hipLaunchKernelGGL(col_zero, dim3(cb), dim3(256), 0, stream, sums, dpad);
+    hipLaunchKernelGGL(col_sum, dim3((unsigned)((d + 255) / 256), (unsigned)ry), dim3(256), 0, stream, X, n, d, sums);
+    hipLaunchKernelGGL(col_mean, dim3(cb), dim3(256), 0, stream, sums, n, d, dpad, mu);
+    return hipGetLastError();
+}
+
 hipError_t launch_tiles(const TileArgs &a, hipStream_t stream)
 {
     int64_t blocks = (int64_t)a.n_qtiles * a.S;

@@ -7,6 +7,33 @@
 namespace knn {
 
 // ---------------------------------------------------------------------------
+// Column means (knn_options_t.center): the vector subtracted from every row before the expanded
+// form is taken, so that data far from the origin does not lose its distances in the rounding of
+// |q|^2 + |r|^2 - 2 q.r.  col_sum: a thread per column, the rows dealt over blockIdx.y, partial
+// sums in double added atomically; col_mean: the division, zero beyond d.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void col_zero(double *sums, int32_t dpad)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < dpad) sums[c] = 0.0;
+}
+
+__global__ __launch_bounds__(256) void col_sum(const float *X, int64_t n, int32_t d, double *sums)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= d) return;
+    double s = 0.0;
+    for (int64_t r = blockIdx.y; r < n; r += gridDim.y) s += (double)X[r * d + c];
+    atomicAdd(&sums[c], s);
+}
+
+__global__ __launch_bounds__(256) void col_mean(const double *sums, int64_t n, int32_t d, int32_t dpad, float *mu)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < dpad) mu[c] = c < d ? (float)(sums[c] / (double)n) : 0.f;
+}
+
+// ---------------------------------------------------------------------------
 // prep_rows: one wave per row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
@@ -48,9 +75,14 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
             }
             continue;
         }
+        // centred value of coordinate c: the difference is exact in double and rounded once
+        auto val = [&](int c) __attribute__((always_inline)) {
+            if (root) return sqrtf(x[c]);
+            return a.mu != nullptr ? (float)((double)x[c] - (double)a.mu[c]) : x[c];
+        };
         float s = 0.f;
         for (int c = lane; c < a.d; c += 64) {
-            float v = root ? sqrtf(x[c]) : x[c];
+            float v = val(c);
             s = fmaf(v, v, s);
         }
         s = wave_sum(s);
@@ -67,11 +99,11 @@ __global__ __launch_bounds__(256) void prep_rows(PrepArgs a)
         }
         if (a.q_out) {
             float *o = a.q_out + row * (int64_t)a.dpad;
-            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? qscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? qscale * val(c) : 0.f;
         }
         if (a.r_out) {
             float *o = a.r_out + row * (int64_t)a.dpad;
-            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? rscale * (root ? sqrtf(x[c]) : x[c]) : 0.f;
+            for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? rscale * val(c) : 0.f;
         }
         if (lane == 0) {
             if (a.c_out) a.c_out[row] = cval;
@@ -636,7 +668,8 @@ __global__ __launch_bounds__(256) void gather_rows(GatherArgs a)
     const int32_t row = a.rows[i];
     const float *x = a.Q + (int64_t)row * a.d;
     float *o = a.q_out + (int64_t)i * a.dpad;
-    for (int c = lane; c < a.dpad; c += 64) o[c] = c < a.d ? -2.f * x[c] : 0.f;
+    for (int c = lane; c < a.dpad; c += 64)
+        o[c] = c < a.d ? -2.f * (a.mu != nullptr ? (float)((double)x[c] - (double)a.mu[c]) : x[c]) : 0.f;
     if (lane == 0) {
         a.self_out[i] = a.self_offset >= 0 ? (int32_t)(a.self_offset + row) : -1;
         a.b_out[i] = 0xffffffffu;

@@ -44,8 +44,11 @@ __global__ __launch_bounds__(256) void prep_split(SplitPrepArgs a)
         for (int wd = lane; wd < a.dpad; wd += 64) {
             const int chunk = wd >> 5, w = wd & 31;
             const int c0 = chunk * 32 + 2 * (w & 15);
-            const float v0 = c0 < a.d ? a.scale * x[c0] : 0.f;
-            const float v1 = c0 + 1 < a.d ? a.scale * x[c0 + 1] : 0.f;
+            auto val = [&](int c) __attribute__((always_inline)) {
+                return a.mu != nullptr ? (float)((double)x[c] - (double)a.mu[c]) : x[c];
+            };
+            const float v0 = c0 < a.d ? a.scale * val(c0) : 0.f;
+            const float v1 = c0 + 1 < a.d ? a.scale * val(c0 + 1) : 0.f;
             uint32_t b0 = bf16_rne(v0), b1 = bf16_rne(v1);
             if (w >= 16) {
                 b0 = bf16_rne(v0 - bf16_value(b0));
@@ -54,8 +57,12 @@ __global__ __launch_bounds__(256) void prep_split(SplitPrepArgs a)
             o[wd] = b0 | (b1 << 16);
         }
         if (a.c_out || a.s_out) {
+            // of the value the pieces are cut from (the centred one, rounded to fp32)
             double s = 0.0;
-            for (int c = lane; c < a.d; c += 64) s = fma((double)x[c], (double)x[c], s);
+            for (int c = lane; c < a.d; c += 64) {
+                const double v = a.mu != nullptr ? (double)(float)((double)x[c] - (double)a.mu[c]) : (double)x[c];
+                s = fma(v, v, s);
+            }
             s = wave_sum_f64(s);
             if (lane == 0) {
                 if (a.c_out) a.c_out[row] = (float)s;
@@ -80,8 +87,9 @@ __global__ __launch_bounds__(256) void prep_split(SplitPrepArgs a)
 // Measured at n = 2^20, d = 256: 1.30 s, of which the selection's rare path 10 %; with the matrix
 // instructions taken out the rest still takes 0.82 s, with the loads taken out 0.99 s.  None of
 // these changed that by more than +-2 %: two chunks per barrier, two query blocks per wave (half
-// the LDS reads), reference rows requested two steps ahead, fragment reads one sub-step ahead of
-// their matrix instructions with the barrier in mid-step.  Matrix instructions alone
+// the LDS reads), reference rows requested two steps ahead (straight into LDS, or through a second
+// register set), fragment reads one sub-step ahead of their matrix instructions with the barrier
+// in mid-step.  Matrix instructions alone
 // (mfma_bf16_only) sustain 1.89e15 flop/s on this device, 0.76 of the nominal peak.
 // ---------------------------------------------------------------------------
 template <int WAVES>

@@ -130,7 +130,7 @@ def test_options_are_validated_everywhere(lib):
     one, ws = ctypes.c_void_p(256), ctypes.c_void_p(4096)
     for field, value in (("variant", 2), ("variant", 5), ("variant", 7), ("variant", -1), ("symmetric", 3),
                          ("rescore", 3), ("r_splits", -1), ("block_rows", -5), ("block_rows", (1 << 20) + 1),
-                         ("reserved", 1)):
+                         ("center", 2), ("center", -1)):
         opt = api.KnnOptions()
         setattr(opt, field, value)
         assert lib.knn_workspace_bytes_ex(100, 100, 8, 3, 0, 1, ctypes.byref(opt)) == 0, (field, value)
