@@ -44,6 +44,7 @@ struct __attribute__((aligned(16))) DistSmem {
     float c[2][QG_TR];                            // by tile parity: read again in the epilogue
     float tr[4][32 * DT_PITCH];                   // per wave: its 32 x 64 tile, query-major
     float mn[4][32 * DB_PITCH];                   // per wave: the chunk minima of 8 tiles for its 32 rows
+    float u[2][QG_TR];                            // by tile parity: threshold + c of the tile's rows (test before the mirrored part)
 };
 
 template <int DPAD, int MODE>
@@ -112,7 +113,12 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
         *(f32x4 *)&sm.r[buf][st_off] = g0;
         *(f32x4 *)&sm.r[buf][st_off + 32 * QG_DC] = g1;
-        if (kc == 0 && tid < QG_TR) sm.c[tb][tid] = gc;
+        if (kc == 0 && tid < QG_TR) {
+            sm.c[tb][tid] = gc;
+            // u_j = tr_j + c_j, raised by more than the roundings of the two forms compared in the
+            // epilogue can amount to (thread j of the first wave holds both)
+            if (filt_m) sm.u[tb][tid] = (tr_next + gc) + 1e-6f * (fabsf(gc) + fabsf(tr_next));
+        }
     };
     const int rbase0 = ql * QG_DC, rbase1 = (32 + ql) * QG_DC;
     const int sw = qg_swz(ql);
@@ -126,9 +132,11 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
     auto step = [&](auto kc_tag, int rt) __attribute__((always_inline)) {
         constexpr int kc = decltype(kc_tag)::value;
         constexpr bool last = kc == NK - 1;
-        const bool more = !last || rt + 1 < rt1;
         if (kc == 0) tr_cur = tr_next;            // this tile's; the fetch below is the next tile's
-        if (more) issue(last ? rt + 1 : rt, last ? 0 : kc + 1);
+        // The chunk's last step fetches its own tile's first rows again instead of nothing: with
+        // fetch and deposit unconditional the compiler knows which loads are pending where, and
+        // puts no wait for them between the stores of the epilogue.
+        issue(last ? min(rt + 1, rt1 - 1) : rt, last ? 0 : kc + 1);
         __builtin_amdgcn_sched_barrier(0);
         if (kc == 0) {
 #pragma unroll
@@ -155,6 +163,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(rf1[c], qf[c], acc1, 0, 0, 0);
             }
         }
+        // Deposit the next step's rows before the epilogue issues its stores: the loads were
+        // issued before them, but how many stores follow is not known at compile time, so a wait
+        // placed after them would be a wait for every store of the tile to be acknowledged.
+        stash(buf ^ 1, last ? 0 : kc + 1, (rt + 1) & 1);
         if (last) {
             // register 4 gg + e of block t is reference row j0 + 32 t + 8 gg + 4 h + e
             const int64_t j0 = (int64_t)rt * QG_TR;
@@ -263,7 +275,35 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                         __builtin_amdgcn_sched_barrier(0);     // eight values at a time: no room for more at d = 256
                     }
                 };
-                if (filt_m) {                                 // (implies want_min)
+                // With thresholds, most tiles late in the walk hold nothing any row can use, and the
+                // loop below (128 vector instructions, 64 LDS writes, then the minima) is the largest
+                // part of the epilogue.  A cheaper test comes first.  Row j keeps a mirrored value
+                // only if (acc - c_j) + c_q <= tr_j; with u_j = tr_j + c_j, raised by more than the
+                // roundings of both forms can amount to, that needs acc - u_j + c_q <= ~0.  The u_j
+                // came into LDS with the tile's c_j, the lanes read the values of their registers'
+                // rows as they read c, and two chains of three-operand minima give the smallest
+                // acc - u over the lane's 32 values.  If no lane finds one at or below -c_q, no row can use its
+                // chunk: it is marked as such (a minimum of +inf: a row that has a threshold has a
+                // full list, and the selection then compares the minima with that threshold only)
+                // and nothing else is done.  No threshold yet (+inf), or rows past the end, never
+                // pass this test; queries past the end have nothing to keep.
+                bool none = false;
+                if (filt_m) {
+                    float ma = INF, mb = INF;
+#pragma unroll
+                    for (int gg = 0; gg < 4; ++gg) {
+                        f32x4 u0 = *(const f32x4 *)&sm.u[rt & 1][gg * 8 + h * 4];
+                        f32x4 u1 = *(const f32x4 *)&sm.u[rt & 1][32 + gg * 8 + h * 4];
+                        ma = fminf(ma, fminf(acc0[4 * gg + 0] - u0[0], acc0[4 * gg + 1] - u0[1]));
+                        mb = fminf(mb, fminf(acc0[4 * gg + 2] - u0[2], acc0[4 * gg + 3] - u0[3]));
+                        ma = fminf(ma, fminf(acc1[4 * gg + 0] - u1[0], acc1[4 * gg + 1] - u1[1]));
+                        mb = fminf(mb, fminf(acc1[4 * gg + 2] - u1[2], acc1[4 * gg + 3] - u1[3]));
+                    }
+                    none = __ballot(qin && !(fminf(ma, mb) + cq > 1e-6f * fabsf(cq))) == 0;
+                }
+                if (none) {
+                    a.Mm[(j0 + lane) * a.ldm + (qbase >> 5) + w] = INF;
+                } else if (filt_m) {                          // (implies want_min)
                     mirrored(std::false_type{}, std::true_type{});
                 } else {
 #pragma unroll
@@ -283,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                         }
                     }
                 }
-                if (want_min) {
+                if (want_min && !none) {
                     typedef float f32x2 __attribute__((ext_vector_type(2)));
                     const float *tr_row = &sm.tr[w][lane * DM_PITCH];
                     float m = INF;
@@ -315,7 +355,6 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                 }
             }
         }
-        if (more) stash(buf ^ 1, last ? 0 : kc + 1, (rt + 1) & 1);
         __syncthreads();
         buf ^= 1;
     };
@@ -376,14 +415,23 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
     }
     f32x4 gq[NPASS], gr[NPASS];
     float gc = 0.f;
+    // the reference rows' addresses are worked out once per tile (64-bit multiplies: a step has
+    // 2048 matrix-pipe cycles per wave, and vector instructions do not hide behind them)
+    const float *rsrc[NPASS];
     auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
+        if (kc == 0) {
+#pragma unroll
+            for (int i = 0; i < NPASS; ++i) {
+                int64_t row = min((int64_t)rt * TR + lrow + i * ROWS_PER_PASS, a.nr - 1);
+                rsrc[i] = a.Rp + row * a.ldr + lcol;
+            }
+            if (tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
+        }
 #pragma unroll
         for (int i = 0; i < NPASS; ++i) {
             gq[i] = *(const f32x4 *)(qsrc[i] + kc * DC);
-            int64_t row = min((int64_t)rt * TR + lrow + i * ROWS_PER_PASS, a.nr - 1);
-            gr[i] = *(const f32x4 *)(a.Rp + row * a.ldr + lcol + kc * DC);
+            gr[i] = *(const f32x4 *)(rsrc[i] + kc * DC);
         }
-        if (kc == 0 && tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
     };
     auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
 #pragma unroll
@@ -405,8 +453,11 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
         const int buf = it & 1;
         int nrt = rt, nkc = kc + 1;
         if (nkc == nk) { nkc = 0; nrt = rt + 1; }
-        const bool more = it + 1 < total;
-        if (more) issue(nrt, nkc);
+        // The last step fetches its own operands again instead of nothing: with the fetch and the
+        // deposit unconditional the compiler knows at the top of a step that no load is pending,
+        // and the address arithmetic does not wait for the stores of the tile before.
+        if (it + 1 == total) { nrt = rt; nkc = kc; }
+        issue(nrt, nkc);
 
         if (kc == 0) {
 #pragma unroll
@@ -437,6 +488,9 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
             }
         }
 
+        // deposit the next step's operands before the stores of the epilogue are issued: the
+        // wait for the loads then does not include them
+        stash(buf ^ 1, nkc, nrt & 1);
         if (kc == nk - 1) {
             // register 4 g + e of block t is reference row j0 + 32 t + 8 g + 4 h + e
             const int64_t j0 = (int64_t)rt * TR;
@@ -519,7 +573,6 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
             }
         }
 
-        if (more) stash(buf ^ 1, nkc, nrt & 1);
         __syncthreads();
         rt = nrt;
         kc = nkc;

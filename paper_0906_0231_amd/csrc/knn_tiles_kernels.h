@@ -88,14 +88,23 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
     f32x4 gq[NPASS], gr[NPASS];
     float gc = 0.f;
 
+    // the reference rows' addresses are worked out once per tile (64-bit multiplies: a step has
+    // 2048 matrix-pipe cycles per wave, and vector instructions do not hide behind them)
+    const float *rsrc[NPASS];
     auto issue = [&](int rt, int kc) __attribute__((always_inline)) {
+        if (kc == 0) {
+#pragma unroll
+            for (int i = 0; i < NPASS; ++i) {
+                int64_t row = min((int64_t)rt * TR + lrow + i * ROWS_PER_PASS, a.nr - 1);
+                rsrc[i] = a.Rp + row * a.ldr + lcol;
+            }
+            if (tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
+        }
 #pragma unroll
         for (int i = 0; i < NPASS; ++i) {
             gq[i] = *(const f32x4 *)(qsrc[i] + kc * DC);
-            int64_t row = min((int64_t)rt * TR + lrow + i * ROWS_PER_PASS, a.nr - 1);
-            gr[i] = *(const f32x4 *)(a.Rp + row * a.ldr + lcol + kc * DC);
+            gr[i] = *(const f32x4 *)(rsrc[i] + kc * DC);
         }
-        if (kc == 0 && tid < TR) gc = a.cR[(int64_t)rt * TR + tid];
     };
     auto stash = [&](int buf, int kc) __attribute__((always_inline)) {
 #pragma unroll
@@ -119,8 +128,10 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
         const int buf = it & 1;
         int nrt = rt, nkc = kc + 1;
         if (nkc == nk) { nkc = 0; nrt = rt + 1; }
-        const bool more = it + 1 < total;
-        if (more) issue(nrt, nkc);
+        // the last step fetches its own operands again instead of nothing: fetch and deposit are
+        // unconditional, so the compiler knows at the top of a step that no load is pending
+        if (it + 1 == total) { nrt = rt; nkc = kc; }
+        issue(nrt, nkc);
 
         if (kc == 0) {
             // accumulators start at c_j: register r of block t is reference row 32t + 8(r/4) + 4h + r%4
@@ -171,7 +182,7 @@ __global__ __launch_bounds__(256, 2) void knn_tiles(TileArgs a)
             __builtin_amdgcn_s_setprio(0);
         }
 
-        if (more) stash(buf ^ 1, nkc);
+        stash(buf ^ 1, nkc);
         __syncthreads();
         rt = nrt;
         kc = nkc;
