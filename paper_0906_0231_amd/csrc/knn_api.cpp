@@ -455,7 +455,7 @@ bool make_plan_core(int64_t nq, int64_t nr, int32_t d, int32_t k, knn_metric_t m
             o = align_up(o + (size_t)(p.blocked ? p.P : p.nq_pad) * p.ldm * sizeof(float), 256);
             p.off_M2 = o;
             if (p.blocked) o = align_up(o + (size_t)p.P * p.ldm * sizeof(float), 256);
-            p.tau = p.blocked && !p.mstream;
+            p.tau = p.blocked;
             p.off_tau = o;
             if (p.tau) o = align_up(o + (size_t)p.nq_pad * sizeof(float), 256);
         }

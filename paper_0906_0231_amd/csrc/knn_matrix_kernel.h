@@ -404,6 +404,12 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
     const int64_t selfj = a.self_offset >= 0 ? a.self_offset + myq : -1;
     const float cq = SYM ? a.cQ[min(myq, a.nq - 1)] : 0.f;
     const bool qin = myq < a.nq;
+    // Rows that already have a full list (a matrix walked block by block): what cannot enter the
+    // list is not stored, as in knn_dist_qreg.  tq: threshold of this lane's query row; trv[t]: of
+    // reference row 128 rt + 32 t + (lane & 31), fetched one step before the tile's last.
+    const float tq = a.tauQ != nullptr ? a.tauQ[min(myq, a.nq - 1)] : __builtin_inff();
+    const bool filt_m = SYM && a.tauR != nullptr && a.Mm != nullptr;
+    float trv[4] = {0.f, 0.f, 0.f, 0.f};
 
     const int lcol = (tid % LD_PER_ROW) * 4;
     const int lrow = tid / LD_PER_ROW;
@@ -431,6 +437,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
         for (int i = 0; i < NPASS; ++i) {
             gq[i] = *(const f32x4 *)(qsrc[i] + kc * DC);
             gr[i] = *(const f32x4 *)(rsrc[i] + kc * DC);
+        }
+        if (kc == nk - 1 && filt_m) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) trv[t] = a.tauR[min((int64_t)rt * TR + 32 * t + ql, a.nr - 1)];
         }
     };
     auto stash = [&](int buf, int kc, int tb) __attribute__((always_inline)) {
@@ -498,33 +508,33 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
             const bool own = a.self_offset >= 0 && j0 < a.self_offset + qbase + 32 * w + 32 &&
                              j0 + TR > a.self_offset + qbase + 32 * w;
             float *tw = &sm.tr[w][ql * DS_PITCH + 4 * h];
-            float dmin = INF;
             const int rr = lane >> 3, cc = (lane & 7) * 4;
             float *drow = a.D + (qbase + 32 * w + rr) * a.ldd + j0 + cc;
+            if (own) {                            // (a tile with a wave's own rows is never mirrored)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (j0 + 32 * t + 8 * (i >> 2) + 4 * h + (i & 3) == selfj) acc[t][i] = INF;
+            }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
+                // chunk 4 rt + t is block t; its 32 columns sit in the row's two lanes
+                float dmin = min16(acc[t]);
+                dmin = fminf(dmin, __shfl_xor(dmin, 32, 64));
+                // collected in LDS for 4 tiles (16 chunks, 64 bytes of the row), see knn_dist_qreg
+                if (a.M != nullptr && h == 0) sm.mn[w][ql * DB_PITCH + 4 * (rt & 3) + t] = dmin;
+                // bit r: row r of the wave's 32 can use this chunk (always, without thresholds)
+                const uint32_t keep = (uint32_t)__ballot(dmin <= tq);
+                if (keep) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4 v = {acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]};
-                    if (own) {
+                    for (int g = 0; g < 4; ++g)
+                        *(f32x4 *)(tw + 8 * g) = f32x4{acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]};
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (j0 + 32 * t + 8 * g + 4 * h + e == selfj) v[e] = INF;
+                    for (int i = 0; i < 4; ++i) {
+                        f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 8 * i) * DS_PITCH + cc];
+                        if ((keep >> (rr + 8 * i)) & 1u) *(f32x4 *)(drow + (int64_t)(8 * i) * a.ldd + 32 * t) = v;
                     }
-                    *(f32x4 *)(tw + 8 * g) = v;
-                    dmin = fminf(dmin, fminf(fminf(v[0], v[1]), fminf(v[2], v[3])));
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    f32x4 v = *(const f32x4 *)&sm.tr[w][(rr + 8 * i) * DS_PITCH + cc];
-                    *(f32x4 *)(drow + (int64_t)(8 * i) * a.ldd + 32 * t) = v;
-                }
-                // chunk 4 rt + t is block t; its 32 columns sit in the row's two lanes.  Collected
-                // in LDS for 4 tiles (16 chunks, 64 bytes of the row), see knn_dist_qreg
-                if (a.M != nullptr) {
-                    dmin = fminf(dmin, __shfl_xor(dmin, 32, 64));
-                    if (h == 0) sm.mn[w][ql * DB_PITCH + 4 * (rt & 3) + t] = dmin;
-                    dmin = INF;
                 }
             }
             if (a.M != nullptr && ((rt & 3) == 3 || rt + 1 == rt1)) {
@@ -548,6 +558,42 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
                 float *tm = &sm.tr[w][(4 * h) * DM_PITCH + ql];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
+                    if (filt_m) {
+                        // thresholds: the values go to LDS only, the minimum of each row decides
+                        // whether the row's 32 values are stored at all
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float m = (acc[t][4 * g + e] - cv[e]) + cq;
+                                tm[(8 * g + e) * DM_PITCH] = qin ? m : INF;
+                            }
+                        }
+                        typedef float f32x2 __attribute__((ext_vector_type(2)));
+                        const float *tr_row = &sm.tr[w][(lane & 31) * DM_PITCH];
+                        float m = INF;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            f32x2 v = *(const f32x2 *)(tr_row + 2 * i);
+                            m = fminf(m, fminf(v[0], v[1]));
+                        }
+                        if (lane < 32) a.Mm[(j0 + 32 * t + lane) * a.ldm + (qbase >> 5) + w] = m;
+                        // bit r: row j0 + 32 t + r can use the wave's chunk
+                        const uint32_t keep = (uint32_t)__ballot(m <= trv[t]);
+                        if (keep) {
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const float mv = (acc[t][4 * g + e] - cv[e]) + cq;
+                                    if ((keep >> (8 * g + 4 * h + e)) & 1u) (tbase + (int64_t)(32 * t + 8 * g + e) * a.ldd)[voff] = mv;
+                                }
+                            }
+                        }
+                        continue;
+                    }
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
