@@ -333,7 +333,8 @@ def test_ties_across_panels(kw):
     assert np.all(gd == 2.0)
 
 
-@pytest.mark.parametrize("n,d,k,panel", [(1536, 48, 8, 512), (2300, 256, 20, 768), (3000, 33, 3, 256)])
+@pytest.mark.parametrize("n,d,k,panel", [(1536, 48, 8, 512), (2300, 256, 20, 768), (3000, 33, 3, 256),
+                                         (1400, 300, 6, 512), (1200, 520, 40, 256)])   # d > 256: the streaming kernel filters alike
 def test_panel_pairs_when_the_neighbours_come_late(n, d, k, panel):
     """Walked by panel pairs, blocks that cannot change a row's list are not stored (a row's
     threshold after the panels it has seen filters what later blocks write).  Here the true
@@ -350,6 +351,29 @@ def test_panel_pairs_when_the_neighbours_come_late(n, d, k, panel):
     assert res.profile.two_phase == 2
     _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", res.idx.cpu().numpy(), res.dist.cpu().numpy())
     assert (res.idx[:third, 0].cpu() == torch.arange(third) + (n - third)).all()
+
+
+def test_ties_across_panels_streaming_kernel():
+    """d > 256, walked by panel pairs with thresholds: a lattice on a line embedded in 300
+    coordinates (every distance exact, every k-th distance tied between the two sides, values AT
+    the thresholds that filter the stores) and a set where every pair is equidistant."""
+    n, k = 1500, 6
+    X = torch.zeros((n, 300), dtype=torch.float32)
+    X[:, 17] = torch.arange(n, dtype=torch.float32)
+    res = knn_build(X.cuda(), k, variant=4, block_rows=512, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.two_phase == 2
+    gi, gd = res.idx.cpu().numpy(), res.dist.cpu().numpy()
+    _check_rows(X.numpy(), np.arange(n), 0, k, "sqeuclidean", gi, gd, strict=True)
+    assert gi[1024].tolist() == [1023, 1025, 1022, 1026, 1021, 1027]
+    E = torch.zeros((600, 600), dtype=torch.float32)
+    E[torch.arange(600), torch.arange(600)] = 1.0
+    res = knn_build(E.cuda(), 17, variant=4, block_rows=256)
+    torch.cuda.synchronize()
+    gi = res.idx.cpu().numpy()
+    for i in (0, 1, 255, 256, 257, 511, 512, 599):
+        assert gi[i].tolist() == [j for j in range(600) if j != i][:17]
+    _check_rows(E.numpy(), np.arange(600), 0, 17, "sqeuclidean", gi, res.dist.cpu().numpy(), strict=True)
 
 
 @pytest.mark.parametrize("variant", [1, 3, 4])
