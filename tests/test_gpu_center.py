@@ -81,6 +81,18 @@ def test_search_offset_data_with_self_offset():
     assert rep.ok, str(rep)
 
 
+def test_center_with_the_panel_walk():
+    """Walked by pairs of row panels (thresholds in the centred p-space on both sides)."""
+    n, d, k = 2600, 96, 12
+    X = _offset_rows(n, d, 77, offset=150.0)
+    res = knn_build(X.cuda(), k, variant=4, block_rows=768, center=True, profile=True)
+    torch.cuda.synchronize()
+    assert res.profile.two_phase == 2
+    rep = _report(X.numpy(), X.numpy(), np.arange(n), k, res.idx.cpu().numpy(), res.dist.cpu().numpy())
+    _say(f"    {rep}")
+    assert rep.ok, str(rep)
+
+
 def test_center_is_exact_on_a_shifted_lattice():
     """Integers 5000 .. 6999 on a line: the mean (5999.5) and every centred value are exact in
     fp32, so the answer is the lattice's, ties to the lower index, bit for bit."""
