@@ -335,21 +335,23 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                     a.Mm[(j0 + lane) * a.ldm + (qbase >> 5) + w] = m;
                     if (filt_m) {
                         // bit j: row j0 + j can use the wave's chunk; the stores wait for this
-                        const u64 keep = __ballot(m <= tr_cur);
-                        if (keep) {
-                            const uint32_t k0 = (uint32_t)(keep >> (4 * h)), k1 = (uint32_t)(keep >> (32 + 4 * h));
-#pragma unroll
-                            for (int gg = 0; gg < 4; ++gg) {
-                                f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
-                                f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    const float m0 = (acc0[4 * gg + e] - c0[e]) + cq;
-                                    const float m1 = (acc1[4 * gg + e] - c1[e]) + cq;
-                                    if ((k0 >> (8 * gg + e)) & 1u) (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
-                                    if ((k1 >> (8 * gg + e)) & 1u) (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
-                                }
+                        u64 keep = __ballot(m <= tr_cur);
+                        // The rows kept (one or two of the 64, typically) are copied out of the LDS
+                        // buffer, where each lies as 32 consecutive values: two rows per pass, one
+                        // per half of the wave.  (64 stores each under its own test of a mask bit
+                        // were 64 branches, which next to a wave that streams matrix instructions
+                        // cost far more than they look.)
+                        while (keep) {
+                            const int r0 = __builtin_ctzll(keep);
+                            keep &= keep - 1;
+                            int r1 = -1;
+                            if (keep) {
+                                r1 = __builtin_ctzll(keep);
+                                keep &= keep - 1;
                             }
+                            const int r = h == 0 ? r0 : r1;
+                            if (r >= 0)
+                                a.Dm[(j0 + r) * a.ldd + qbase + 32 * w + ql] = sm.tr[w][r * DM_PITCH + ql];
                         }
                     }
                 }
@@ -580,17 +582,19 @@ __global__ __launch_bounds__(256, 2) void knn_dist_stream(DistArgs a)
                         }
                         if (lane < 32) a.Mm[(j0 + 32 * t + lane) * a.ldm + (qbase >> 5) + w] = m;
                         // bit r: row j0 + 32 t + r can use the wave's chunk
-                        const uint32_t keep = (uint32_t)__ballot(m <= trv[t]);
-                        if (keep) {
-#pragma unroll
-                            for (int g = 0; g < 4; ++g) {
-                                f32x4 cv = *(const f32x4 *)&sm.c[rt & 1][t * 32 + g * 8 + h * 4];
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    const float mv = (acc[t][4 * g + e] - cv[e]) + cq;
-                                    if ((keep >> (8 * g + 4 * h + e)) & 1u) (tbase + (int64_t)(32 * t + 8 * g + e) * a.ldd)[voff] = mv;
-                                }
+                        uint32_t keep = (uint32_t)__ballot(m <= trv[t]);
+                        // the rows kept are copied out of the LDS buffer, two per pass (see knn_dist_qreg)
+                        while (keep) {
+                            const int r0 = __builtin_ctz(keep);
+                            keep &= keep - 1;
+                            int r1 = -1;
+                            if (keep) {
+                                r1 = __builtin_ctz(keep);
+                                keep &= keep - 1;
                             }
+                            const int r = h == 0 ? r0 : r1;
+                            if (r >= 0)
+                                a.Dm[(j0 + 32 * t + r) * a.ldd + qbase + 32 * w + ql] = sm.tr[w][r * DM_PITCH + ql];
                         }
                         continue;
                     }
