@@ -305,23 +305,10 @@ __global__ __launch_bounds__(256, 2) void knn_dist_qreg(DistArgs a)
                     a.Mm[(j0 + lane) * a.ldm + (qbase >> 5) + w] = INF;
                 } else if (filt_m) {                          // (implies want_min)
                     mirrored(std::false_type{}, std::true_type{});
+                } else if (want_min) {
+                    mirrored(std::true_type{}, std::true_type{});
                 } else {
-#pragma unroll
-                    for (int gg = 0; gg < 4; ++gg) {
-                        f32x4 c0 = *(const f32x4 *)&sm.c[rt & 1][gg * 8 + h * 4];
-                        f32x4 c1 = *(const f32x4 *)&sm.c[rt & 1][32 + gg * 8 + h * 4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float m0 = (acc0[4 * gg + e] - c0[e]) + cq;
-                            const float m1 = (acc1[4 * gg + e] - c1[e]) + cq;
-                            (tbase + (int64_t)(8 * gg + e) * a.ldd)[voff] = m0;
-                            (tbase + (int64_t)(32 + 8 * gg + e) * a.ldd)[voff] = m1;
-                            if (want_min) {
-                                tm[(8 * gg + e) * DM_PITCH] = m0;
-                                tm[(32 + 8 * gg + e) * DM_PITCH] = m1;
-                            }
-                        }
-                    }
+                    mirrored(std::true_type{}, std::false_type{});
                 }
                 if (want_min && !none) {
                     typedef float f32x2 __attribute__((ext_vector_type(2)));
