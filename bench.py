@@ -34,7 +34,7 @@ VALU_F32_PLAIN_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # holds the run.  Reported per launch next to `achieved`; null for anything not listed.
 OFFLINE_TRAFFIC_BYTES_PER_STEP = {
     ("c3_lowrank32_n1048576_d256_k10", "knn_dist_qreg"):
-        (3.674e11 + 4.867e11, "profiles/knn_two_phase_c3_panel_pairs.md"),
+        (3.326e11 + 4.864e11, "profiles/knn_two_phase_c3_panel_pairs.md"),
     ("c3_lowrank32_n1048576_d256_k10", "knn_pairs_qreg"):
         (5.83e12 + 3.01e10, "profiles/knn_c3_registers_resident.md"),
     ("c3_lowrank32_n1048576_d256_k10", "knn_tiles_qreg"):
